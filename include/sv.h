@@ -1,0 +1,172 @@
+/*
+ * sv.h - C ABI of the MI355X (gfx950) Speculative Verification hot path.
+ *
+ * One decode step of Speculative Verification (arxiv 2509.24328) over
+ * B sequences x k drafted positions x V vocabulary entries:
+ *
+ *   sv_row_stats        draft/companion indicators S and A      (Sec. 4.2; appendix defs of S and A)
+ *   sv_accept_estimate  binned estimate P^(T_i | S, A)           (appendix def. of the observed probability)
+ *   sv_select_length    verification length per sequence         (Sec. 5: E(N|gamma), goodput, batch greedy)
+ *   sv_verify_sample    speculative-sampling verification        (Sec. 4.2 last paragraph; Leviathan et al.)
+ *
+ * Conventions common to all calls
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
+ *     never allocates, frees or synchronises: each call only enqueues kernels
+ *     on `stream` (a hipStream_t passed as void*; NULL = the default stream)
+ *     and returns.  Results are valid once the stream has reached that point.
+ *   - Tensors are dense row-major with the vocabulary innermost.  Logits are
+ *     SV_F32 (IEEE binary32) or SV_BF16 (bfloat16, the upper 16 bits of a
+ *     binary32).  Base pointers need only element alignment; rows that start
+ *     on a 16-byte boundary (always the case when V*elem_size is a multiple of
+ *     16 and the base is 16-byte aligned) take the vector-load path.
+ *   - Return value: SV_OK or a negative SV_ERR_* for argument errors detected
+ *     on the host (nothing is enqueued then).  Data-dependent conditions (NaN
+ *     rows, token ids out of range, near-ties) are never errors: they set
+ *     SV_FLAG_* bits in the flags outputs.
+ *   - `ws` is caller-provided device scratch of at least
+ *     sv_workspace_bytes(B, k, V, dtype) bytes, 256-byte aligned, which may be
+ *     reused by the next call on the same stream.  Calls that share a
+ *     workspace must not overlap in time.
+ */
+#ifndef SV_H_
+#define SV_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef void* sv_stream_t;
+
+enum { SV_F32 = 0, SV_BF16 = 1 };
+enum { SV_BATCH_GREEDY = 0, SV_PER_SEQUENCE = 1 };
+
+enum {
+  SV_OK = 0,
+  SV_ERR_INVALID_ARG = -1, /* a size is out of range / inconsistent            */
+  SV_ERR_NULL = -2,        /* a required pointer is NULL                       */
+  SV_ERR_DTYPE = -3,       /* dtype is neither SV_F32 nor SV_BF16              */
+  SV_ERR_ALIGN = -4,       /* a pointer is not aligned to its element type     */
+  SV_ERR_WORKSPACE = -5,   /* ws is NULL, misaligned or smaller than required  */
+  SV_ERR_LAUNCH = -6,      /* the HIP runtime rejected a launch                */
+  SV_ERR_TOO_LARGE = -7    /* problem exceeds a documented library limit       */
+};
+
+/* Condition bits written to flags outputs. */
+enum {
+  SV_FLAG_BAD_ROW = 1,            /* a needed row holds NaN/+inf or no finite entry           */
+  SV_FLAG_NEAR_TIE = 2,           /* |u - min(1, ratio)| < 1e-6 at an evaluated position      */
+  SV_FLAG_RESIDUAL_FALLBACK = 4,  /* residual mass 0 / non-finite: token drawn from target    */
+  SV_FLAG_NEAR_CDF_EDGE = 8,      /* sampling threshold within 1e-6 * W of a CDF edge         */
+  SV_FLAG_BAD_TOKEN = 16          /* drafted token id outside [0, V)                          */
+};
+
+/* Largest B*k accepted by sv_select_length (keys are sorted in one workgroup). */
+#define SV_SELECT_MAX_KEYS 4096
+/* Largest k accepted by sv_verify_sample. */
+#define SV_MAX_K 64
+
+/* Human-readable name of a status code (static string, never NULL). */
+const char* sv_strerror(int status);
+
+/* Bytes of device scratch sv_row_stats / sv_verify_sample need for this shape
+ * (0 if the shape is invalid). */
+size_t sv_workspace_bytes(int B, int k, int V, int dtype);
+
+/*
+ * Indicators between draft and companion distributions (Sec. 4.2):
+ *   P_d = softmax(z_d[b,i,:]),  P_c = softmax(z_c[b,i,:])
+ *   S[b,i] = sum_v min(P_d(v), P_c(v))
+ *   A[b,i] = min(1, P_c(x[b,i]) / P_d(x[b,i]))          (1 when P_d(x) = 0)
+ * plus the row log-sum-exps and, optionally, KL(P_d || P_c).
+ *   z_d, z_c   [B,k,V] dtype        in
+ *   x          [B,k]   int32        in   drafted token ids
+ *   lse_d, lse_c, S, A [B,k] float  out  (NaN for bad rows; A NaN for bad tokens)
+ *   kl_or_null [B,k] float          out  optional
+ *   flags_or_null [B,k] uint32      out  optional, SV_FLAG_BAD_ROW / SV_FLAG_BAD_TOKEN
+ * B, k, V >= 1.  B = 0 is accepted and does nothing.
+ */
+int sv_row_stats(const void* z_d, const void* z_c, const int32_t* x,
+                 int B, int k, int V, int dtype,
+                 float* lse_d, float* lse_c, float* S, float* A,
+                 float* kl_or_null, uint32_t* flags_or_null,
+                 void* ws, size_t ws_bytes, sv_stream_t stream);
+
+/*
+ * Binned acceptance estimate (appendix definition of P(T_i | S, A)):
+ *   p_hat[j] = table[bin(S[j]; edges_s), bin(A[j]; edges_a)]
+ * Bins are half-open [e_i, e_{i+1}) over ascending edges, the top bin closed,
+ * values outside the edges clamped to the first/last bin, NaN -> bin 0.
+ *   S, A        [n] float           in
+ *   edges_s     [n_s+1] float, edges_a [n_a+1] float, table [n_s,n_a] float   in
+ *   p_hat       [n] float           out
+ *   edge_flag_or_null [n] uint8     out  1 when S or A is NaN or lies within 1e-5
+ *                                        (float32 |v - e| <= 1e-5f) of an interior edge
+ * n >= 0, n_s, n_a >= 1.
+ */
+int sv_accept_estimate(const float* S, const float* A, int n,
+                       const float* edges_s, int n_s,
+                       const float* edges_a, int n_a,
+                       const float* table,
+                       float* p_hat, uint8_t* edge_flag_or_null, sv_stream_t stream);
+
+/*
+ * Verification length per sequence (Sec. 5).  With c[b,j] = prod_{i<=j} p_hat[b,i]
+ * (estimates clamped to [0,1], NaN -> 0; float64, left to right) the expected
+ * accepted length of verifying gamma tokens of b is sum_{j<gamma} c[b,j].
+ * SV_BATCH_GREEDY: order all (b,j) by c descending (ties: b, then j, ascending);
+ * E_M = sum of the first M keys, accumulated in that order in float64;
+ * estimated goodput G_M = E_M / latency[M], G_0 = 0; M* = the largest M such
+ * that G_1 < G_2 < ... < G_M* keeps strictly improving from G_0 (first peak);
+ * gamma[b] = number of selected keys of sequence b.
+ * SV_PER_SEQUENCE: the same search on every sequence alone with latency[0..k].
+ *   p_hat   [B,k] float     in
+ *   latency [n_latency] float, > 0   in   n_latency >= B*k+1 (batch) or k+1 (per sequence)
+ *   gamma   [B] int32       out  0..k
+ *   t_offsets [B+1] int32   out  exclusive scan of gamma[b] + 1
+ *   total_M [1] int32       out  sum_b gamma[b]
+ * Limit: B*k <= SV_SELECT_MAX_KEYS, else SV_ERR_TOO_LARGE.
+ */
+int sv_select_length(const float* p_hat, int B, int k,
+                     const float* latency, int n_latency, int mode,
+                     int32_t* gamma, int32_t* t_offsets, int32_t* total_M,
+                     sv_stream_t stream);
+
+/*
+ * Speculative-sampling verification of the first gamma[b] drafted tokens of
+ * each sequence (Sec. 4.2, last paragraph; the rule itself is Leviathan et al.'s):
+ * for i < gamma[b] accept x[b,i] iff u_i < p_t(x)/p_d(x); n = leading accepts;
+ * then draw one token at position n: from the normalised residual
+ * max(0, p_t - p_d) if n < gamma[b], else from the target distribution of
+ * position gamma[b] (bonus token / position the target generates itself).
+ * Draws are inverse-CDF over ascending token id: the smallest v whose
+ * inclusive cumulative weight exceeds u' * W.
+ * Uniforms: Philox-4x32-10, key = (seed lo, seed hi), counter = (i, b, 0, step);
+ * word 0 -> u_i, word 1 -> u' for sampling at position i; value ((w>>8)+0.5)*2^-24.
+ *   z_t   dense [B,k+1,V] when t_offsets_or_null is NULL, else packed
+ *         [n_t_rows,V] with the target row of (b,i), i <= gamma[b], at row t_offsets[b]+i
+ *   t_offsets_or_null [B+1] int32   in   optional
+ *   n_t_rows          rows in packed z_t (ignored when dense); rows addressed
+ *                     beyond it are treated as bad rows, never read
+ *   z_d   [B,k,V] dtype, x [B,k] int32                       in
+ *   gamma_or_null [B] int32          in   optional (NULL: gamma[b] = k); clamped to 0..k
+ *   out_tokens [B,k+1] int32         out  accepted tokens, the drawn token, then -1
+ *   n_accept   [B] int32             out
+ *   flags      [B] uint32            out  SV_FLAG_* bits
+ *   ratio_or_null [B,k] float        out  optional: p_t/p_d at evaluated positions, NaN elsewhere
+ * Limits: k <= SV_MAX_K.
+ */
+int sv_verify_sample(const void* z_t, const int32_t* t_offsets_or_null, int n_t_rows,
+                     const void* z_d, const int32_t* x, const int32_t* gamma_or_null,
+                     int B, int k, int V, int dtype,
+                     uint64_t seed, uint32_t step,
+                     int32_t* out_tokens, int32_t* n_accept, uint32_t* flags,
+                     float* ratio_or_null,
+                     void* ws, size_t ws_bytes, sv_stream_t stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SV_H_ */

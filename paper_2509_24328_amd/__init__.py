@@ -1,0 +1,9 @@
+"""MI355X-native hot path of Speculative Verification (arxiv 2509.24328).
+
+`binding` exposes the C ABI of include/sv.h one to one; `step` chains the four
+calls of one decode step on a stream.
+"""
+from . import binding  # noqa: F401  (fails loudly when libsv.so is missing)
+from .binding import (SV_BATCH_GREEDY, SV_BF16, SV_F32, SV_PER_SEQUENCE, SvError,  # noqa: F401
+                      alloc_workspace, sv_accept_estimate, sv_row_stats, sv_select_length,
+                      sv_strerror, sv_verify_sample, sv_workspace_bytes)

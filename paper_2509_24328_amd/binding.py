@@ -1,0 +1,117 @@
+"""Thin ctypes binding over the C ABI in include/sv.h.
+
+Argument marshalling only: every step of the path runs in the HIP kernels of
+libsv.so.  PyTorch provides device memory and the stream.  There is no CPU
+fallback: if the library has not been built, importing this module fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsv.so")
+
+SV_F32, SV_BF16 = 0, 1
+SV_BATCH_GREEDY, SV_PER_SEQUENCE = 0, 1
+SV_OK = 0
+SV_ERR_INVALID_ARG, SV_ERR_NULL, SV_ERR_DTYPE, SV_ERR_ALIGN = -1, -2, -3, -4
+SV_ERR_WORKSPACE, SV_ERR_LAUNCH, SV_ERR_TOO_LARGE = -5, -6, -7
+FLAG_BAD_ROW, FLAG_NEAR_TIE, FLAG_RESIDUAL_FALLBACK, FLAG_NEAR_CDF_EDGE, FLAG_BAD_TOKEN = 1, 2, 4, 8, 16
+SV_SELECT_MAX_KEYS = 4096
+SV_MAX_K = 64
+
+EXPORTS = ("sv_strerror", "sv_workspace_bytes", "sv_row_stats", "sv_accept_estimate",
+           "sv_select_length", "sv_verify_sample")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2509_24328_amd.build` "
+                      "(or __graft_entry__.build()); there is no fallback path")
+
+lib = ctypes.CDLL(LIB_PATH)
+_vp, _i, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+lib.sv_strerror.restype = ctypes.c_char_p
+lib.sv_strerror.argtypes = [_i]
+lib.sv_workspace_bytes.restype = _sz
+lib.sv_workspace_bytes.argtypes = [_i, _i, _i, _i]
+lib.sv_row_stats.restype = _i
+lib.sv_row_stats.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+lib.sv_accept_estimate.restype = _i
+lib.sv_accept_estimate.argtypes = [_vp, _vp, _i, _vp, _i, _vp, _i, _vp, _vp, _vp, _vp]
+lib.sv_select_length.restype = _i
+lib.sv_select_length.argtypes = [_vp, _i, _i, _vp, _i, _i, _vp, _vp, _vp, _vp]
+lib.sv_verify_sample.restype = _i
+lib.sv_verify_sample.argtypes = [_vp, _vp, _i, _vp, _vp, _vp, _i, _i, _i, _i, ctypes.c_uint64,
+                                 ctypes.c_uint32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+
+
+class SvError(RuntimeError):
+    def __init__(self, status):
+        self.status = status
+        super().__init__(lib.sv_strerror(status).decode())
+
+
+def _check(status):
+    if status != SV_OK:
+        raise SvError(status)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _dtype_tag(t):
+    if t.dtype == torch.float32:
+        return SV_F32
+    if t.dtype == torch.bfloat16:
+        return SV_BF16
+    raise SvError(SV_ERR_DTYPE)
+
+
+def sv_strerror(status):
+    return lib.sv_strerror(status).decode()
+
+
+def sv_workspace_bytes(B, k, V, dtype):
+    return int(lib.sv_workspace_bytes(B, k, V, dtype))
+
+
+def alloc_workspace(B, k, V, dtype, device="cuda"):
+    n = max(sv_workspace_bytes(B, k, V, dtype), 256)
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def sv_row_stats(z_d, z_c, x, lse_d, lse_c, S, A, kl=None, flags=None, ws=None, stream=None):
+    B, k, V = z_d.shape
+    _check(lib.sv_row_stats(_ptr(z_d), _ptr(z_c), _ptr(x), B, k, V, _dtype_tag(z_d),
+                            _ptr(lse_d), _ptr(lse_c), _ptr(S), _ptr(A), _ptr(kl), _ptr(flags),
+                            _ptr(ws), 0 if ws is None else ws.numel(), _stream(stream)))
+
+
+def sv_accept_estimate(S, A, edges_s, edges_a, table, p_hat, edge_flag=None, stream=None):
+    _check(lib.sv_accept_estimate(_ptr(S), _ptr(A), S.numel(), _ptr(edges_s), edges_s.numel() - 1,
+                                  _ptr(edges_a), edges_a.numel() - 1, _ptr(table), _ptr(p_hat),
+                                  _ptr(edge_flag), _stream(stream)))
+
+
+def sv_select_length(p_hat, latency, mode, gamma, t_offsets, total_M, stream=None):
+    B, k = p_hat.shape
+    _check(lib.sv_select_length(_ptr(p_hat), B, k, _ptr(latency), latency.numel(), mode,
+                                _ptr(gamma), _ptr(t_offsets), _ptr(total_M), _stream(stream)))
+
+
+def sv_verify_sample(z_t, t_offsets, z_d, x, gamma, seed, step, out_tokens, n_accept, flags,
+                     ratio=None, ws=None, stream=None):
+    B, k, V = z_d.shape
+    n_t_rows = z_t.shape[0] if t_offsets is not None else 0
+    _check(lib.sv_verify_sample(_ptr(z_t), _ptr(t_offsets), n_t_rows, _ptr(z_d), _ptr(x), _ptr(gamma),
+                                B, k, V, _dtype_tag(z_d), seed, step, _ptr(out_tokens), _ptr(n_accept),
+                                _ptr(flags), _ptr(ratio), _ptr(ws), 0 if ws is None else ws.numel(),
+                                _stream(stream)))

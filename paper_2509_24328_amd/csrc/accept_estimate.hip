@@ -1,0 +1,56 @@
+// sv_accept_estimate: lookup of the binned acceptance estimate P^(T_i | S, A)
+// (appendix definition of the observed probability in the SV paper).
+// One lane per (sequence, position); the profile table and its edges are a few
+// hundred floats and stay in cache.  Launch-latency bound.
+#include "sv_device.hpp"
+#include "sv_host.hpp"
+
+namespace sv {
+
+// Half-open bins [e_j, e_{j+1}), top bin closed, outside values clamped, NaN -> 0.
+__device__ __forceinline__ int bin_of(float v, const float* edges, int n) {
+  if (isnan(v)) return 0;
+  int idx = 0;
+  for (int j = 1; j <= n; ++j)
+    if (edges[j] <= v) idx = j;
+  return min(idx, n - 1);
+}
+
+// |v - e_j| <= 1e-5 in fp32 for an interior edge, or v is NaN.
+__device__ __forceinline__ bool near_edge(float v, const float* edges, int n) {
+  if (isnan(v)) return true;
+  for (int j = 1; j < n; ++j)
+    if (fabsf(__fsub_rn(v, edges[j])) <= 1e-5f) return true;
+  return false;
+}
+
+__global__ void accept_estimate_kernel(const float* S, const float* A, int n,
+                                       const float* edges_s, int n_s,
+                                       const float* edges_a, int n_a,
+                                       const float* table, float* p_hat, uint8_t* edge_flag) {
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= n) return;
+  const float s = S[j], a = A[j];
+  p_hat[j] = table[bin_of(s, edges_s, n_s) * n_a + bin_of(a, edges_a, n_a)];
+  if (edge_flag) edge_flag[j] = (near_edge(s, edges_s, n_s) || near_edge(a, edges_a, n_a)) ? 1 : 0;
+}
+
+}  // namespace sv
+
+extern "C" int sv_accept_estimate(const float* S, const float* A, int n,
+                                  const float* edges_s, int n_s, const float* edges_a, int n_a,
+                                  const float* table, float* p_hat, uint8_t* edge_flag_or_null,
+                                  sv_stream_t stream) {
+  using namespace sv;
+  SV_REQUIRE(n >= 0 && n_s >= 1 && n_a >= 1, SV_ERR_INVALID_ARG);
+  if (n == 0) return SV_OK;
+  SV_REQUIRE(S && A && edges_s && edges_a && table && p_hat, SV_ERR_NULL);
+  SV_REQUIRE(is_aligned(S, 4) && is_aligned(A, 4) && is_aligned(edges_s, 4) && is_aligned(edges_a, 4) &&
+                 is_aligned(table, 4) && is_aligned(p_hat, 4),
+             SV_ERR_ALIGN);
+  const int threads = 256;
+  hipLaunchKernelGGL(accept_estimate_kernel, dim3((n + threads - 1) / threads), dim3(threads), 0,
+                     as_stream(stream), S, A, n, edges_s, n_s, edges_a, n_a, table, p_hat,
+                     edge_flag_or_null);
+  return launch_status();
+}

@@ -1,0 +1,167 @@
+// sv_select_length: verification length per sequence from the acceptance
+// estimates (Sec. 5 of the SV paper: P_gamma(N), E(N | gamma), estimated
+// goodput, incremental search, batch-level greedy rule).
+//
+// With c[b,j] = prod_{i<=j} p_hat[b,i] the expected accepted length of
+// verifying gamma tokens of sequence b is sum_{j<gamma} c[b,j], so the token
+// "with the highest increase in expected acceptance length" is always the
+// largest not-yet-taken c.  Because c is non-increasing along a sequence,
+// sorting all (b,j) by (c descending, b, j ascending) reproduces the greedy
+// order.  One workgroup: products (one lane per sequence), bitonic sort in LDS,
+// the running sum E_M in exactly that order (one lane, fp64, so that the
+// integer outputs do not depend on a reduction tree), goodput and first-peak
+// search in parallel, then counts and offsets.  Launch-latency bound.
+#include "sv_device.hpp"
+#include "sv_host.hpp"
+
+namespace sv {
+
+constexpr int kSelThreads = 1024;
+constexpr int kSelMax = SV_SELECT_MAX_KEYS;   // power of two
+
+__device__ __forceinline__ double clean_p(float p) {
+  if (isnan(p)) return 0.0;
+  return fmin(fmax((double)p, 0.0), 1.0);
+}
+
+// true when key (ca, ia) sorts before key (cb, ib)
+__device__ __forceinline__ bool key_before(double ca, int ia, double cb, int ib) {
+  return ca > cb || (ca == cb && ia < ib);
+}
+
+// Exclusive scan of gamma[b] + 1 over b = 0..B-1 by the whole workgroup.
+// `part` holds blockDim.x ints of LDS.
+__device__ __forceinline__ void offsets_scan(const int32_t* gamma, int B, int32_t* t_offsets, int* part) {
+  const int tid = threadIdx.x, nt = blockDim.x;
+  const int q = (B + nt - 1) / nt;                    // entries per thread
+  const int lo = min(tid * q, B), hi = min(lo + q, B);
+  int local = 0;
+  for (int b = lo; b < hi; ++b) local += gamma[b] + 1;
+  part[tid] = local;
+  __syncthreads();
+  for (int off = 1; off < nt; off <<= 1) {            // Hillis-Steele on integers (exact)
+    const int add = tid >= off ? part[tid - off] : 0;
+    __syncthreads();
+    part[tid] += add;
+    __syncthreads();
+  }
+  int run = part[tid] - local;
+  for (int b = lo; b < hi; ++b) {
+    t_offsets[b] = run;
+    run += gamma[b] + 1;
+  }
+  if (tid == nt - 1) t_offsets[B] = part[nt - 1];
+}
+
+__global__ __launch_bounds__(kSelThreads) void select_batch_kernel(
+    const float* p_hat, int B, int k, const float* latency, int32_t* gamma, int32_t* t_offsets,
+    int32_t* total_M) {
+  __shared__ double key_c[kSelMax];     // sort keys, later the running sums E_M
+  __shared__ int key_i[kSelMax];
+  __shared__ int part[kSelThreads];
+  __shared__ int m_star;
+  const int tid = threadIdx.x, nt = blockDim.x;
+  const int n = B * k;
+  int npad = 1;
+  while (npad < n) npad <<= 1;
+
+  for (int b = tid; b < B; b += nt) {
+    double acc = 1.0;
+    for (int j = 0; j < k; ++j) {
+      acc = acc * clean_p(p_hat[b * k + j]);
+      key_c[b * k + j] = acc;
+      key_i[b * k + j] = b * k + j;
+    }
+  }
+  for (int j = n + tid; j < npad; j += nt) { key_c[j] = -1.0; key_i[j] = 0x7fffffff; }
+  if (tid == 0) m_star = n;
+  __syncthreads();
+
+  // bitonic sort, "before" order ascending in position
+  for (int size = 2; size <= npad; size <<= 1) {
+    for (int stride = size >> 1; stride > 0; stride >>= 1) {
+      for (int t = tid; t < npad / 2; t += nt) {
+        const int lo = 2 * t - (t & (stride - 1));
+        const int hi = lo + stride;
+        const bool up = (lo & size) == 0;
+        const double cl = key_c[lo], ch = key_c[hi];
+        const int il = key_i[lo], ih = key_i[hi];
+        const bool swap = up ? key_before(ch, ih, cl, il) : key_before(cl, il, ch, ih);
+        if (swap) { key_c[lo] = ch; key_c[hi] = cl; key_i[lo] = ih; key_i[hi] = il; }
+      }
+      __syncthreads();
+    }
+  }
+
+  // E_M in selection order, one lane: key_c[M-1] becomes E_M
+  if (tid == 0) {
+    double E = 0.0;
+    for (int j = 0; j < n; ++j) { E += key_c[j]; key_c[j] = E; }
+  }
+  __syncthreads();
+  // goodput G_M = E_M / latency[M]; M* = first M >= 0 with not (G_{M+1} > G_M)
+  for (int M = tid; M < n; M += nt) {
+    const double g_cur = (M == 0) ? 0.0 : key_c[M - 1] / (double)latency[M];
+    const double g_nxt = key_c[M] / (double)latency[M + 1];
+    if (!(g_nxt > g_cur)) atomicMin(&m_star, M);
+  }
+  for (int b = tid; b < B; b += nt) gamma[b] = 0;
+  __syncthreads();
+  const int M = m_star;
+  for (int r = tid; r < M; r += nt) atomicAdd(&gamma[key_i[r] / k], 1);
+  if (tid == 0) *total_M = M;
+  __syncthreads();
+  offsets_scan(gamma, B, t_offsets, part);
+}
+
+__global__ __launch_bounds__(kSelThreads) void select_per_sequence_kernel(
+    const float* p_hat, int B, int k, const float* latency, int32_t* gamma, int32_t* t_offsets,
+    int32_t* total_M) {
+  __shared__ int part[kSelThreads];
+  __shared__ int total;
+  const int tid = threadIdx.x, nt = blockDim.x;
+  if (tid == 0) total = 0;
+  __syncthreads();
+  int mine = 0;
+  for (int b = tid; b < B; b += nt) {
+    double acc = 1.0, E = 0.0, best = 0.0;
+    int g = 0;
+    while (g < k) {
+      acc = acc * clean_p(p_hat[b * k + g]);
+      const double E_new = E + acc;
+      const double good = E_new / (double)latency[g + 1];
+      if (!(good > best)) break;
+      E = E_new; best = good; ++g;
+    }
+    gamma[b] = g;
+    mine += g;
+  }
+  if (mine) atomicAdd(&total, mine);
+  __syncthreads();
+  if (tid == 0) *total_M = total;
+  offsets_scan(gamma, B, t_offsets, part);
+}
+
+}  // namespace sv
+
+extern "C" int sv_select_length(const float* p_hat, int B, int k, const float* latency, int n_latency,
+                                int mode, int32_t* gamma, int32_t* t_offsets, int32_t* total_M,
+                                sv_stream_t stream) {
+  using namespace sv;
+  SV_REQUIRE(mode == SV_BATCH_GREEDY || mode == SV_PER_SEQUENCE, SV_ERR_INVALID_ARG);
+  SV_REQUIRE(B >= 1 && k >= 1, SV_ERR_INVALID_ARG);
+  SV_REQUIRE((long long)B * k <= SV_SELECT_MAX_KEYS, SV_ERR_TOO_LARGE);
+  SV_REQUIRE(n_latency >= (mode == SV_BATCH_GREEDY ? B * k + 1 : k + 1), SV_ERR_INVALID_ARG);
+  SV_REQUIRE(p_hat && latency && gamma && t_offsets && total_M, SV_ERR_NULL);
+  SV_REQUIRE(is_aligned(p_hat, 4) && is_aligned(latency, 4) && is_aligned(gamma, 4) &&
+                 is_aligned(t_offsets, 4) && is_aligned(total_M, 4),
+             SV_ERR_ALIGN);
+  hipStream_t st = as_stream(stream);
+  if (mode == SV_BATCH_GREEDY)
+    hipLaunchKernelGGL(select_batch_kernel, dim3(1), dim3(kSelThreads), 0, st, p_hat, B, k, latency,
+                       gamma, t_offsets, total_M);
+  else
+    hipLaunchKernelGGL(select_per_sequence_kernel, dim3(1), dim3(kSelThreads), 0, st, p_hat, B, k,
+                       latency, gamma, t_offsets, total_M);
+  return launch_status();
+}

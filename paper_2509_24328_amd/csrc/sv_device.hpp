@@ -1,0 +1,308 @@
+// Device-side building blocks shared by the SV kernels (gfx950 only).
+//
+//  * 128-bit streaming loads of bf16 / fp32 logits and their unpacking
+//  * the per-lane online (max, sum-exp) accumulator in the base-2 domain
+//  * wavefront (64-lane) and workgroup reductions
+//  * Philox-4x32-10 for the speculative-sampling uniforms
+//
+// A row's normaliser is carried as the pair (m, s): m = the row maximum in raw
+// logit units and s = sum_v 2^(z_v * L32 - c(m)), c(m) = fl32(max(m, -1e38) * L32),
+// where L32 is log2(e) rounded to fp32.  Because L32 / log2(e) = 1 + 1.33e-8 the
+// sum is the soft-max normaliser at a temperature off by that factor; the fp64
+// epilogue removes the first-order effect around the row maximum
+// (lse_from_ms), leaving an error below 1.4e-8 * (H - H_inf) of the row.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sv {
+
+constexpr int kWave = 64;
+constexpr float kL32 = 1.44269502162933349609375f;          // fl32(log2 e)
+constexpr double kLog2e = 1.4426950408889634073599246810019;  // log2 e
+constexpr double kLn2 = 0.69314718055994530941723212145818;
+constexpr double kTauMinus1 = (double)kL32 / kLog2e - 1.0;   // ~ +1.33e-8
+constexpr float kRefFloor = -1.0e38f;                         // keeps c(m) finite
+
+enum { DT_F32 = 0, DT_BF16 = 1 };
+
+template <int DT> struct Elem;
+template <> struct Elem<DT_F32> { static constexpr int bytes = 4; static constexpr int per_vec = 4; };
+template <> struct Elem<DT_BF16> { static constexpr int bytes = 2; static constexpr int per_vec = 8; };
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // one 128-bit load
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// v_exp_f32: 2^x, no denormal fix-ups (results below 2^-126 flush to zero, which
+// is what a vanishing probability mass should do here).
+__device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// One scalar logit of a row.
+template <int DT>
+__device__ __forceinline__ float load_elem(const void* row, int v) {
+  if (DT == DT_F32) return reinterpret_cast<const float*>(row)[v];
+  uint32_t h = reinterpret_cast<const uint16_t*>(row)[v];
+  return __uint_as_float(h << 16);
+}
+
+// Unpack one 16-byte vector into per_vec floats.
+template <int DT>
+__device__ __forceinline__ void unpack(const u32x4& q, float (&f)[Elem<DT>::per_vec]) {
+  if constexpr (DT == DT_F32) {
+    f[0] = __uint_as_float(q.x); f[1] = __uint_as_float(q.y);
+    f[2] = __uint_as_float(q.z); f[3] = __uint_as_float(q.w);
+  } else {
+    f[0] = bf16_lo(q.x); f[1] = bf16_hi(q.x);
+    f[2] = bf16_lo(q.y); f[3] = bf16_hi(q.y);
+    f[4] = bf16_lo(q.z); f[5] = bf16_hi(q.z);
+    f[6] = bf16_lo(q.w); f[7] = bf16_hi(q.w);
+  }
+}
+
+__device__ __forceinline__ bool aligned16(const void* p) {
+  return (reinterpret_cast<uintptr_t>(p) & 15u) == 0;
+}
+
+// ---------------------------------------------------------------------------
+// online (max, sum 2^(z L32 - c)) accumulator, one per lane
+// ---------------------------------------------------------------------------
+struct Online {
+  float m;   // running maximum (raw units); -inf before the first element
+  float c;   // fl32(max(m, kRefFloor) * L32)
+  float s;   // sum of 2^(z*L32 - c) so far
+
+  __device__ __forceinline__ void init() { m = -INFINITY; c = kRefFloor * kL32; s = 0.f; }
+
+  template <int N>
+  __device__ __forceinline__ void add(const float (&z)[N]) {
+    float mx = m;
+#pragma unroll
+    for (int j = 0; j + 1 < N; j += 2) mx = fmaxf(fmaxf(mx, z[j]), z[j + 1]);   // v_max3_f32
+    if (N & 1) mx = fmaxf(mx, z[N - 1]);
+    const float cn = fmaxf(mx, kRefFloor) * kL32;
+    const float scale = exp2_fast(c - cn);
+    float e[N];
+#pragma unroll
+    for (int j = 0; j < N; ++j) e[j] = exp2_fast(__builtin_fmaf(z[j], kL32, -cn));
+    // pairwise tree so that no single chain carries all roundings
+    float t = 0.f;
+    if constexpr (N == 8) {
+      t = ((e[0] + e[1]) + (e[2] + e[3])) + ((e[4] + e[5]) + (e[6] + e[7]));
+    } else if constexpr (N == 4) {
+      t = (e[0] + e[1]) + (e[2] + e[3]);
+    } else {
+#pragma unroll
+      for (int j = 0; j < N; ++j) t += e[j];
+    }
+    s = __builtin_fmaf(s, scale, t);
+    m = mx;
+    c = cn;
+  }
+
+  __device__ __forceinline__ void add1(float z) {
+    const float mx = fmaxf(m, z);
+    const float cn = fmaxf(mx, kRefFloor) * kL32;
+    s = __builtin_fmaf(s, exp2_fast(c - cn), exp2_fast(__builtin_fmaf(z, kL32, -cn)));
+    m = mx;
+    c = cn;
+  }
+};
+
+// A row's normaliser: exact maximum m and fp64 sum s relative to c(m).
+struct MS {
+  float m;
+  double s;
+};
+
+__device__ __forceinline__ float ref_of(float m) { return fmaxf(m, kRefFloor) * kL32; }
+
+__device__ __forceinline__ double shfl_xor_f64(double v, int mask) {
+  int lo = __double2loint(v), hi = __double2hiint(v);
+  lo = __shfl_xor(lo, mask, kWave);
+  hi = __shfl_xor(hi, mask, kWave);
+  return __hiloint2double(hi, lo);
+}
+
+__device__ __forceinline__ float wave_max_f32(float v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
+  return v;
+}
+
+__device__ __forceinline__ double wave_sum_f64(double v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v += shfl_xor_f64(v, off);
+  return v;
+}
+
+// Scratch for the workgroup reductions below (up to 16 waves).
+struct BlockScratch {
+  float f[16];
+  double d[16];
+};
+
+// Workgroup sum of fp64 partials in a fixed order; result in every thread.
+__device__ __forceinline__ double block_sum_f64(double v, BlockScratch& sm) {
+  v = wave_sum_f64(v);
+  const int wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  if ((threadIdx.x & 63) == 0) sm.d[wave] = v;
+  __syncthreads();
+  double r = 0.0;
+  for (int w = 0; w < nw; ++w) r += sm.d[w];
+  __syncthreads();
+  return r;
+}
+
+__device__ __forceinline__ float block_max_f32(float v, BlockScratch& sm) {
+  v = wave_max_f32(v);
+  const int wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  if ((threadIdx.x & 63) == 0) sm.f[wave] = v;
+  __syncthreads();
+  float r = sm.f[0];
+  for (int w = 1; w < nw; ++w) r = fmaxf(r, sm.f[w]);
+  __syncthreads();
+  return r;
+}
+
+// Workgroup merge of the per-lane accumulators; result valid in every thread.
+// Every lane rescales its sum once to the workgroup-wide reference (a factor
+// 2^(c_lane - c_row) <= 1 from v_exp_f32), then the sums are added in fp64.
+__device__ __forceinline__ MS block_merge(const Online& o, BlockScratch& sm) {
+  MS r;
+  r.m = block_max_f32(o.m, sm);
+  const float cr = ref_of(r.m);
+  const double scaled = (double)o.s * (double)exp2_fast(o.c - cr);
+  r.s = block_sum_f64(scaled, sm);
+  return r;
+}
+
+// Row normaliser in fp64 from (m, s):  log2-domain kappa = c(m) + log2 s is the
+// log2 of sum_v 2^(z_v L32); the natural-log LSE follows after removing the
+// temperature offset around the maximum.  Bad rows (NaN, +inf, no finite
+// entry) give NaN.
+__device__ __forceinline__ double lse_from_ms(const MS& r) {
+  if (!(r.s > 0.0) || !isfinite(r.s) || !isfinite(r.m)) return __builtin_nan("");
+  const double kappa = (double)ref_of(r.m) + log2(r.s);
+  return kappa * kLn2 - kTauMinus1 * (double)r.m;
+}
+
+// log2 of sum_v 2^(z_v L32): the normaliser that makes 2^(z L32 - kappa) sum to
+// one.  Those probabilities are the soft-max at temperature L32/log2(e); entry
+// v deviates from the exact one by a relative 1.33e-8 * (z_v - E_p[z]).
+__device__ __forceinline__ double kappa_l32(const MS& r) {
+  return (double)ref_of(r.m) + log2(r.s);
+}
+
+// ---------------------------------------------------------------------------
+// Sweep of one row: online accumulation by the whole workgroup.
+// ---------------------------------------------------------------------------
+template <int DT>
+__device__ __forceinline__ void sweep_online(const void* row, int V, Online& acc) {
+  constexpr int EPV = Elem<DT>::per_vec;
+  const int tid = threadIdx.x, nt = blockDim.x;
+  if (aligned16(row)) {
+    const u32x4* p = reinterpret_cast<const u32x4*>(row);
+    const int nvec = V / EPV;
+    int i = tid;
+    for (; i + 3 * nt < nvec; i += 4 * nt) {
+      const u32x4 q0 = __builtin_nontemporal_load(p + i);
+      const u32x4 q1 = __builtin_nontemporal_load(p + i + nt);
+      const u32x4 q2 = __builtin_nontemporal_load(p + i + 2 * nt);
+      const u32x4 q3 = __builtin_nontemporal_load(p + i + 3 * nt);
+      float f[EPV];
+      unpack<DT>(q0, f); acc.add(f);
+      unpack<DT>(q1, f); acc.add(f);
+      unpack<DT>(q2, f); acc.add(f);
+      unpack<DT>(q3, f); acc.add(f);
+    }
+    for (; i < nvec; i += nt) {
+      const u32x4 q = __builtin_nontemporal_load(p + i);
+      float f[EPV];
+      unpack<DT>(q, f);
+      acc.add(f);
+    }
+    for (int v = nvec * EPV + tid; v < V; v += nt) acc.add1(load_elem<DT>(row, v));
+  } else {
+    for (int v = tid; v < V; v += nt) acc.add1(load_elem<DT>(row, v));
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Visit elements [v0, v1) of one row (PAIR = false) or of two rows at the same
+// vocabulary index (PAIR = true) with the whole workgroup: f(v, za, zb).
+// Vector loads when both rows start on 16 bytes and v0 is a vector multiple.
+// ---------------------------------------------------------------------------
+template <int DT, bool PAIR, class F>
+__device__ __forceinline__ void visit_range(const void* a, const void* b, int v0, int v1, F&& f) {
+  constexpr int EPV = Elem<DT>::per_vec;
+  const int tid = threadIdx.x, nt = blockDim.x;
+  const bool vec = aligned16(a) && (!PAIR || aligned16(b)) && (v0 % EPV == 0);
+  if (vec) {
+    const u32x4* pa = reinterpret_cast<const u32x4*>(a);
+    const u32x4* pb = reinterpret_cast<const u32x4*>(b);
+    const int i1 = v1 / EPV;
+    int i = v0 / EPV + tid;
+    for (; i + nt < i1; i += 2 * nt) {
+      const u32x4 qa0 = pa[i], qa1 = pa[i + nt];
+      u32x4 qb0 = qa0, qb1 = qa1;
+      if (PAIR) { qb0 = pb[i]; qb1 = pb[i + nt]; }
+      float fa[EPV], fb[EPV];
+      unpack<DT>(qa0, fa); unpack<DT>(qb0, fb);
+#pragma unroll
+      for (int j = 0; j < EPV; ++j) f(i * EPV + j, fa[j], fb[j]);
+      unpack<DT>(qa1, fa); unpack<DT>(qb1, fb);
+#pragma unroll
+      for (int j = 0; j < EPV; ++j) f((i + nt) * EPV + j, fa[j], fb[j]);
+    }
+    for (; i < i1; i += nt) {
+      const u32x4 qa = pa[i];
+      u32x4 qb = qa;
+      if (PAIR) qb = pb[i];
+      float fa[EPV], fb[EPV];
+      unpack<DT>(qa, fa); unpack<DT>(qb, fb);
+#pragma unroll
+      for (int j = 0; j < EPV; ++j) f(i * EPV + j, fa[j], fb[j]);
+    }
+    for (int v = i1 * EPV + tid; v < v1; v += nt) {
+      const float za = load_elem<DT>(a, v);
+      f(v, za, PAIR ? load_elem<DT>(b, v) : za);
+    }
+  } else {
+    for (int v = v0 + tid; v < v1; v += nt) {
+      const float za = load_elem<DT>(a, v);
+      f(v, za, PAIR ? load_elem<DT>(b, v) : za);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Philox-4x32-10 (Salmon et al., SC'11), written for this library
+// ---------------------------------------------------------------------------
+struct U4 { uint32_t w[4]; };
+
+__device__ __forceinline__ U4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                            uint32_t k0, uint32_t k1) {
+  constexpr uint32_t MUL_A = 0xD2511F53u, MUL_B = 0xCD9E8D57u;
+  constexpr uint32_t WEYL_A = 0x9E3779B9u, WEYL_B = 0xBB67AE85u;
+#pragma unroll
+  for (int round = 0; round < 10; ++round) {
+    const uint32_t a_hi = __umulhi(MUL_A, c0), a_lo = MUL_A * c0;
+    const uint32_t b_hi = __umulhi(MUL_B, c2), b_lo = MUL_B * c2;
+    const uint32_t n0 = b_hi ^ c1 ^ k0;
+    const uint32_t n2 = a_hi ^ c3 ^ k1;
+    c0 = n0; c1 = b_lo; c2 = n2; c3 = a_lo;
+    k0 += WEYL_A; k1 += WEYL_B;
+  }
+  U4 r;
+  r.w[0] = c0; r.w[1] = c1; r.w[2] = c2; r.w[3] = c3;
+  return r;
+}
+
+__device__ __forceinline__ double unit_from_word(uint32_t w) {
+  return ((double)(w >> 8) + 0.5) * (1.0 / 16777216.0);
+}
+
+}  // namespace sv

@@ -1,0 +1,66 @@
+// Host-side helpers of the C ABI: argument checks, launch checks and the
+// layout of the caller-provided device workspace.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/sv.h"
+
+namespace sv {
+
+constexpr int kChunk = 8192;          // vocabulary entries per sampling chunk
+constexpr size_t kWsAlign = 256;
+
+inline hipStream_t as_stream(sv_stream_t s) { return reinterpret_cast<hipStream_t>(s); }
+
+inline int elem_bytes(int dtype) { return dtype == SV_F32 ? 4 : (dtype == SV_BF16 ? 2 : 0); }
+
+inline bool is_aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+inline int n_chunks(int V) { return (V + kChunk - 1) / kChunk; }
+
+// Workspace carve-up for sv_verify_sample.  All offsets are multiples of 256.
+struct VerifyWs {
+  double* s_t;        // [B*(k+1)] sum relative to c(m) of each target row
+  double* s_d;        // [B*k]     same for draft rows
+  float* m_t;         // [B*(k+1)] row maxima
+  float* m_d;         // [B*k]
+  float* zx_t;        // [B*k] target logit of the drafted token
+  float* zx_d;        // [B*k] draft logit of the drafted token
+  double* mass_r;     // [B*C] residual mass of each chunk of the sampling row
+  double* mass_t;     // [B*C] target mass of each chunk of the sampling row
+  uint32_t* done;     // [B] chunks finished per sequence
+  size_t bytes;
+};
+
+inline size_t ws_round(size_t n) { return (n + kWsAlign - 1) / kWsAlign * kWsAlign; }
+
+inline VerifyWs carve_verify_ws(void* base, int B, int k, int V) {
+  VerifyWs w;
+  char* p = static_cast<char*>(base);
+  size_t off = 0;
+  const size_t rt = (size_t)B * (k + 1), rd = (size_t)B * k, bc = (size_t)B * n_chunks(V);
+  auto take = [&](size_t bytes) { char* q = p ? p + off : nullptr; off += ws_round(bytes); return q; };
+  w.s_t = reinterpret_cast<double*>(take(rt * 8));
+  w.s_d = reinterpret_cast<double*>(take(rd * 8));
+  w.m_t = reinterpret_cast<float*>(take(rt * 4));
+  w.m_d = reinterpret_cast<float*>(take(rd * 4));
+  w.zx_t = reinterpret_cast<float*>(take(rd * 4));
+  w.zx_d = reinterpret_cast<float*>(take(rd * 4));
+  w.mass_r = reinterpret_cast<double*>(take(bc * 8));
+  w.mass_t = reinterpret_cast<double*>(take(bc * 8));
+  w.done = reinterpret_cast<uint32_t*>(take((size_t)B * 4));
+  w.bytes = off;
+  return w;
+}
+
+inline int launch_status() { return hipGetLastError() == hipSuccess ? SV_OK : SV_ERR_LAUNCH; }
+
+}  // namespace sv
+
+#define SV_REQUIRE(cond, code) \
+  do {                         \
+    if (!(cond)) return (code); \
+  } while (0)

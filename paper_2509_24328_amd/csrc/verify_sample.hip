@@ -1,0 +1,397 @@
+// sv_verify_sample: speculative-sampling verification of the selected draft
+// prefix of every sequence (Sec. 4.2 last paragraph of the SV paper; the
+// accept / residual / bonus rule is the standard speculative-sampling one).
+//
+// Two kernels on the caller's stream:
+//
+//  1. verify_rows_kernel   one workgroup per logit row that the step needs
+//     (target rows 0..gamma_b, draft rows 0..gamma_b-1 of every sequence).
+//     Streams the row once with 128-bit loads and keeps a per-lane online
+//     (max, sum-exp); writes the row's (m, s) and the logit of the drafted
+//     token.  Rows outside the verification length exit without reading.
+//     HBM-bound: V * elem_size bytes per row.
+//
+//  2. verify_sample_kernel  grid (chunks, B).  Every workgroup re-derives the
+//     sequence's accept count from the row scalars in fp64 (k <= 64 positions,
+//     one wavefront), then sums its chunk of the sampling row: residual
+//     max(0, P_t - P_d) and P_t.  The workgroup that finishes last for a
+//     sequence scans the chunk masses, locates the chunk holding u' * W, stages
+//     that chunk's weights in LDS and finds the token with a block prefix scan.
+//     Touches B rows (pairs) only.
+#include "sv_device.hpp"
+#include "sv_host.hpp"
+
+namespace sv {
+
+constexpr int kRowsThreads = 256;
+constexpr int kSampleThreads = 256;
+constexpr int kSeg = kChunk / kSampleThreads;   // contiguous weights per thread in the final scan
+
+struct VerifyArgs {
+  const void* z_t;
+  const int32_t* t_offsets;   // nullable
+  int n_t_rows;
+  const void* z_d;
+  const int32_t* x;
+  const int32_t* gamma;       // nullable
+  int B, k, V;
+  uint32_t seed_lo, seed_hi, step;
+  int32_t* out_tokens;
+  int32_t* n_accept;
+  uint32_t* flags;
+  float* ratio;               // nullable
+  VerifyWs ws;
+};
+
+__device__ __forceinline__ int gamma_of(const VerifyArgs& a, int b) {
+  int g = a.gamma ? a.gamma[b] : a.k;
+  return min(max(g, 0), a.k);
+}
+
+// Target row of (b, i), or nullptr when a packed offset points outside z_t.
+template <int DT>
+__device__ __forceinline__ const void* target_row(const VerifyArgs& a, int b, int i) {
+  long row;
+  if (a.t_offsets) {
+    row = (long)a.t_offsets[b] + i;
+    if (row < 0 || row >= a.n_t_rows) return nullptr;
+  } else {
+    row = (long)b * (a.k + 1) + i;
+  }
+  return static_cast<const char*>(a.z_t) + (size_t)row * a.V * Elem<DT>::bytes;
+}
+
+template <int DT>
+__device__ __forceinline__ const void* draft_row(const VerifyArgs& a, int b, int i) {
+  return static_cast<const char*>(a.z_d) + ((size_t)b * a.k + i) * a.V * Elem<DT>::bytes;
+}
+
+// ---------------------------------------------------------------------------
+// kernel 1: row normalisers
+// ---------------------------------------------------------------------------
+template <int DT>
+__global__ __launch_bounds__(kRowsThreads) void verify_rows_kernel(VerifyArgs a) {
+  __shared__ BlockScratch sm;
+  const int per_seq = 2 * a.k + 1;
+  const int b = blockIdx.x / per_seq;
+  const int r = blockIdx.x - b * per_seq;
+  const bool is_target = r <= a.k;
+  const int i = is_target ? r : r - (a.k + 1);
+  if (r == 0 && threadIdx.x == 0) a.ws.done[b] = 0;   // consumed by kernel 2
+  const int g = gamma_of(a, b);
+  if (is_target ? (i > g) : (i >= g)) return;          // not verified: no bytes read
+
+  const void* row = is_target ? target_row<DT>(a, b, i) : draft_row<DT>(a, b, i);
+  Online acc;
+  acc.init();
+  if (row) sweep_online<DT>(row, a.V, acc);
+  const MS ms = block_merge(acc, sm);
+  if (threadIdx.x == 0) {
+    float zx = __builtin_nanf("");
+    if (i < a.k && row) {
+      const int tok = a.x[b * a.k + i];
+      if (tok >= 0 && tok < a.V) zx = load_elem<DT>(row, tok);
+    }
+    if (is_target) {
+      const int idx = b * (a.k + 1) + i;
+      a.ws.m_t[idx] = ms.m;
+      a.ws.s_t[idx] = ms.s;                 // s = 0 for a missing row => bad row
+      if (i < a.k) a.ws.zx_t[b * a.k + i] = zx;
+    } else {
+      const int idx = b * a.k + i;
+      a.ws.m_d[idx] = ms.m;
+      a.ws.s_d[idx] = ms.s;
+      a.ws.zx_d[idx] = zx;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// kernel 2: accept count, chunk masses, token
+// ---------------------------------------------------------------------------
+// Probability of one vocabulary entry: 2^(z L - kappa) with L = log2 e carried
+// as L32 + l_lo and kappa = k_hi + k_lo, so that neither the rounding of the
+// constant nor that of the row normaliser biases every entry of a row the
+// same way: p = e * (1 + ln2 * (z l_lo - k_lo)), e = 2^(z L32 - k_hi).
+struct ProbRow {
+  float k_hi;      // fl32(kappa)
+  float lo_mul;    // ln2 * (log2 e - L32)
+  float lo_add;    // -ln2 * (kappa - k_hi)
+  __device__ __forceinline__ void set(double lse) {
+    const double kappa = lse * kLog2e;
+    k_hi = (float)kappa;
+    lo_mul = (float)(kLn2 * (kLog2e - (double)kL32));
+    lo_add = (float)(-kLn2 * (kappa - (double)k_hi));
+  }
+  __device__ __forceinline__ float p(float z) const {
+    const float e = exp2_fast(__builtin_fmaf(z, kL32, -k_hi));
+    const float corr = __builtin_fmaf(z, lo_mul, lo_add);
+    return e > 0.f ? __builtin_fmaf(e, corr, e) : 0.f;   // z = -inf: corr is inf, mass is 0
+  }
+};
+
+// LDS position of weight p: one padding word per 32 so that threads walking
+// their own contiguous 32-entry segments hit different banks.
+__device__ __forceinline__ int skew(int p) { return p + (p >> 5); }
+
+struct SampleShared {
+  BlockScratch red;
+  float w[kChunk + kChunk / 32];  // weights of the located chunk (skewed)
+  int n;                         // accepted count
+  uint32_t flags;
+  int is_last;
+  int chunk;
+  int use_resid;
+  int found_thread;
+  double tau_local;
+  double W;
+};
+
+template <int DT>
+__global__ __launch_bounds__(kSampleThreads) void verify_sample_kernel(VerifyArgs a) {
+  __shared__ SampleShared sh;
+  const int b = blockIdx.y, c = blockIdx.x, C = gridDim.x;
+  const int tid = threadIdx.x;
+  const int k = a.k, V = a.V;
+  const int g = gamma_of(a, b);
+
+  // ---- accept count: one lane per drafted position, wavefront 0 ----------
+  if (tid < kWave) {
+    const int i = tid;
+    bool evaluated = i < g;
+    bool accept = true;
+    uint32_t fl = 0;
+    double rho = __builtin_nan("");
+    if (evaluated) {
+      const MS mt{a.ws.m_t[b * (k + 1) + i], a.ws.s_t[b * (k + 1) + i]};
+      const MS md{a.ws.m_d[b * k + i], a.ws.s_d[b * k + i]};
+      const double lse_t = lse_from_ms(mt), lse_d = lse_from_ms(md);
+      const int tok = a.x[b * k + i];
+      if (tok < 0 || tok >= V) {
+        fl |= SV_FLAG_BAD_TOKEN;
+      } else if (isnan(lse_t) || isnan(lse_d)) {
+        fl |= SV_FLAG_BAD_ROW;
+      } else {
+        const double lt = (double)a.ws.zx_t[b * k + i] - lse_t;
+        const double ld = (double)a.ws.zx_d[b * k + i] - lse_d;
+        rho = exp(lt - ld);        // -inf - -inf = NaN: rejected
+      }
+      const U4 r = philox4x32_10((uint32_t)i, (uint32_t)b, 0u, a.step, a.seed_lo, a.seed_hi);
+      const double u = unit_from_word(r.w[0]);
+      accept = u < rho;            // false for NaN
+      if (!isnan(rho) && fabs(u - fmin(1.0, rho)) < 1e-6) fl |= SV_FLAG_NEAR_TIE;
+    }
+    const unsigned long long rej = __ballot(evaluated && !accept);
+    const int n = rej ? (int)__builtin_ctzll(rej) : g;       // leading accepts
+    // flags of the positions that were actually evaluated: 0..min(n, g-1)
+    if (!(evaluated && i <= n)) fl = 0;
+    for (int off = 32; off >= 1; off >>= 1) fl |= __shfl_xor(fl, off, kWave);
+    if (c == 0 && a.ratio && i < k) a.ratio[b * k + i] = (evaluated && i <= n) ? (float)rho : __builtin_nanf("");
+    if (tid == 0) { sh.n = n; sh.flags = fl; }
+  }
+  __syncthreads();
+  const int n = sh.n;
+  uint32_t flags = sh.flags;
+
+  // ---- sampling row and its normalisers -----------------------------------
+  const void* row_t = target_row<DT>(a, b, n);
+  bool resid = n < g;
+  const void* row_d = resid ? draft_row<DT>(a, b, n) : nullptr;
+  const double lse_t = lse_from_ms(MS{a.ws.m_t[b * (k + 1) + n], a.ws.s_t[b * (k + 1) + n]});
+  const bool target_ok = row_t && !isnan(lse_t);
+  ProbRow pt, pd;
+  pt.set(target_ok ? lse_t : 0.0);
+  if (resid) {
+    const double lse_d = lse_from_ms(MS{a.ws.m_d[b * k + n], a.ws.s_d[b * k + n]});
+    if (isnan(lse_d)) {            // unusable draft row: draw from the target instead
+      resid = false;
+      flags |= SV_FLAG_BAD_ROW | SV_FLAG_RESIDUAL_FALLBACK;
+    } else {
+      pd.set(lse_d);
+    }
+  }
+  if (!target_ok) flags |= SV_FLAG_BAD_ROW;
+
+  // ---- mass of this chunk --------------------------------------------------
+  const int v0 = c * kChunk, v1 = min(V, v0 + kChunk);
+  float acc_r = 0.f, acc_t = 0.f;
+  if (target_ok) {
+    if (resid) {
+      visit_range<DT, true>(row_t, row_d, v0, v1, [&](int, float zt, float zd) {
+        const float p = pt.p(zt);
+        acc_t += p;
+        acc_r += fmaxf(0.f, p - pd.p(zd));
+      });
+    } else {
+      visit_range<DT, false>(row_t, nullptr, v0, v1, [&](int, float zt, float) { acc_t += pt.p(zt); });
+    }
+  }
+  const double mass_r = block_sum_f64((double)acc_r, sh.red);
+  const double mass_t = block_sum_f64((double)acc_t, sh.red);
+  if (tid == 0) {
+    a.ws.mass_r[b * C + c] = mass_r;
+    a.ws.mass_t[b * C + c] = mass_t;
+    __threadfence();                                   // masses before the ticket
+    const uint32_t ticket = atomicAdd(&a.ws.done[b], 1u);
+    sh.is_last = (ticket == (uint32_t)(C - 1));
+  }
+  __syncthreads();
+  if (!sh.is_last) return;
+  __threadfence();                                     // see every other chunk's masses
+
+  // ---- last workgroup of the sequence: pick the token ----------------------
+  if (tid == 0) {
+    const volatile double* mr = a.ws.mass_r + (size_t)b * C;
+    const volatile double* mt = a.ws.mass_t + (size_t)b * C;
+    double Wr = 0.0, Wt = 0.0;
+    for (int j = 0; j < C; ++j) { Wr += mr[j]; Wt += mt[j]; }
+    int use_resid = resid;
+    if (target_ok && resid && !(isfinite(Wr) && Wr > 0.0)) { use_resid = 0; flags |= SV_FLAG_RESIDUAL_FALLBACK; }
+    const double W = use_resid ? Wr : Wt;
+    int chunk = -1;
+    double tau_local = 0.0;
+    if (target_ok && isfinite(W) && W > 0.0) {
+      const U4 r = philox4x32_10((uint32_t)n, (uint32_t)b, 0u, a.step, a.seed_lo, a.seed_hi);
+      const double tau = unit_from_word(r.w[1]) * W;
+      const volatile double* ms = use_resid ? mr : mt;
+      double excl = 0.0;
+      int last_pos = -1;
+      double last_excl = 0.0;
+      for (int j = 0; j < C; ++j) {
+        const double mj = ms[j];
+        if (mj > 0.0) { last_pos = j; last_excl = excl; }
+        if (excl + mj > tau) { chunk = j; tau_local = tau - excl; break; }
+        excl += mj;
+      }
+      if (chunk < 0) { chunk = last_pos; tau_local = tau - last_excl; }   // rounding: last chunk with mass
+    } else {
+      flags |= SV_FLAG_BAD_ROW;
+    }
+    sh.chunk = chunk;
+    sh.tau_local = tau_local;
+    sh.use_resid = use_resid;
+    sh.W = W;
+    sh.flags = flags;
+    sh.found_thread = kSampleThreads;
+  }
+  __syncthreads();
+  const int chunk = sh.chunk;
+  int32_t* out = a.out_tokens + (size_t)b * (k + 1);
+  for (int i = tid; i <= k; i += blockDim.x) out[i] = (i < n) ? a.x[b * k + i] : -1;
+  if (tid == 0) a.n_accept[b] = n;
+  if (chunk < 0) {                                     // nothing can be drawn
+    if (tid == 0) a.flags[b] = sh.flags;
+    return;
+  }
+
+  // stage the chunk's weights in LDS in vocabulary order
+  const int w0 = chunk * kChunk, w1 = min(V, w0 + kChunk);
+  for (int j = (w1 - w0) + tid; j < kChunk; j += blockDim.x) sh.w[skew(j)] = 0.f;
+  if (sh.use_resid) {
+    visit_range<DT, true>(row_t, row_d, w0, w1, [&](int v, float zt, float zd) {
+      sh.w[skew(v - w0)] = fmaxf(0.f, pt.p(zt) - pd.p(zd));
+    });
+  } else {
+    visit_range<DT, false>(row_t, nullptr, w0, w1, [&](int v, float zt, float) { sh.w[skew(v - w0)] = pt.p(zt); });
+  }
+  __syncthreads();
+
+  // block prefix scan over contiguous per-thread segments (fp64)
+  static_assert(kSeg == 32, "skew() pads once per 32-entry segment");
+  const float* wseg = sh.w + tid * (kSeg + 1);         // this thread's segment, skewed
+  double seg_sum = 0.0;
+#pragma unroll 8
+  for (int j = 0; j < kSeg; ++j) seg_sum += (double)wseg[j];
+  // inclusive scan inside the wavefront, then across wavefronts through LDS
+  double incl = seg_sum;
+  const int lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {
+    int lo = __double2loint(incl), hi = __double2hiint(incl);
+    lo = __shfl_up(lo, off, kWave);
+    hi = __shfl_up(hi, off, kWave);
+    const double o = __hiloint2double(hi, lo);
+    if (lane >= off) incl += o;
+  }
+  if (lane == 63) sh.red.d[wave] = incl;
+  __syncthreads();
+  double wave_base = 0.0;
+  for (int w = 0; w < wave; ++w) wave_base += sh.red.d[w];
+  incl += wave_base;
+  const double excl = incl - seg_sum;
+  const double tau_local = sh.tau_local;
+  // first thread whose inclusive sum passes the threshold; none when rounding
+  // between the two passes put the threshold at or beyond the chunk total
+  if (incl > tau_local) atomicMin(&sh.found_thread, tid);
+  __syncthreads();
+  int owner = sh.found_thread;
+  const bool beyond = owner >= kSampleThreads;
+  if (beyond) owner = kSampleThreads - 1;
+  if (tid != owner) return;
+
+  const double W = sh.W;
+  double run = excl, prev = excl;
+  int y = -1;
+  if (!beyond) {
+    for (int j = 0; j < kSeg; ++j) {
+      prev = run;
+      run += (double)wseg[j];
+      if (run > tau_local) { y = tid * kSeg + j; break; }
+    }
+  }
+  uint32_t fl = sh.flags;
+  if (y >= 0) {
+    if (fmin(run - tau_local, tau_local - prev) / W < 1e-6) fl |= SV_FLAG_NEAR_CDF_EDGE;
+  } else {
+    // rounding left no entry whose running sum passes the threshold: take the
+    // last positive-weight entry at or before the end of this segment
+    fl |= SV_FLAG_NEAR_CDF_EDGE;
+    for (int p = (tid + 1) * kSeg - 1; p >= 0; --p)
+      if (sh.w[skew(p)] > 0.f) { y = p; break; }
+  }
+  if (y >= 0) out[n] = w0 + y; else fl |= SV_FLAG_BAD_ROW;   // y < 0: the chunk holds no mass at all
+  a.flags[b] = fl;
+}
+
+template <int DT>
+static int launch_verify(const VerifyArgs& a, hipStream_t st) {
+  const int rows = a.B * (2 * a.k + 1);
+  hipLaunchKernelGGL(verify_rows_kernel<DT>, dim3(rows), dim3(kRowsThreads), 0, st, a);
+  if (launch_status() != SV_OK) return SV_ERR_LAUNCH;
+  hipLaunchKernelGGL(verify_sample_kernel<DT>, dim3(n_chunks(a.V), a.B), dim3(kSampleThreads), 0, st, a);
+  return launch_status();
+}
+
+}  // namespace sv
+
+extern "C" int sv_verify_sample(const void* z_t, const int32_t* t_offsets_or_null, int n_t_rows,
+                                const void* z_d, const int32_t* x, const int32_t* gamma_or_null,
+                                int B, int k, int V, int dtype, uint64_t seed, uint32_t step,
+                                int32_t* out_tokens, int32_t* n_accept, uint32_t* flags,
+                                float* ratio_or_null, void* ws, size_t ws_bytes, sv_stream_t stream) {
+  using namespace sv;
+  SV_REQUIRE(dtype == SV_F32 || dtype == SV_BF16, SV_ERR_DTYPE);
+  SV_REQUIRE(B >= 0 && k >= 1 && V >= 1, SV_ERR_INVALID_ARG);
+  SV_REQUIRE(k <= SV_MAX_K, SV_ERR_TOO_LARGE);
+  SV_REQUIRE((long long)B * (2 * k + 1) <= 0x7fffffffLL && B <= 65535, SV_ERR_TOO_LARGE);
+  if (B == 0) return SV_OK;
+  SV_REQUIRE(z_t && z_d && x && out_tokens && n_accept && flags, SV_ERR_NULL);
+  SV_REQUIRE(!t_offsets_or_null || n_t_rows >= 0, SV_ERR_INVALID_ARG);
+  const int eb = elem_bytes(dtype);
+  SV_REQUIRE(is_aligned(z_t, eb) && is_aligned(z_d, eb), SV_ERR_ALIGN);
+  SV_REQUIRE(is_aligned(x, 4) && is_aligned(out_tokens, 4) && is_aligned(n_accept, 4) &&
+                 is_aligned(flags, 4) && is_aligned(t_offsets_or_null, 4) &&
+                 is_aligned(gamma_or_null, 4) && is_aligned(ratio_or_null, 4),
+             SV_ERR_ALIGN);
+  SV_REQUIRE(ws && is_aligned(ws, kWsAlign) && ws_bytes >= sv_workspace_bytes(B, k, V, dtype),
+             SV_ERR_WORKSPACE);
+  VerifyArgs a;
+  a.z_t = z_t; a.t_offsets = t_offsets_or_null; a.n_t_rows = n_t_rows;
+  a.z_d = z_d; a.x = x; a.gamma = gamma_or_null;
+  a.B = B; a.k = k; a.V = V;
+  a.seed_lo = (uint32_t)(seed & 0xffffffffu); a.seed_hi = (uint32_t)(seed >> 32); a.step = step;
+  a.out_tokens = out_tokens; a.n_accept = n_accept; a.flags = flags; a.ratio = ratio_or_null;
+  a.ws = carve_verify_ws(ws, B, k, V);
+  return dtype == SV_F32 ? launch_verify<DT_F32>(a, as_stream(stream))
+                         : launch_verify<DT_BF16>(a, as_stream(stream));
+}

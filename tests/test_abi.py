@@ -1,0 +1,76 @@
+"""CPU-only checks of the boundary: the library loads, exports every symbol
+the header declares, and rejects bad arguments on the host (no launch)."""
+import ctypes
+import os
+import re
+
+import paper_2509_24328_amd as P
+from paper_2509_24328_amd import binding as Bd
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_every_declared_symbol_is_exported():
+    header = open(os.path.join(ROOT, "include", "sv.h")).read()
+    declared = set(re.findall(r"\b(sv_[a-z_]+)\s*\(", header))
+    assert declared == set(Bd.EXPORTS)
+    for name in declared:
+        assert getattr(Bd.lib, name) is not None
+
+
+def test_status_strings():
+    for code in range(-7, 1):
+        assert P.sv_strerror(code).startswith("SV_")
+    assert "unknown" in P.sv_strerror(-99)
+
+
+def test_workspace_sizing():
+    assert P.sv_workspace_bytes(64, 8, 152064, P.SV_BF16) > 0
+    assert P.sv_workspace_bytes(64, 8, 152064, P.SV_BF16) % 256 == 0
+    assert P.sv_workspace_bytes(64, 0, 152064, P.SV_BF16) == 0
+    assert P.sv_workspace_bytes(64, 8, 152064, 7) == 0
+    assert P.sv_workspace_bytes(128, 8, 1000, P.SV_F32) > P.sv_workspace_bytes(64, 8, 1000, P.SV_F32)
+
+
+def test_argument_errors_are_reported_before_any_launch():
+    L = Bd.lib
+    p = ctypes.c_void_p(256 * 1024)          # a non-NULL, aligned, never dereferenced address
+    odd = ctypes.c_void_p(256 * 1024 + 1)
+    big = 1 << 30
+    rs = lambda **kw: L.sv_row_stats(kw.get("zd", p), p, p, kw.get("B", 2), kw.get("k", 2),
+                                     kw.get("V", 8), kw.get("dt", 1), p, p, p, p, None, None,
+                                     kw.get("ws", p), kw.get("wsb", big), None)
+    assert rs(dt=3) == Bd.SV_ERR_DTYPE
+    assert rs(k=0) == Bd.SV_ERR_INVALID_ARG
+    assert rs(V=0) == Bd.SV_ERR_INVALID_ARG
+    assert rs(B=-1) == Bd.SV_ERR_INVALID_ARG
+    assert rs(zd=None) == Bd.SV_ERR_NULL
+    assert rs(zd=odd) == Bd.SV_ERR_ALIGN
+    assert rs(ws=None) == Bd.SV_ERR_WORKSPACE
+    assert rs(wsb=16) == Bd.SV_ERR_WORKSPACE
+    assert rs(ws=odd) == Bd.SV_ERR_WORKSPACE
+
+    vs = lambda **kw: L.sv_verify_sample(kw.get("zt", p), kw.get("offs", None), kw.get("nt", 0), p, p,
+                                         None, kw.get("B", 2), kw.get("k", 2), 8, kw.get("dt", 1), 0, 0,
+                                         kw.get("out", p), p, p, None, kw.get("ws", p),
+                                         kw.get("wsb", big), None)
+    assert vs(dt=-1) == Bd.SV_ERR_DTYPE
+    assert vs(k=65) == Bd.SV_ERR_TOO_LARGE
+    assert vs(zt=None) == Bd.SV_ERR_NULL
+    assert vs(out=None) == Bd.SV_ERR_NULL
+    assert vs(offs=p, nt=-1) == Bd.SV_ERR_INVALID_ARG
+    assert vs(wsb=0) == Bd.SV_ERR_WORKSPACE
+
+    ae = lambda **kw: L.sv_accept_estimate(kw.get("S", p), p, kw.get("n", 4), p, kw.get("ns", 5), p, 5,
+                                           p, p, None, None)
+    assert ae(n=-1) == Bd.SV_ERR_INVALID_ARG
+    assert ae(ns=0) == Bd.SV_ERR_INVALID_ARG
+    assert ae(S=None) == Bd.SV_ERR_NULL
+    assert ae(S=odd) == Bd.SV_ERR_ALIGN
+
+    sl = lambda **kw: L.sv_select_length(kw.get("p", p), kw.get("B", 4), kw.get("k", 4), p,
+                                         kw.get("nl", 17), kw.get("mode", 0), p, p, p, None)
+    assert sl(mode=2) == Bd.SV_ERR_INVALID_ARG
+    assert sl(nl=16) == Bd.SV_ERR_INVALID_ARG
+    assert sl(B=4097, k=1, nl=5000) == Bd.SV_ERR_TOO_LARGE
+    assert sl(p=None) == Bd.SV_ERR_NULL

@@ -1,0 +1,125 @@
+"""GPU parity on the degenerate inputs of the method: bad rows, impossible
+tokens, zero verification length, identical models, masked vocabularies."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import sv_oracle as O
+
+import harness as H
+
+pytestmark = pytest.mark.gpu
+
+
+def _case(B=4, k=3, V=300, seed=0, dtype=torch.float32):
+    rng = np.random.default_rng(seed)
+    z_t = (2 * rng.standard_normal((B, k + 1, V))).astype(np.float32)
+    z_d = (z_t[:, :k] + rng.standard_normal((B, k, V))).astype(np.float32)
+    z_c = (z_t[:, :k] + rng.standard_normal((B, k, V))).astype(np.float32)
+    x = rng.integers(0, V, size=(B, k)).astype(np.int32)
+    return z_t, z_d, z_c, x
+
+
+def _run_verify(z_t, z_d, x, **kw):
+    ref = O.verify_sample(z_t, z_d, x, **kw)
+    got = H.gpu_verify(H.dev(z_t), H.dev(z_d), H.dev(x), **kw)
+    return got, ref
+
+
+def test_empty_batch_is_a_no_op():
+    import paper_2509_24328_amd as P
+    e = torch.empty(0, device="cuda")
+    ws = P.alloc_workspace(0, 4, 100, P.SV_F32)
+    assert P.binding.lib.sv_row_stats(None, None, None, 0, 4, 100, P.SV_F32, None, None, None, None,
+                                      None, None, None, 0, None) == 0
+    assert P.binding.lib.sv_verify_sample(None, None, 0, None, None, None, 0, 4, 100, P.SV_F32, 0, 0,
+                                          None, None, None, None, None, 0, None) == 0
+    assert P.binding.lib.sv_accept_estimate(None, None, 0, None, 3, None, 3, None, None, None, None) == 0
+    torch.cuda.synchronize()
+    del e, ws
+
+
+def test_bad_rows_and_tokens_in_row_stats():
+    z_t, z_d, z_c, x = _case()
+    z_d[0, 0, 5] = np.nan
+    z_c[1, 1, :] = -np.inf
+    z_d[2, 2, 7] = np.inf
+    x[3, 0] = -1
+    x[3, 1] = 300
+    z_d[3, 2, x[3, 2]] = -np.inf          # drafted token the draft could not have produced
+    z_c[0, 1, 10:200] = -np.inf           # masked vocabulary entries are fine
+    ref = O.row_stats(z_d, z_c, x)
+    got = H.gpu_row_stats(H.dev(z_d), H.dev(z_c), H.dev(x))
+    H.assert_row_stats(got, ref)
+    assert got["A"][3, 2] == 1.0 and np.isinf(got["KL"][0, 1])
+
+
+def test_bad_rows_and_tokens_in_verify():
+    z_t, z_d, z_c, x = _case(B=6)
+    z_t[0, 0, 3] = np.nan                 # first target row bad: nothing can be drawn
+    z_d[1, 1, 3] = np.nan                 # draft row bad at position 1
+    x[2, 0] = 999                         # token out of range
+    z_t[3, 2, :] = -np.inf                # all -inf target row
+    z_d[4, 0, x[4, 0]] = -np.inf          # p_d(x) = 0 -> ratio inf -> accepted
+    z_t[5, 0, x[5, 0]] = -np.inf          # p_t(x) = 0 -> ratio 0 -> rejected
+    for seed in range(4):
+        got, ref = _run_verify(z_t, z_d, x, seed=seed)
+        H.assert_verify(got, ref, 3)
+        assert got["tokens"][0, 0] == -1 and got["flags"][0] & O.FLAG_BAD_ROW
+        assert got["flags"][2] & O.FLAG_BAD_TOKEN and got["n_accept"][2] == 0
+        assert got["n_accept"][5] == 0 and got["n_accept"][4] >= 1
+
+
+def test_identical_models_accept_all_and_zero_gamma():
+    z_t, _, _, x = _case(B=5, k=4, V=1000, seed=2)
+    z_d = z_t[:, :4].copy()
+    got, ref = _run_verify(z_t, z_d, x, seed=9)
+    H.assert_verify(got, ref, 4)
+    assert np.all(got["n_accept"] == 4)
+    gamma = np.zeros(5, np.int32)
+    got, ref = _run_verify(z_t, z_d, x, gamma=gamma, seed=9)
+    H.assert_verify(got, ref, 4)
+    assert np.all(got["n_accept"] == 0) and np.all(got["tokens"][:, 0] >= 0)
+
+
+def test_disjoint_supports_and_one_hot_target():
+    B, k, V = 3, 2, 64
+    z_t = np.full((B, k + 1, V), -np.inf, np.float32)
+    z_d = np.full((B, k, V), -np.inf, np.float32)
+    z_t[:, :, :32] = 0.0
+    z_d[:, :, 32:] = 0.0
+    z_t[2, 0, :] = -np.inf
+    z_t[2, 0, 17] = 2.0                   # one-hot target row
+    x = np.full((B, k), 40, np.int32)
+    for seed in range(3):
+        got, ref = _run_verify(z_t, z_d, x, seed=seed)
+        H.assert_verify(got, ref, k)
+        assert np.all(got["n_accept"] == 0) and np.all(got["tokens"][:, 0] < 32)
+        assert got["tokens"][2, 0] == 17
+
+
+def test_packed_offsets_out_of_range_are_flagged_not_read():
+    z_t, z_d, z_c, x = _case(B=3, k=2, V=128)
+    gamma = np.array([2, 1, 2], np.int32)
+    offs = np.array([0, 3, 5, 8], np.int32)
+    packed = np.concatenate([z_t[b, :gamma[b] + 1] for b in range(3)])
+    short = packed[:6]                    # sequence 2 now points past the buffer
+    got = H.gpu_verify(H.dev(short), H.dev(z_d), H.dev(x), gamma=gamma, t_offsets=offs, seed=1)
+    ref = O.verify_sample(packed, z_d, x, gamma=gamma, t_offsets=offs, seed=1)
+    for b in range(2):
+        assert np.array_equal(got["tokens"][b], ref["tokens"][b])
+    assert got["flags"][2] & O.FLAG_BAD_ROW
+
+
+def test_results_are_reproducible_run_to_run():
+    z_t, z_d, z_c, x = _case(B=8, k=4, V=5000, seed=5)
+    a = H.gpu_verify(H.dev(z_t), H.dev(z_d), H.dev(x), seed=4)
+    s1 = H.gpu_row_stats(H.dev(z_d), H.dev(z_c), H.dev(x))
+    for _ in range(3):
+        b = H.gpu_verify(H.dev(z_t), H.dev(z_d), H.dev(x), seed=4)
+        s2 = H.gpu_row_stats(H.dev(z_d), H.dev(z_c), H.dev(x))
+        for n in ("tokens", "n_accept", "flags"):
+            assert np.array_equal(a[n], b[n])
+        assert np.array_equal(a["ratio"], b["ratio"], equal_nan=True)
+        for n in ("lse_d", "S", "A", "KL"):
+            assert np.array_equal(s1[n], s2[n], equal_nan=True)
