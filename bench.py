@@ -1,0 +1,258 @@
+#!/usr/bin/env python3
+"""Benchmark of the SV decode-step hot path on one MI355X.
+
+A step = the four C-ABI calls chained on one stream over one batch of synthetic
+logits resident in HBM:
+    sv_row_stats -> sv_accept_estimate -> sv_select_length -> sv_verify_sample
+at the headline configuration B=64, k=8, V=152064, bf16.  Verification runs at
+full length (gamma = k for every sequence), which is the 1088-row workload the
+metric is quoted on; the selected lengths are still computed every step.  The
+inputs rotate over several distinct copies so that no step finds its logits in
+the 256 MB Infinity Cache.
+
+Prints one JSON line: whole-step throughput in logit rows/s, the HBM roofline
+of the dominant kernel from hipEvents recorded around every launch of it, the
+same for the other kernels, and the CPU oracle timed on this machine.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0        # MI355X published HBM3E bandwidth
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=3, help="0-based index into svgen.CONFIGS")
+    ap.add_argument("--copies", type=int, default=4, help="distinct input copies rotated over")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seqs", type=int, default=0, help="sequences the oracle is timed on (0 = auto)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (reference for rocprofv3 byte counters)")
+    return ap.parse_args()
+
+
+class Hip:
+    """The few HIP runtime calls the bench needs for its own events."""
+
+    def __init__(self):
+        self.lib = ctypes.CDLL("libamdhip64.so")
+        self.lib.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.lib.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.lib.hipEventDestroy.argtypes = [ctypes.c_void_p]
+
+    def event(self):
+        e = ctypes.c_void_p()
+        rc = self.lib.hipEventCreate(ctypes.byref(e))
+        assert rc == 0, f"hipEventCreate -> {rc}"
+        return e
+
+    def elapsed_ms(self, a, b):
+        ms = ctypes.c_float()
+        rc = self.lib.hipEventElapsedTime(ctypes.byref(ms), a, b)
+        assert rc == 0, f"hipEventElapsedTime -> {rc}"
+        return ms.value
+
+
+def read_traffic_file(name):
+    """Measured HBM bytes per launch from the committed rocprofv3 --pmc summary."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_cfg4.txt")
+    out = {}
+    if os.path.exists(path):
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch["):
+                key = line[line.index("[") + 1:line.index("]")]
+                out[key] = float(line.split("=")[1].split()[0])
+    return out.get(name)
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on one GPU only (--gpus {args.gpus} requested); "
+              "no multi-GPU path exists, run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2509_24328_amd as P
+    from paper_2509_24328_amd import binding as Bd
+    import svgen
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    cfgdesc = svgen.CONFIGS[args.config]
+    B, k, V = cfgdesc["B"], cfgdesc["k"], cfgdesc["V"]
+    eb = 2 if cfgdesc["dtype"] == "bf16" else 4
+    tag = P.SV_BF16 if eb == 2 else P.SV_F32
+    t_setup = time.time()
+
+    # ---- inputs: copy 0 is the canonical CPU-seeded config (also fed to the
+    # oracle); the others are drawn on the GPU with the same recipe
+    copies = []
+    cpu_cfg = svgen.make_config(args.config)
+    copies.append({n: cpu_cfg[n].cuda() for n in ("z_t", "z_d", "z_c", "x")})
+    for r in range(1, args.copies):
+        c = svgen.make_config(args.config, seed=1000 + args.config + 100 * r, device="cuda")
+        copies.append({n: c[n] for n in ("z_t", "z_d", "z_c", "x")})
+    edges_s, edges_a, table = svgen.profile_table(10, 10)
+    lat = svgen.latency_table(B * k)
+    cu = lambda a: torch.as_tensor(a).cuda()
+    d_es, d_ea, d_tab, d_lat = cu(edges_s), cu(edges_a), cu(table), cu(lat)
+    f32 = lambda *s: torch.zeros(s, dtype=torch.float32, device="cuda")
+    i32 = lambda *s: torch.zeros(s, dtype=torch.int32, device="cuda")
+    lse_d, lse_c, S, A, p_hat = (f32(B, k) for _ in range(5))
+    gamma, offs, total = i32(B), i32(B + 1), i32(1)
+    tokens, n_acc, flags = i32(B, k + 1), i32(B), i32(B)
+    ws = P.alloc_workspace(B, k, V, tag)
+    stream = torch.cuda.current_stream()
+
+    def step(i, seed=0):
+        c = copies[i % len(copies)]
+        P.sv_row_stats(c["z_d"], c["z_c"], c["x"], lse_d, lse_c, S, A, None, None, ws, stream)
+        P.sv_accept_estimate(S, A, d_es, d_ea, d_tab, p_hat, None, stream)
+        P.sv_select_length(p_hat, d_lat, P.SV_BATCH_GREEDY, gamma, offs, total, stream)
+        P.sv_verify_sample(c["z_t"], None, c["z_d"], c["x"], None, seed, i, tokens, n_acc, flags,
+                           None, ws, stream)
+
+    # ---- timed region: W warm-up steps, then exactly K steps between syncs
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    # ---- the same K steps again with hipEvents around every kernel launch
+    hip = Hip()
+    names = {Bd.SV_KERNEL_ROW_STATS: "row_stats_kernel", Bd.SV_KERNEL_ACCEPT_ESTIMATE: "accept_estimate_kernel",
+             Bd.SV_KERNEL_SELECT_LENGTH: "select_batch_kernel", Bd.SV_KERNEL_VERIFY_ROWS: "verify_rows_kernel",
+             Bd.SV_KERNEL_VERIFY_MASS: "verify_mass_kernel", Bd.SV_KERNEL_VERIFY_PICK: "verify_pick_kernel"}
+    ev = {kid: [(hip.event(), hip.event()) for _ in range(args.steps)] for kid in names}
+    for i in range(args.steps):
+        for kid in names:
+            P.sv_set_timing_events(kid, ev[kid][i][0], ev[kid][i][1])
+        step(i)
+    for kid in names:
+        P.sv_set_timing_events(kid, None, None)
+    torch.cuda.synchronize()
+    us = {names[kid]: float(np.mean([hip.elapsed_ms(a, b) for a, b in ev[kid]]) * 1e3) for kid in names}
+    for kid in names:
+        for a, b in ev[kid]:
+            hip.lib.hipEventDestroy(a)
+            hip.lib.hipEventDestroy(b)
+
+    # ---- algorithmic bytes per launch (each input byte once)
+    row_bytes = V * eb
+    verify_rows = B * (2 * k + 1)
+    stats_rows = 2 * B * k
+    alg = {"verify_rows_kernel": verify_rows * row_bytes, "row_stats_kernel": stats_rows * row_bytes,
+           "verify_mass_kernel": 0, "verify_pick_kernel": 0, "accept_estimate_kernel": 0,
+           "select_batch_kernel": 0}
+    kernels = {}
+    for n, t_us in us.items():
+        kernels[n] = {"avg_us": round(t_us, 2)}
+        if alg[n]:
+            gbs = alg[n] / t_us * 1e-3
+            kernels[n].update({"algorithmic_bytes": alg[n], "achieved_GBps": round(gbs, 1),
+                               "frac_of_peak": round(gbs / PEAK_HBM_GBS, 4)})
+    dominant = max((n for n in us if alg[n]), key=lambda n: us[n])
+    dom_gbs = alg[dominant] / us[dominant] * 1e-3
+    roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(dom_gbs, 1), "peak": PEAK_HBM_GBS,
+                "unit": "GB/s", "frac": round(dom_gbs / PEAK_HBM_GBS, 4),
+                "traffic": read_traffic_file(dominant), "avg_us": round(us[dominant], 2),
+                "algorithmic_bytes": alg[dominant]}
+    metric_kernel = "verify_rows_kernel"
+    mk_gbs = alg[metric_kernel] / us[metric_kernel] * 1e-3
+    verify_call_us = us["verify_rows_kernel"] + us["verify_mass_kernel"] + us["verify_pick_kernel"]
+
+    # ---- correctness on the timed buffers + CPU oracle baseline (copy 0)
+    step(0, seed=0)
+    torch.cuda.synchronize()
+    got = dict(S=S.cpu().numpy(), A=A.cpu().numpy(), p_hat=p_hat.cpu().numpy(), gamma=gamma.cpu().numpy(),
+               tokens=tokens.cpu().numpy(), n_accept=n_acc.cpu().numpy(), flags=flags.cpu().numpy())
+    cpu_baseline = None
+    parity = None
+    if not args.no_cpu_baseline:
+        from oracle import sv_oracle as O
+        nseq = args.cpu_seqs or B
+        nseq = min(nseq, B)
+        zt, zd, zc = (svgen.to_numpy_bits(cpu_cfg[n][:nseq]) for n in ("z_t", "z_d", "z_c"))
+        x = cpu_cfg["x"][:nseq].numpy()
+        c0 = time.perf_counter()
+        r = O.row_stats(zd, zc, x)
+        rp, _ = O.accept_estimate(r["S"].astype(np.float32), r["A"].astype(np.float32), edges_s, edges_a, table)
+        rg, _, _ = O.select_length(rp, svgen.latency_table(nseq * k))
+        ref = O.verify_sample(zt, zd, x, seed=0, step=0)
+        c1 = time.perf_counter()
+        cpu_rows = nseq * (2 * k) + nseq * (2 * k + 1)
+        cpu_baseline = {"value": round(cpu_rows / (c1 - c0), 2), "unit": "rows/s", "cores": 1, "kind": "oracle",
+                        "sample": f"first {nseq} of {B} sequences of the same batch "
+                                  f"({cpu_rows} logit rows, all four calls, {c1 - c0:.1f} s)",
+                        "GBps": round(cpu_rows * row_bytes / (c1 - c0) * 1e-9, 4)}
+        near = (ref["flags"] & (O.FLAG_NEAR_TIE | O.FLAG_NEAR_CDF_EDGE)) != 0
+        near |= (got["flags"][:nseq] & (O.FLAG_NEAR_TIE | O.FLAG_NEAR_CDF_EDGE)) != 0
+        ok = ~near
+        bad = int(np.sum(got["n_accept"][:nseq][ok] != ref["n_accept"][ok]))
+        bad += int(np.sum(np.any(got["tokens"][:nseq][ok] != ref["tokens"][ok], axis=1)))
+        s_err = float(np.max(np.abs(got["S"][:nseq] - r["S"]) / r["S"]))
+        a_err = float(np.max(np.abs(got["A"][:nseq] - r["A"]) / r["A"]))
+        parity = {"sequences_checked": int(nseq), "token_or_count_mismatches_off_flag": bad,
+                  "flagged_near_tie_or_edge": int(near.sum()), "max_rel_err_S": s_err, "max_rel_err_A": a_err,
+                  "p_hat_equal": bool(np.array_equal(got["p_hat"][:nseq], rp)),
+                  "gamma_equal": bool(np.array_equal(got["gamma"], rg)) if nseq == B else None}
+        assert bad == 0 and s_err < 1e-5 and a_err < 1e-5, parity
+
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+
+    rows_per_step = stats_rows + verify_rows
+    out = {
+        "metric": "SV verify step: logit rows/s + achieved HBM GB/s (B=64, k=8, V=152064 bf16)",
+        "value": round(rows_per_step / (ms_per_step * 1e-3), 1),
+        "unit": "rows/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": cfgdesc["name"], "B": B, "k": k, "V": V, "logit_dtype": cfgdesc["dtype"],
+                   "calls": "row_stats+accept_estimate+select_length+verify_sample(gamma=k)",
+                   "rows_per_step": rows_per_step, "row_stats_rows": stats_rows, "verify_rows": verify_rows,
+                   "input_copies_rotated": len(copies)},
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline,
+        "verify_step": {"rows": verify_rows, "us": round(verify_call_us, 2),
+                        "rows_per_s": round(verify_rows / verify_call_us * 1e6, 1),
+                        "metric_kernel": metric_kernel, "metric_kernel_GBps": round(mk_gbs, 1),
+                        "metric_kernel_frac_of_peak": round(mk_gbs / PEAK_HBM_GBS, 4)},
+        "kernels": kernels,
+        "sum_kernel_us": round(sum(us.values()), 2),
+        "parity": parity,
+        "mean_gamma_selected": float(np.mean(got["gamma"])),
+        "mean_accepted_full_verify": float(np.mean(got["n_accept"])),
+        "setup_s": round(time.time() - t_setup, 1),
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

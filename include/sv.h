@@ -68,6 +68,17 @@ enum {
 /* Largest k accepted by sv_verify_sample. */
 #define SV_MAX_K 64
 
+/* Kernels of the library, for sv_set_timing_events. */
+enum {
+  SV_KERNEL_ROW_STATS = 0,
+  SV_KERNEL_ACCEPT_ESTIMATE = 1,
+  SV_KERNEL_SELECT_LENGTH = 2,
+  SV_KERNEL_VERIFY_ROWS = 3,    /* first kernel of sv_verify_sample: row normalisers   */
+  SV_KERNEL_VERIFY_MASS = 4,    /* second: accept count, chunk masses of the sampled row */
+  SV_KERNEL_VERIFY_PICK = 5,    /* third: chunk scan, LDS prefix scan, token             */
+  SV_KERNEL_COUNT = 6
+};
+
 /* Human-readable name of a status code (static string, never NULL). */
 const char* sv_strerror(int status);
 
@@ -156,7 +167,7 @@ int sv_select_length(const float* p_hat, int B, int k,
  *   n_accept   [B] int32             out
  *   flags      [B] uint32            out  SV_FLAG_* bits
  *   ratio_or_null [B,k] float        out  optional: p_t/p_d at evaluated positions, NaN elsewhere
- * Limits: k <= SV_MAX_K.
+ * Limits: k <= SV_MAX_K, V <= 16777216.
  */
 int sv_verify_sample(const void* z_t, const int32_t* t_offsets_or_null, int n_t_rows,
                      const void* z_d, const int32_t* x, const int32_t* gamma_or_null,
@@ -165,6 +176,17 @@ int sv_verify_sample(const void* z_t, const int32_t* t_offsets_or_null, int n_t_
                      int32_t* out_tokens, int32_t* n_accept, uint32_t* flags,
                      float* ratio_or_null,
                      void* ws, size_t ws_bytes, sv_stream_t stream);
+
+/*
+ * Timing taps for benchmarks (not part of the method): while a pair of
+ * hipEvent_t handles is set for `kernel`, every launch of that kernel records
+ * `start_event` immediately before and `stop_event` immediately after it on the
+ * launch stream, so that hipEventElapsedTime(start, stop) brackets that kernel
+ * alone.  Pass NULLs to clear.  Host-side global state: not thread-safe, and
+ * the events must outlive the launches.  Returns SV_ERR_INVALID_ARG for an
+ * unknown kernel id or when only one of the two events is given.
+ */
+int sv_set_timing_events(int kernel, void* start_event, void* stop_event);
 
 #ifdef __cplusplus
 }

@@ -24,7 +24,9 @@ SV_SELECT_MAX_KEYS = 4096
 SV_MAX_K = 64
 
 EXPORTS = ("sv_strerror", "sv_workspace_bytes", "sv_row_stats", "sv_accept_estimate",
-           "sv_select_length", "sv_verify_sample")
+           "sv_select_length", "sv_verify_sample", "sv_set_timing_events")
+(SV_KERNEL_ROW_STATS, SV_KERNEL_ACCEPT_ESTIMATE, SV_KERNEL_SELECT_LENGTH, SV_KERNEL_VERIFY_ROWS,
+ SV_KERNEL_VERIFY_MASS, SV_KERNEL_VERIFY_PICK, SV_KERNEL_COUNT) = range(7)
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2509_24328_amd.build` "
@@ -45,6 +47,8 @@ lib.sv_select_length.argtypes = [_vp, _i, _i, _vp, _i, _i, _vp, _vp, _vp, _vp]
 lib.sv_verify_sample.restype = _i
 lib.sv_verify_sample.argtypes = [_vp, _vp, _i, _vp, _vp, _vp, _i, _i, _i, _i, ctypes.c_uint64,
                                  ctypes.c_uint32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+lib.sv_set_timing_events.restype = _i
+lib.sv_set_timing_events.argtypes = [_i, _vp, _vp]
 
 
 class SvError(RuntimeError):
@@ -115,3 +119,8 @@ def sv_verify_sample(z_t, t_offsets, z_d, x, gamma, seed, step, out_tokens, n_ac
                                 B, k, V, _dtype_tag(z_d), seed, step, _ptr(out_tokens), _ptr(n_accept),
                                 _ptr(flags), _ptr(ratio), _ptr(ws), 0 if ws is None else ws.numel(),
                                 _stream(stream)))
+
+
+def sv_set_timing_events(kernel, start_event, stop_event):
+    """start_event / stop_event: raw hipEvent_t handles (ints / c_void_p) or None."""
+    _check(lib.sv_set_timing_events(kernel, start_event, stop_event))

@@ -49,6 +49,7 @@ extern "C" int sv_accept_estimate(const float* S, const float* A, int n,
                  is_aligned(table, 4) && is_aligned(p_hat, 4),
              SV_ERR_ALIGN);
   const int threads = 256;
+  TapScope tap(SV_KERNEL_ACCEPT_ESTIMATE, as_stream(stream));
   hipLaunchKernelGGL(accept_estimate_kernel, dim3((n + threads - 1) / threads), dim3(threads), 0,
                      as_stream(stream), S, A, n, edges_s, n_s, edges_a, n_a, table, p_hat,
                      edge_flag_or_null);

@@ -20,3 +20,15 @@ extern "C" size_t sv_workspace_bytes(int B, int k, int V, int dtype) {
   if (B == 0) return sv::kWsAlign;
   return sv::carve_verify_ws(nullptr, B, k, V).bytes;
 }
+
+namespace sv {
+TimingTap g_taps[SV_KERNEL_COUNT] = {};
+}
+
+extern "C" int sv_set_timing_events(int kernel, void* start_event, void* stop_event) {
+  if (kernel < 0 || kernel >= SV_KERNEL_COUNT) return SV_ERR_INVALID_ARG;
+  if ((start_event == nullptr) != (stop_event == nullptr)) return SV_ERR_INVALID_ARG;
+  sv::g_taps[kernel].start = reinterpret_cast<hipEvent_t>(start_event);
+  sv::g_taps[kernel].stop = reinterpret_cast<hipEvent_t>(stop_event);
+  return SV_OK;
+}

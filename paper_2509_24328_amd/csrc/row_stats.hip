@@ -157,6 +157,7 @@ extern "C" int sv_row_stats(const void* z_d, const void* z_c, const int32_t* x,
   StatsArgs a{z_d, z_c, x, B, k, V, lse_d, lse_c, S, A, kl_or_null, flags_or_null};
   const dim3 grid(B * k), block(kStatsThreads);
   hipStream_t st = as_stream(stream);
+  TapScope tap(SV_KERNEL_ROW_STATS, st);
   if (dtype == SV_F32) {
     if (kl_or_null) hipLaunchKernelGGL((row_stats_kernel<DT_F32, true>), grid, block, 0, st, a);
     else hipLaunchKernelGGL((row_stats_kernel<DT_F32, false>), grid, block, 0, st, a);
@@ -164,5 +165,5 @@ extern "C" int sv_row_stats(const void* z_d, const void* z_c, const int32_t* x,
     if (kl_or_null) hipLaunchKernelGGL((row_stats_kernel<DT_BF16, true>), grid, block, 0, st, a);
     else hipLaunchKernelGGL((row_stats_kernel<DT_BF16, false>), grid, block, 0, st, a);
   }
-  return launch_status();
+  return launch_status();   // the tap's stop event is recorded on scope exit
 }

@@ -29,14 +29,16 @@ __device__ __forceinline__ bool key_before(double ca, int ia, double cb, int ib)
   return ca > cb || (ca == cb && ia < ib);
 }
 
-// Exclusive scan of gamma[b] + 1 over b = 0..B-1 by the whole workgroup.
+// Exclusive scan of cnt[b] + 1 over b = 0..B-1 by the whole workgroup; writes
+// gamma[b] = cnt[b] and t_offsets[0..B].  cnt may live in LDS or global memory;
 // `part` holds blockDim.x ints of LDS.
-__device__ __forceinline__ void offsets_scan(const int32_t* gamma, int B, int32_t* t_offsets, int* part) {
+__device__ __forceinline__ void offsets_scan(const int* cnt, int B, int32_t* gamma, int32_t* t_offsets,
+                                             int* part) {
   const int tid = threadIdx.x, nt = blockDim.x;
   const int q = (B + nt - 1) / nt;                    // entries per thread
   const int lo = min(tid * q, B), hi = min(lo + q, B);
   int local = 0;
-  for (int b = lo; b < hi; ++b) local += gamma[b] + 1;
+  for (int b = lo; b < hi; ++b) local += cnt[b] + 1;
   part[tid] = local;
   __syncthreads();
   for (int off = 1; off < nt; off <<= 1) {            // Hillis-Steele on integers (exact)
@@ -47,8 +49,10 @@ __device__ __forceinline__ void offsets_scan(const int32_t* gamma, int B, int32_
   }
   int run = part[tid] - local;
   for (int b = lo; b < hi; ++b) {
+    const int gb = cnt[b];
+    gamma[b] = gb;
     t_offsets[b] = run;
-    run += gamma[b] + 1;
+    run += gb + 1;
   }
   if (tid == nt - 1) t_offsets[B] = part[nt - 1];
 }
@@ -57,46 +61,92 @@ __global__ __launch_bounds__(kSelThreads) void select_batch_kernel(
     const float* p_hat, int B, int k, const float* latency, int32_t* gamma, int32_t* t_offsets,
     int32_t* total_M) {
   __shared__ double key_c[kSelMax];     // sort keys, later the running sums E_M
-  __shared__ int key_i[kSelMax];
+  __shared__ int key_i[kSelMax];        // first the raw estimates (as float bits), then key indices
+  __shared__ int cnt[kSelMax];          // selected tokens per sequence
   __shared__ int part[kSelThreads];
   __shared__ int m_star;
   const int tid = threadIdx.x, nt = blockDim.x;
   const int n = B * k;
-  int npad = 1;
+  int npad = 16;                       // a power of two >= max(n, 16)
   while (npad < n) npad <<= 1;
 
+  // estimates into LDS with one round of coalesced loads
+  float* p_lds = reinterpret_cast<float*>(key_i);
+  for (int j = tid; j < n; j += nt) p_lds[j] = p_hat[j];
+  __syncthreads();
   for (int b = tid; b < B; b += nt) {
     double acc = 1.0;
     for (int j = 0; j < k; ++j) {
-      acc = acc * clean_p(p_hat[b * k + j]);
+      acc = acc * clean_p(p_lds[b * k + j]);
       key_c[b * k + j] = acc;
-      key_i[b * k + j] = b * k + j;
     }
+    cnt[b] = 0;
   }
-  for (int j = n + tid; j < npad; j += nt) { key_c[j] = -1.0; key_i[j] = 0x7fffffff; }
+  __syncthreads();
+  for (int j = tid; j < npad; j += nt) {
+    if (j < n) { key_i[j] = j; } else { key_c[j] = -1.0; key_i[j] = 0x7fffffff; }
+  }
   if (tid == 0) m_star = n;
   __syncthreads();
 
   // bitonic sort, "before" order ascending in position
-  for (int size = 2; size <= npad; size <<= 1) {
-    for (int stride = size >> 1; stride > 0; stride >>= 1) {
-      for (int t = tid; t < npad / 2; t += nt) {
-        const int lo = 2 * t - (t & (stride - 1));
-        const int hi = lo + stride;
-        const bool up = (lo & size) == 0;
-        const double cl = key_c[lo], ch = key_c[hi];
-        const int il = key_i[lo], ih = key_i[hi];
-        const bool swap = up ? key_before(ch, ih, cl, il) : key_before(cl, il, ch, ih);
-        if (swap) { key_c[lo] = ch; key_c[hi] = cl; key_i[lo] = ih; key_i[hi] = il; }
+  if (npad <= nt) {
+    // one key per lane, held in registers: partners closer than a wavefront are
+    // exchanged by lane shuffles, farther ones through LDS
+    double c = key_c[tid < npad ? tid : 0];
+    int idx = key_i[tid < npad ? tid : 0];
+    for (int size = 2; size <= npad; size <<= 1) {
+      for (int stride = size >> 1; stride > 0; stride >>= 1) {
+        double pc;
+        int pi;
+        if (stride >= kWave) {
+          __syncthreads();
+          if (tid < npad) { key_c[tid] = c; key_i[tid] = idx; }
+          __syncthreads();
+          pc = key_c[(tid ^ stride) & (npad - 1)];
+          pi = key_i[(tid ^ stride) & (npad - 1)];
+        } else {
+          pc = shfl_xor_f64(c, stride);
+          pi = __shfl_xor(idx, stride, kWave);
+        }
+        const bool up = (tid & size) == 0, lower = (tid & stride) == 0;
+        const bool mine_first = key_before(c, idx, pc, pi);
+        if ((lower == up) ? !mine_first : mine_first) { c = pc; idx = pi; }
       }
-      __syncthreads();
+    }
+    __syncthreads();
+    if (tid < npad) { key_c[tid] = c; key_i[tid] = idx; }
+    __syncthreads();
+  } else {
+    for (int size = 2; size <= npad; size <<= 1) {
+      for (int stride = size >> 1; stride > 0; stride >>= 1) {
+        for (int t = tid; t < npad / 2; t += nt) {
+          const int lo = 2 * t - (t & (stride - 1));
+          const int hi = lo + stride;
+          const bool up = (lo & size) == 0;
+          const double cl = key_c[lo], ch = key_c[hi];
+          const int il = key_i[lo], ih = key_i[hi];
+          const bool swap = up ? key_before(ch, ih, cl, il) : key_before(cl, il, ch, ih);
+          if (swap) { key_c[lo] = ch; key_c[hi] = cl; key_i[lo] = ih; key_i[hi] = il; }
+        }
+        __syncthreads();
+      }
     }
   }
 
-  // E_M in selection order, one lane: key_c[M-1] becomes E_M
+  // E_M in selection order, one lane: key_c[M-1] becomes E_M.  The padding keys
+  // sort last, so running over whole batches of 16 never touches E_1..E_n.
   if (tid == 0) {
     double E = 0.0;
-    for (int j = 0; j < n; ++j) { E += key_c[j]; key_c[j] = E; }
+    for (int j0 = 0; j0 < npad; j0 += 16) {   // batches of loads keep LDS latency off the add chain
+      double v[16];
+#pragma unroll
+      for (int q = 0; q < 16; ++q) v[q] = key_c[j0 + q];
+#pragma unroll
+      for (int q = 0; q < 16; ++q) { E += v[q]; v[q] = E; }
+#pragma unroll
+      for (int q = 0; q < 16; ++q) key_c[j0 + q] = v[q];
+    }
   }
   __syncthreads();
   // goodput G_M = E_M / latency[M]; M* = first M >= 0 with not (G_{M+1} > G_M)
@@ -105,13 +155,12 @@ __global__ __launch_bounds__(kSelThreads) void select_batch_kernel(
     const double g_nxt = key_c[M] / (double)latency[M + 1];
     if (!(g_nxt > g_cur)) atomicMin(&m_star, M);
   }
-  for (int b = tid; b < B; b += nt) gamma[b] = 0;
   __syncthreads();
   const int M = m_star;
-  for (int r = tid; r < M; r += nt) atomicAdd(&gamma[key_i[r] / k], 1);
+  for (int r = tid; r < M; r += nt) atomicAdd(&cnt[key_i[r] / k], 1);
   if (tid == 0) *total_M = M;
   __syncthreads();
-  offsets_scan(gamma, B, t_offsets, part);
+  offsets_scan(cnt, B, gamma, t_offsets, part);
 }
 
 __global__ __launch_bounds__(kSelThreads) void select_per_sequence_kernel(
@@ -139,7 +188,7 @@ __global__ __launch_bounds__(kSelThreads) void select_per_sequence_kernel(
   if (mine) atomicAdd(&total, mine);
   __syncthreads();
   if (tid == 0) *total_M = total;
-  offsets_scan(gamma, B, t_offsets, part);
+  offsets_scan(gamma, B, gamma, t_offsets, part);
 }
 
 }  // namespace sv
@@ -157,8 +206,12 @@ extern "C" int sv_select_length(const float* p_hat, int B, int k, const float* l
                  is_aligned(t_offsets, 4) && is_aligned(total_M, 4),
              SV_ERR_ALIGN);
   hipStream_t st = as_stream(stream);
+  TapScope tap(SV_KERNEL_SELECT_LENGTH, st);
+  // one lane per (padded) key up to the workgroup limit
+  int threads = 64;
+  while (threads < kSelThreads && threads < B * k) threads <<= 1;
   if (mode == SV_BATCH_GREEDY)
-    hipLaunchKernelGGL(select_batch_kernel, dim3(1), dim3(kSelThreads), 0, st, p_hat, B, k, latency,
+    hipLaunchKernelGGL(select_batch_kernel, dim3(1), dim3(threads), 0, st, p_hat, B, k, latency,
                        gamma, t_offsets, total_M);
   else
     hipLaunchKernelGGL(select_per_sequence_kernel, dim3(1), dim3(kSelThreads), 0, st, p_hat, B, k,

@@ -10,6 +10,8 @@
 
 namespace sv {
 
+struct Plan;
+
 constexpr int kChunk = 8192;          // vocabulary entries per sampling chunk
 constexpr size_t kWsAlign = 256;
 
@@ -31,7 +33,7 @@ struct VerifyWs {
   float* zx_d;        // [B*k] draft logit of the drafted token
   double* mass_r;     // [B*C] residual mass of each chunk of the sampling row
   double* mass_t;     // [B*C] target mass of each chunk of the sampling row
-  uint32_t* done;     // [B] chunks finished per sequence
+  Plan* plan;          // [B] per-sequence sampling plan (verify_sample.hip)
   size_t bytes;
 };
 
@@ -51,12 +53,29 @@ inline VerifyWs carve_verify_ws(void* base, int B, int k, int V) {
   w.zx_d = reinterpret_cast<float*>(take(rd * 4));
   w.mass_r = reinterpret_cast<double*>(take(bc * 8));
   w.mass_t = reinterpret_cast<double*>(take(bc * 8));
-  w.done = reinterpret_cast<uint32_t*>(take((size_t)B * 4));
+  w.plan = reinterpret_cast<Plan*>(take((size_t)B * 32));
   w.bytes = off;
   return w;
 }
 
 inline int launch_status() { return hipGetLastError() == hipSuccess ? SV_OK : SV_ERR_LAUNCH; }
+
+// Optional hipEvent pair recorded right before / after a kernel (api.hip).
+struct TimingTap {
+  hipEvent_t start, stop;
+};
+extern TimingTap g_taps[SV_KERNEL_COUNT];
+
+struct TapScope {           // records start on construction, stop on destruction
+  hipStream_t st;
+  hipEvent_t stop;
+  TapScope(int kernel, hipStream_t s) : st(s), stop(g_taps[kernel].stop) {
+    if (g_taps[kernel].start) (void)hipEventRecord(g_taps[kernel].start, st);
+  }
+  ~TapScope() {
+    if (stop) (void)hipEventRecord(stop, st);
+  }
+};
 
 }  // namespace sv
 

@@ -2,7 +2,7 @@
 // prefix of every sequence (Sec. 4.2 last paragraph of the SV paper; the
 // accept / residual / bonus rule is the standard speculative-sampling one).
 //
-// Two kernels on the caller's stream:
+// Three kernels on the caller's stream:
 //
 //  1. verify_rows_kernel   one workgroup per logit row that the step needs
 //     (target rows 0..gamma_b, draft rows 0..gamma_b-1 of every sequence).
@@ -11,13 +11,18 @@
 //     token.  Rows outside the verification length exit without reading.
 //     HBM-bound: V * elem_size bytes per row.
 //
-//  2. verify_sample_kernel  grid (chunks, B).  Every workgroup re-derives the
+//  2. verify_mass_kernel   grid (chunks, B).  Every workgroup re-derives the
 //     sequence's accept count from the row scalars in fp64 (k <= 64 positions,
-//     one wavefront), then sums its chunk of the sampling row: residual
-//     max(0, P_t - P_d) and P_t.  The workgroup that finishes last for a
-//     sequence scans the chunk masses, locates the chunk holding u' * W, stages
-//     that chunk's weights in LDS and finds the token with a block prefix scan.
-//     Touches B rows (pairs) only.
+//     one wavefront), then sums its 8192-entry chunk of the sampling row:
+//     residual max(0, P_t - P_d) and P_t.  Touches B rows (pairs) only.
+//
+//  3. verify_pick_kernel   one workgroup per sequence: scans the chunk masses in
+//     order (fp64), locates the chunk holding u' * W, stages that chunk's
+//     weights in LDS and finds the token with a block prefix scan.
+//
+// Kernel boundaries carry the cross-workgroup hand-offs (row scalars, chunk
+// masses): device-scope fences inside a kernel were measured to cost far more
+// than a launch on this part.
 #include "sv_device.hpp"
 #include "sv_host.hpp"
 
@@ -26,6 +31,7 @@ namespace sv {
 constexpr int kRowsThreads = 256;
 constexpr int kSampleThreads = 256;
 constexpr int kSeg = kChunk / kSampleThreads;   // contiguous weights per thread in the final scan
+constexpr int kMaxChunks = 2048;                // V <= kMaxChunks * kChunk
 
 struct VerifyArgs {
   const void* z_t;
@@ -77,7 +83,6 @@ __global__ __launch_bounds__(kRowsThreads) void verify_rows_kernel(VerifyArgs a)
   const int r = blockIdx.x - b * per_seq;
   const bool is_target = r <= a.k;
   const int i = is_target ? r : r - (a.k + 1);
-  if (r == 0 && threadIdx.x == 0) a.ws.done[b] = 0;   // consumed by kernel 2
   const int g = gamma_of(a, b);
   if (is_target ? (i > g) : (i >= g)) return;          // not verified: no bytes read
 
@@ -134,22 +139,28 @@ struct ProbRow {
 // their own contiguous 32-entry segments hit different banks.
 __device__ __forceinline__ int skew(int p) { return p + (p >> 5); }
 
-struct SampleShared {
-  BlockScratch red;
-  float w[kChunk + kChunk / 32];  // weights of the located chunk (skewed)
-  int n;                         // accepted count
+// What the pick kernel needs to know about a sequence, written by the mass kernel.
+struct alignas(16) Plan {
+  double lse_t, lse_d;
+  int n;               // accepted count = position that is sampled
   uint32_t flags;
-  int is_last;
-  int chunk;
-  int use_resid;
-  int found_thread;
-  double tau_local;
-  double W;
+  int resid;           // 1: residual max(0, P_t - P_d), 0: target distribution
+  int target_ok;
 };
 
+static_assert(sizeof(Plan) == 32, "workspace carve-up reserves 32 bytes per sequence");
+
+struct MassShared {
+  BlockScratch red;
+  int n;
+  uint32_t flags;
+};
+
+// grid (chunks, B): accept count (re-derived per workgroup: k <= 64 positions,
+// one wavefront, fp64) and the mass of one chunk of the sampling row.
 template <int DT>
-__global__ __launch_bounds__(kSampleThreads) void verify_sample_kernel(VerifyArgs a) {
-  __shared__ SampleShared sh;
+__global__ __launch_bounds__(kSampleThreads) void verify_mass_kernel(VerifyArgs a) {
+  __shared__ MassShared sh;
   const int b = blockIdx.y, c = blockIdx.x, C = gridDim.x;
   const int tid = threadIdx.x;
   const int k = a.k, V = a.V;
@@ -198,11 +209,12 @@ __global__ __launch_bounds__(kSampleThreads) void verify_sample_kernel(VerifyArg
   bool resid = n < g;
   const void* row_d = resid ? draft_row<DT>(a, b, n) : nullptr;
   const double lse_t = lse_from_ms(MS{a.ws.m_t[b * (k + 1) + n], a.ws.s_t[b * (k + 1) + n]});
+  double lse_d = 0.0;
   const bool target_ok = row_t && !isnan(lse_t);
   ProbRow pt, pd;
   pt.set(target_ok ? lse_t : 0.0);
   if (resid) {
-    const double lse_d = lse_from_ms(MS{a.ws.m_d[b * k + n], a.ws.s_d[b * k + n]});
+    lse_d = lse_from_ms(MS{a.ws.m_d[b * k + n], a.ws.s_d[b * k + n]});
     if (isnan(lse_d)) {            // unusable draft row: draw from the target instead
       resid = false;
       flags |= SV_FLAG_BAD_ROW | SV_FLAG_RESIDUAL_FALLBACK;
@@ -211,6 +223,17 @@ __global__ __launch_bounds__(kSampleThreads) void verify_sample_kernel(VerifyArg
     }
   }
   if (!target_ok) flags |= SV_FLAG_BAD_ROW;
+  if (c == 0) {
+    if (tid == 0) {
+      Plan pl;
+      pl.lse_t = lse_t; pl.lse_d = lse_d; pl.n = n; pl.flags = flags;
+      pl.resid = resid ? 1 : 0; pl.target_ok = target_ok ? 1 : 0;
+      a.ws.plan[b] = pl;
+      a.n_accept[b] = n;
+    }
+    int32_t* out = a.out_tokens + (size_t)b * (k + 1);
+    for (int i = tid; i <= k; i += blockDim.x) out[i] = (i < n) ? a.x[b * k + i] : -1;
+  }
 
   // ---- mass of this chunk --------------------------------------------------
   const int v0 = c * kChunk, v1 = min(V, v0 + kChunk);
@@ -231,18 +254,51 @@ __global__ __launch_bounds__(kSampleThreads) void verify_sample_kernel(VerifyArg
   if (tid == 0) {
     a.ws.mass_r[b * C + c] = mass_r;
     a.ws.mass_t[b * C + c] = mass_t;
-    __threadfence();                                   // masses before the ticket
-    const uint32_t ticket = atomicAdd(&a.ws.done[b], 1u);
-    sh.is_last = (ticket == (uint32_t)(C - 1));
+  }
+}
+
+struct PickShared {
+  BlockScratch red;
+  union {
+    float w[kChunk + kChunk / 32];  // weights of the located chunk (skewed)
+    double mass[2 * kMaxChunks];    // before that: residual / target mass of every chunk
+  };
+  uint32_t flags;
+  int chunk;
+  int use_resid;
+  int found_thread;
+  double tau_local;
+  double W;
+};
+static_assert(sizeof(double) * 2 * kMaxChunks <= sizeof(float) * (kChunk + kChunk / 32), "mass fits under w");
+
+// grid (B): scan the chunk masses of the sequence, locate the chunk holding
+// u' * W, stage its weights in LDS and find the token with a block prefix scan.
+template <int DT>
+__global__ __launch_bounds__(kSampleThreads) void verify_pick_kernel(VerifyArgs a, int C) {
+  __shared__ PickShared sh;
+  const int b = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int k = a.k, V = a.V;
+  const Plan pl = a.ws.plan[b];
+  const int n = pl.n;
+  const bool target_ok = pl.target_ok != 0;
+  const bool resid = pl.resid != 0;
+  const void* row_t = target_row<DT>(a, b, n);
+  const void* row_d = resid ? draft_row<DT>(a, b, n) : nullptr;
+  ProbRow pt, pd;
+  pt.set(target_ok ? pl.lse_t : 0.0);
+  pd.set(resid ? pl.lse_d : 0.0);
+
+  for (int j = tid; j < C; j += blockDim.x) {          // all chunk masses in one round of loads
+    sh.mass[j] = a.ws.mass_r[(size_t)b * C + j];
+    sh.mass[C + j] = a.ws.mass_t[(size_t)b * C + j];
   }
   __syncthreads();
-  if (!sh.is_last) return;
-  __threadfence();                                     // see every other chunk's masses
-
-  // ---- last workgroup of the sequence: pick the token ----------------------
   if (tid == 0) {
-    const volatile double* mr = a.ws.mass_r + (size_t)b * C;
-    const volatile double* mt = a.ws.mass_t + (size_t)b * C;
+    uint32_t flags = pl.flags;
+    const double* mr = sh.mass;
+    const double* mt = sh.mass + C;
     double Wr = 0.0, Wt = 0.0;
     for (int j = 0; j < C; ++j) { Wr += mr[j]; Wt += mt[j]; }
     int use_resid = resid;
@@ -253,7 +309,7 @@ __global__ __launch_bounds__(kSampleThreads) void verify_sample_kernel(VerifyArg
     if (target_ok && isfinite(W) && W > 0.0) {
       const U4 r = philox4x32_10((uint32_t)n, (uint32_t)b, 0u, a.step, a.seed_lo, a.seed_hi);
       const double tau = unit_from_word(r.w[1]) * W;
-      const volatile double* ms = use_resid ? mr : mt;
+      const double* ms = use_resid ? mr : mt;
       double excl = 0.0;
       int last_pos = -1;
       double last_excl = 0.0;
@@ -276,18 +332,18 @@ __global__ __launch_bounds__(kSampleThreads) void verify_sample_kernel(VerifyArg
   }
   __syncthreads();
   const int chunk = sh.chunk;
+  const int use_resid = sh.use_resid;
   int32_t* out = a.out_tokens + (size_t)b * (k + 1);
-  for (int i = tid; i <= k; i += blockDim.x) out[i] = (i < n) ? a.x[b * k + i] : -1;
-  if (tid == 0) a.n_accept[b] = n;
   if (chunk < 0) {                                     // nothing can be drawn
     if (tid == 0) a.flags[b] = sh.flags;
     return;
   }
+  __syncthreads();                                     // masses are dead: w may overwrite them
 
   // stage the chunk's weights in LDS in vocabulary order
   const int w0 = chunk * kChunk, w1 = min(V, w0 + kChunk);
   for (int j = (w1 - w0) + tid; j < kChunk; j += blockDim.x) sh.w[skew(j)] = 0.f;
-  if (sh.use_resid) {
+  if (use_resid) {
     visit_range<DT, true>(row_t, row_d, w0, w1, [&](int v, float zt, float zd) {
       sh.w[skew(v - w0)] = fmaxf(0.f, pt.p(zt) - pd.p(zd));
     });
@@ -356,9 +412,21 @@ __global__ __launch_bounds__(kSampleThreads) void verify_sample_kernel(VerifyArg
 template <int DT>
 static int launch_verify(const VerifyArgs& a, hipStream_t st) {
   const int rows = a.B * (2 * a.k + 1);
-  hipLaunchKernelGGL(verify_rows_kernel<DT>, dim3(rows), dim3(kRowsThreads), 0, st, a);
+  {
+    TapScope tap(SV_KERNEL_VERIFY_ROWS, st);
+    hipLaunchKernelGGL(verify_rows_kernel<DT>, dim3(rows), dim3(kRowsThreads), 0, st, a);
+  }
   if (launch_status() != SV_OK) return SV_ERR_LAUNCH;
-  hipLaunchKernelGGL(verify_sample_kernel<DT>, dim3(n_chunks(a.V), a.B), dim3(kSampleThreads), 0, st, a);
+  const int C = n_chunks(a.V);
+  {
+    TapScope tap(SV_KERNEL_VERIFY_MASS, st);
+    hipLaunchKernelGGL(verify_mass_kernel<DT>, dim3(C, a.B), dim3(kSampleThreads), 0, st, a);
+  }
+  if (launch_status() != SV_OK) return SV_ERR_LAUNCH;
+  {
+    TapScope tap(SV_KERNEL_VERIFY_PICK, st);
+    hipLaunchKernelGGL(verify_pick_kernel<DT>, dim3(a.B), dim3(kSampleThreads), 0, st, a, C);
+  }
   return launch_status();
 }
 
@@ -372,7 +440,7 @@ extern "C" int sv_verify_sample(const void* z_t, const int32_t* t_offsets_or_nul
   using namespace sv;
   SV_REQUIRE(dtype == SV_F32 || dtype == SV_BF16, SV_ERR_DTYPE);
   SV_REQUIRE(B >= 0 && k >= 1 && V >= 1, SV_ERR_INVALID_ARG);
-  SV_REQUIRE(k <= SV_MAX_K, SV_ERR_TOO_LARGE);
+  SV_REQUIRE(k <= SV_MAX_K && n_chunks(V) <= kMaxChunks, SV_ERR_TOO_LARGE);
   SV_REQUIRE((long long)B * (2 * k + 1) <= 0x7fffffffLL && B <= 65535, SV_ERR_TOO_LARGE);
   if (B == 0) return SV_OK;
   SV_REQUIRE(z_t && z_d && x && out_tokens && n_accept && flags, SV_ERR_NULL);
