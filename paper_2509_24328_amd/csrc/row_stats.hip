@@ -4,15 +4,28 @@
 // One workgroup per (sequence, position).  Sweep 1 streams the draft row and
 // the companion row together with 128-bit loads and keeps one online
 // (max, sum-exp) accumulator per row and lane.  S = sum_v min(P_d, P_c) needs
-// both normalisers before the element-wise comparison, so sweep 2 reads the
-// pair again (served from L2 / Infinity Cache when the workgroup's pair is
-// still resident there) and accumulates
+// both normalisers before the element-wise comparison, so a second sweep over
+// the pair is unavoidable; it accumulates
 //     min(P_d, P_c) = 2^min(a_d, a_c),  a = z * L32 - kappa   (one exp per entry)
 // and, on request, KL(P_d || P_c) = ln2 * sum_v P_d (a_d - a_c).
 // A = min(1, P_c(x) / P_d(x)) is a scalar epilogue in fp64.
+//
+// Two kernels:
+//  * row_stats_stash_kernel (rows on 16-byte boundaries): 1024 lanes, one
+//    workgroup per CU.  Sweep 1 parks what it reads on chip - the first 10
+//    vector pairs of every lane stay in registers, the next 4800 pairs go to
+//    LDS (150 KB) - and only the rest of the pair (about a fifth at V = 152064,
+//    bf16) is read again, most recent bytes first so that they are still in L2.
+//  * row_stats_kernel: plain two-sweep version for rows of any alignment.
 // Algorithmic HBM traffic: 2 * V * elem_size bytes per workgroup.
 #include "sv_device.hpp"
 #include "sv_host.hpp"
+
+// Phase marks: empty in the library; a profiling build may define
+// SV_PHASE_MARK(n) to record a clock at the boundaries of the kernel's phases.
+#ifndef SV_PHASE_MARK
+#define SV_PHASE_MARK(n)
+#endif
 
 namespace sv {
 
@@ -68,70 +81,284 @@ __device__ __forceinline__ void sweep_online_pair(const void* ra, const void* rb
   }
 }
 
+// Sweep-2 arithmetic for one vocabulary entry (see row_stats_kernel for the
+// head/tail split of the normalisers).
+template <bool WITH_KL>
+struct MinAcc {
+  float kd, kc, delta;
+  float acc_s = 0.f, acc_kl = 0.f;
+  __device__ __forceinline__ void add(float zd, float zc) {
+    const float ad = __builtin_fmaf(zd, kL32, -kd);
+    const float ac = __builtin_fmaf(zc, kL32, -kc) + delta;
+    if (WITH_KL) {
+      const float pd = exp2_fast(ad);
+      acc_s += fminf(pd, exp2_fast(ac));
+      const float t = pd * (ad - ac);          // 0 * inf when P_d underflows: dropped below
+      acc_kl += (pd > 0.f) ? t : 0.f;
+    } else {
+      acc_s += exp2_fast(fminf(ad, ac));
+    }
+  }
+  template <int DT>
+  __device__ __forceinline__ void add_vec(const u32x4& qd, const u32x4& qc) {
+    float fd[Elem<DT>::per_vec], fc[Elem<DT>::per_vec];
+    unpack<DT>(qd, fd);
+    unpack<DT>(qc, fc);
+#pragma unroll
+    for (int j = 0; j < Elem<DT>::per_vec; ++j) {
+      add(fd[j], fc[j]);
+      // both sums advance together: otherwise all S terms are formed first and
+      // the exponents wait in scratch for the KL terms
+      if (WITH_KL && (j & 1)) asm volatile("" : "+v"(acc_s), "+v"(acc_kl));
+    }
+  }
+};
+
+// Scalar epilogue shared by both kernels: A, flags and the stores.
+template <int DT, bool WITH_KL>
+__device__ __forceinline__ void stats_epilogue(const StatsArgs& a, int pair, const void* rd, const void* rc,
+                                               double lse_d, double lse_c, double S, double KL) {
+  const bool bad = isnan(lse_d) || isnan(lse_c);
+  uint32_t fl = bad ? SV_FLAG_BAD_ROW : 0u;
+  double A = __builtin_nan("");
+  if (!bad) {
+    const int tok = a.x[pair];
+    if (tok < 0 || tok >= a.V) {
+      fl |= SV_FLAG_BAD_TOKEN;
+    } else {
+      const double ld = (double)load_elem<DT>(rd, tok) - lse_d;
+      const double lc = (double)load_elem<DT>(rc, tok) - lse_c;
+      A = (ld == -INFINITY) ? 1.0 : fmin(1.0, exp(lc - ld));
+    }
+  }
+  a.lse_d[pair] = (float)lse_d;
+  a.lse_c[pair] = (float)lse_c;
+  a.S[pair] = (float)S;
+  a.A[pair] = (float)A;
+  if (WITH_KL) a.kl[pair] = (float)KL;
+  if (a.flags) a.flags[pair] = fl;
+}
+
+constexpr int kStashThreads = 512;
+constexpr int kLdsVecs = 2432;       // vector pairs parked in LDS (2 * 2432 * 16 B = 76 KB)
+constexpr int kLdsIters = (kLdsVecs + kStashThreads - 1) / kStashThreads;
+constexpr size_t kStashLdsBytes = 2 * (size_t)kLdsVecs * 16;
+
+// 16 bytes per lane from global memory straight into LDS: lane l of the
+// wavefront writes lds_wave_base + 16 * l (global_load_lds_dwordx4).
+__device__ __forceinline__ void load_to_lds(const u32x4* src, u32x4* lds_wave_base) {
+  __builtin_amdgcn_global_load_lds(
+      reinterpret_cast<const __attribute__((address_space(1))) void*>(reinterpret_cast<uintptr_t>(src)),
+      reinterpret_cast<__attribute__((address_space(3))) void*>(reinterpret_cast<uintptr_t>(lds_wave_base)),
+      16, 0, 0);
+}
+
+// vector pairs per lane parked in registers: what fits beside the sweep-2
+// arithmetic within the 128 VGPRs a 1024-lane workgroup leaves each lane
+template <bool WITH_KL>
+constexpr int reg_iters() { return WITH_KL ? 8 : 10; }
+
+template <int DT, bool WITH_KL>
+__global__ __launch_bounds__(kStashThreads) void row_stats_stash_kernel(StatsArgs a) {
+  constexpr int kRegIters = reg_iters<WITH_KL>();
+  extern __shared__ u32x4 park[];                      // [kLdsVecs] draft, then [kLdsVecs] companion
+  __shared__ BlockScratch sm;
+  __shared__ MergeScratch<2> mg;
+  constexpr int EPV = Elem<DT>::per_vec;
+  constexpr uint32_t kNegInfWord = (DT == DT_BF16) ? 0xFF80FF80u : 0xFF800000u;
+  const int tid = threadIdx.x;
+  constexpr int nt = kStashThreads;
+  const int pair = blockIdx.x;
+  const size_t row_bytes = (size_t)a.V * Elem<DT>::bytes;
+  const u32x4* pd = reinterpret_cast<const u32x4*>(static_cast<const char*>(a.z_d) + pair * row_bytes);
+  const u32x4* pc = reinterpret_cast<const u32x4*>(static_cast<const char*>(a.z_c) + pair * row_bytes);
+  const int nvec = a.V / EPV;                           // rows are whole vectors here
+  const int lds_begin = kRegIters * nt;
+  const int lds_end = min(nvec, lds_begin + kLdsVecs);
+  const u32x4 neg = {kNegInfWord, kNegInfWord, kNegInfWord, kNegInfWord};
+
+  // ---- sweep 1 ------------------------------------------------------------
+  SV_PHASE_MARK(0)
+  Online on[2];
+  Online& od = on[0];
+  Online& oc = on[1];
+  od.init();
+  oc.init();
+  u32x4 sd[kRegIters], sc[kRegIters];
+#pragma unroll
+  for (int j = 0; j < kRegIters; ++j) {                 // all loads in flight before any use
+    const int i = tid + j * nt;
+    sd[j] = neg;
+    sc[j] = neg;
+    if (i < nvec) { sd[j] = pd[i]; sc[j] = pc[i]; }
+  }
+  // the LDS share goes straight from memory into LDS (no registers in between)
+  // and lands while the register share is being accumulated
+  {
+    const int wave_base = tid & ~(kWave - 1);
+#pragma unroll
+    for (int j = 0; j < kLdsIters; ++j) {
+      const int slot = j * nt + wave_base;              // LDS slot of lane 0; the hardware adds lane * 16 B
+      const int i = lds_begin + j * nt + tid;
+      if (i < lds_end) {
+        load_to_lds(pd + i, park + slot);
+        load_to_lds(pc + i, park + kLdsVecs + slot);
+      }
+    }
+  }
+  SV_PHASE_MARK(1)
+#pragma unroll
+  for (int j = 0; j < kRegIters; ++j) {                 // -inf padding adds nothing
+    float f[EPV];
+    unpack<DT>(sd[j], f); od.add(f);
+    __builtin_amdgcn_sched_barrier(0);
+    unpack<DT>(sc[j], f); oc.add(f);
+    __builtin_amdgcn_sched_barrier(0);                  // one pair at a time: the parked vectors own the registers
+  }
+  SV_PHASE_MARK(2)
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // LDS share has landed (own lanes only: no barrier)
+  for (int i = lds_begin + tid; i < lds_end; i += nt) {
+    float f[EPV];
+    unpack<DT>(park[i - lds_begin], f); od.add(f);
+    unpack<DT>(park[kLdsVecs + i - lds_begin], f); oc.add(f);
+  }
+  SV_PHASE_MARK(3)
+  {
+    int i = lds_end + tid;
+    for (; i + nt < nvec; i += 2 * nt) {
+      const u32x4 d0 = pd[i], c0 = pc[i], d1 = pd[i + nt], c1 = pc[i + nt];
+      float f[EPV];
+      unpack<DT>(d0, f); od.add(f);
+      __builtin_amdgcn_sched_barrier(0);
+      unpack<DT>(c0, f); oc.add(f);
+      __builtin_amdgcn_sched_barrier(0);
+      unpack<DT>(d1, f); od.add(f);
+      __builtin_amdgcn_sched_barrier(0);
+      unpack<DT>(c1, f); oc.add(f);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    for (; i < nvec; i += nt) {
+      const u32x4 d0 = pd[i], c0 = pc[i];
+      float f[EPV];
+      unpack<DT>(d0, f); od.add(f);
+      unpack<DT>(c0, f); oc.add(f);
+    }
+  }
+  SV_PHASE_MARK(4)
+  MS merged[2];
+  block_merge<2>(on, mg, merged);
+  const MS msd = merged[0], msc = merged[1];
+  const double lse_d = lse_from_ms(msd), lse_c = lse_from_ms(msc);
+  const bool bad = isnan(lse_d) || isnan(lse_c);
+
+  SV_PHASE_MARK(5)
+  // ---- sweep 2: rest of the pair from L2/HBM (newest first), then LDS, then registers
+  double S = __builtin_nan(""), KL = __builtin_nan("");
+  if (!bad) {
+    const double kappa_d = kappa_l32(msd), kappa_c = kappa_l32(msc);
+    MinAcc<WITH_KL> acc;
+    acc.kd = (float)kappa_d;
+    acc.kc = (float)kappa_c;
+    const double tail_d = kappa_d - (double)acc.kd, tail_c = kappa_c - (double)acc.kc;
+    acc.delta = (float)(tail_d - tail_c);
+    {
+      // walk the re-read region backwards: its end was read last in sweep 1
+      const int n_rest = nvec - lds_end;
+      int r = tid;
+      for (; r + nt < n_rest; r += 2 * nt) {
+        const int i0 = nvec - 1 - r, i1 = nvec - 1 - (r + nt);
+        const u32x4 d0 = pd[i0], c0 = pc[i0], d1 = pd[i1], c1 = pc[i1];
+        acc.template add_vec<DT>(d0, c0);
+        __builtin_amdgcn_sched_barrier(0);
+        acc.template add_vec<DT>(d1, c1);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      for (; r < n_rest; r += nt) {
+        const int i0 = nvec - 1 - r;
+        acc.template add_vec<DT>(pd[i0], pc[i0]);
+      }
+    }
+    SV_PHASE_MARK(6)
+    for (int i = lds_begin + tid; i < lds_end; i += nt)
+      acc.template add_vec<DT>(park[i - lds_begin], park[kLdsVecs + i - lds_begin]);
+    SV_PHASE_MARK(7)
+#pragma unroll
+    for (int j = 0; j < kRegIters; ++j) {               // -inf padding: 2^-inf = 0
+      // keep the vectors packed between the sweeps: without this the unpacked
+      // floats of sweep 1 are kept alive for reuse and spill
+      asm volatile("" : "+v"(sd[j].x), "+v"(sd[j].y), "+v"(sd[j].z), "+v"(sd[j].w));
+      asm volatile("" : "+v"(sc[j].x), "+v"(sc[j].y), "+v"(sc[j].z), "+v"(sc[j].w));
+      acc.template add_vec<DT>(sd[j], sc[j]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    SV_PHASE_MARK(8)
+    const double f_d = exp2(-tail_d);
+    S = f_d * block_sum_f64((double)acc.acc_s, sm);
+    if (WITH_KL) KL = f_d * kLn2 * block_sum_f64((double)acc.acc_kl, sm);
+  }
+  SV_PHASE_MARK(9)
+  if (tid == 0) stats_epilogue<DT, WITH_KL>(a, pair, pd, pc, lse_d, lse_c, S, KL);
+}
+
 template <int DT, bool WITH_KL>
 __global__ __launch_bounds__(kStatsThreads) void row_stats_kernel(StatsArgs a) {
   __shared__ BlockScratch sm;
+  __shared__ MergeScratch<2> mg;
   const int pair = blockIdx.x;                       // b * k + i
   const size_t row_bytes = (size_t)a.V * Elem<DT>::bytes;
   const void* rd = static_cast<const char*>(a.z_d) + pair * row_bytes;
   const void* rc = static_cast<const char*>(a.z_c) + pair * row_bytes;
 
-  Online od, oc;
-  od.init();
-  oc.init();
-  sweep_online_pair<DT>(rd, rc, a.V, od, oc);
-  const MS msd = block_merge(od, sm);
-  const MS msc = block_merge(oc, sm);
+  Online on[2];
+  on[0].init();
+  on[1].init();
+  sweep_online_pair<DT>(rd, rc, a.V, on[0], on[1]);
+  MS merged[2];
+  block_merge<2>(on, mg, merged);
+  const MS msd = merged[0], msc = merged[1];
   const double lse_d = lse_from_ms(msd), lse_c = lse_from_ms(msc);
   const bool bad = isnan(lse_d) || isnan(lse_c);
 
   double S = __builtin_nan(""), KL = __builtin_nan("");
   if (!bad) {
     // kappa = log2-domain normaliser consistent with the L32 exponent scale,
-    // split into an fp32 head and a tail.  With a = z*L32 - head:  P_d = f_d 2^(a_d),  P_c = f_d 2^(a_c + delta),
+    // split into an fp32 head and a tail.  With a = z*L32 - head:
+    // P_d = f_d 2^(a_d),  P_c = f_d 2^(a_c + delta),
     // f_d = 2^(-tail_d), delta = tail_d - tail_c, so one scalar factor at the
     // end removes the rounding of both heads.
     const double kappa_d = kappa_l32(msd), kappa_c = kappa_l32(msc);
-    const float kd = (float)kappa_d, kc = (float)kappa_c;
-    const double tail_d = kappa_d - (double)kd, tail_c = kappa_c - (double)kc;
-    const float delta = (float)(tail_d - tail_c);
-    float acc_s = 0.f, acc_kl = 0.f;
-    visit_range<DT, true>(rd, rc, 0, a.V, [&](int, float zd, float zc) {
-      const float ad = __builtin_fmaf(zd, kL32, -kd);
-      const float ac = __builtin_fmaf(zc, kL32, -kc) + delta;
-      if (WITH_KL) {
-        const float pd = exp2_fast(ad);
-        acc_s += (ad <= ac) ? pd : exp2_fast(ac);
-        if (pd > 0.f) acc_kl = __builtin_fmaf(pd, ad - ac, acc_kl);
-      } else {
-        acc_s += exp2_fast(fminf(ad, ac));
-      }
-    });
+    MinAcc<WITH_KL> acc;
+    acc.kd = (float)kappa_d;
+    acc.kc = (float)kappa_c;
+    const double tail_d = kappa_d - (double)acc.kd, tail_c = kappa_c - (double)acc.kc;
+    acc.delta = (float)(tail_d - tail_c);
+    visit_range<DT, true>(rd, rc, 0, a.V, [&](int, float zd, float zc) { acc.add(zd, zc); });
     const double f_d = exp2(-tail_d);
-    S = f_d * block_sum_f64((double)acc_s, sm);
-    if (WITH_KL) KL = f_d * kLn2 * block_sum_f64((double)acc_kl, sm);
+    S = f_d * block_sum_f64((double)acc.acc_s, sm);
+    if (WITH_KL) KL = f_d * kLn2 * block_sum_f64((double)acc.acc_kl, sm);
   }
+  if (threadIdx.x == 0) stats_epilogue<DT, WITH_KL>(a, pair, rd, rc, lse_d, lse_c, S, KL);
+}
 
-  if (threadIdx.x == 0) {
-    uint32_t fl = bad ? SV_FLAG_BAD_ROW : 0u;
-    double A = __builtin_nan("");
-    if (!bad) {
-      const int tok = a.x[pair];
-      if (tok < 0 || tok >= a.V) {
-        fl |= SV_FLAG_BAD_TOKEN;
-      } else {
-        const double ld = (double)load_elem<DT>(rd, tok) - lse_d;
-        const double lc = (double)load_elem<DT>(rc, tok) - lse_c;
-        A = (ld == -INFINITY) ? 1.0 : fmin(1.0, exp(lc - ld));
-      }
+template <int DT, bool WITH_KL>
+static int launch_stats(const StatsArgs& a, bool rows_aligned, hipStream_t st) {
+  const dim3 grid(a.B * a.k);
+  if (rows_aligned) {
+    // more than 64 KB of dynamic LDS has to be allowed once per kernel
+    static bool allowed = false;
+    if (!allowed) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(&row_stats_stash_kernel<DT, WITH_KL>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kStashLdsBytes) != hipSuccess)
+        return SV_ERR_LAUNCH;
+      allowed = true;
     }
-    a.lse_d[pair] = (float)lse_d;
-    a.lse_c[pair] = (float)lse_c;
-    a.S[pair] = (float)S;
-    a.A[pair] = (float)A;
-    if (WITH_KL) a.kl[pair] = (float)KL;
-    if (a.flags) a.flags[pair] = fl;
+    TapScope tap(SV_KERNEL_ROW_STATS, st);
+    hipLaunchKernelGGL((row_stats_stash_kernel<DT, WITH_KL>), grid, dim3(kStashThreads), kStashLdsBytes, st, a);
+  } else {
+    TapScope tap(SV_KERNEL_ROW_STATS, st);
+    hipLaunchKernelGGL((row_stats_kernel<DT, WITH_KL>), grid, dim3(kStatsThreads), 0, st, a);
   }
+  return launch_status();
 }
 
 }  // namespace sv
@@ -155,15 +382,9 @@ extern "C" int sv_row_stats(const void* z_d, const void* z_c, const int32_t* x,
   SV_REQUIRE(ws && is_aligned(ws, kWsAlign) && ws_bytes >= sv_workspace_bytes(B, k, V, dtype),
              SV_ERR_WORKSPACE);
   StatsArgs a{z_d, z_c, x, B, k, V, lse_d, lse_c, S, A, kl_or_null, flags_or_null};
-  const dim3 grid(B * k), block(kStatsThreads);
+  const bool rows_aligned = is_aligned(z_d, 16) && is_aligned(z_c, 16) && ((size_t)V * eb) % 16 == 0;
   hipStream_t st = as_stream(stream);
-  TapScope tap(SV_KERNEL_ROW_STATS, st);
-  if (dtype == SV_F32) {
-    if (kl_or_null) hipLaunchKernelGGL((row_stats_kernel<DT_F32, true>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((row_stats_kernel<DT_F32, false>), grid, block, 0, st, a);
-  } else {
-    if (kl_or_null) hipLaunchKernelGGL((row_stats_kernel<DT_BF16, true>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((row_stats_kernel<DT_BF16, false>), grid, block, 0, st, a);
-  }
-  return launch_status();   // the tap's stop event is recorded on scope exit
+  if (dtype == SV_F32)
+    return kl_or_null ? launch_stats<DT_F32, true>(a, rows_aligned, st) : launch_stats<DT_F32, false>(a, rows_aligned, st);
+  return kl_or_null ? launch_stats<DT_BF16, true>(a, rows_aligned, st) : launch_stats<DT_BF16, false>(a, rows_aligned, st);
 }

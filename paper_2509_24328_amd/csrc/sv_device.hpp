@@ -167,16 +167,37 @@ __device__ __forceinline__ float block_max_f32(float v, BlockScratch& sm) {
   return r;
 }
 
-// Workgroup merge of the per-lane accumulators; result valid in every thread.
-// Every lane rescales its sum once to the workgroup-wide reference (a factor
-// 2^(c_lane - c_row) <= 1 from v_exp_f32), then the sums are added in fp64.
-__device__ __forceinline__ MS block_merge(const Online& o, BlockScratch& sm) {
-  MS r;
-  r.m = block_max_f32(o.m, sm);
-  const float cr = ref_of(r.m);
-  const double scaled = (double)o.s * (double)exp2_fast(o.c - cr);
-  r.s = block_sum_f64(scaled, sm);
-  return r;
+// Workgroup merge of the per-lane accumulators of NR rows at once; results
+// valid in every thread after a single barrier.  Inside a wavefront every lane
+// rescales its sum to the wavefront's reference (a factor 2^(c_lane - c_wave)
+// <= 1 from v_exp_f32) and the sums are added in fp64; the per-wavefront
+// pairs go through LDS and every thread folds them in the same fixed order.
+template <int NR>
+struct MergeScratch {
+  float m[NR][16];
+  double s[NR][16];
+};
+
+template <int NR>
+__device__ __forceinline__ void block_merge(const Online (&o)[NR], MergeScratch<NR>& sm, MS (&out)[NR]) {
+  const int wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+#pragma unroll
+  for (int r = 0; r < NR; ++r) {
+    const float mw = wave_max_f32(o[r].m);
+    const double sw = wave_sum_f64((double)o[r].s * (double)exp2_fast(o[r].c - ref_of(mw)));
+    if ((threadIdx.x & 63) == 0) { sm.m[r][wave] = mw; sm.s[r][wave] = sw; }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < NR; ++r) {
+    float m = sm.m[r][0];
+    for (int w = 1; w < nw; ++w) m = fmaxf(m, sm.m[r][w]);
+    const float cr = ref_of(m);
+    double acc = 0.0;
+    for (int w = 0; w < nw; ++w) acc += sm.s[r][w] * (double)exp2_fast(ref_of(sm.m[r][w]) - cr);
+    out[r].m = m;
+    out[r].s = acc;
+  }
 }
 
 // Row normaliser in fp64 from (m, s):  log2-domain kappa = c(m) + log2 s is the

@@ -77,7 +77,7 @@ __device__ __forceinline__ const void* draft_row(const VerifyArgs& a, int b, int
 // ---------------------------------------------------------------------------
 template <int DT>
 __global__ __launch_bounds__(kRowsThreads) void verify_rows_kernel(VerifyArgs a) {
-  __shared__ BlockScratch sm;
+  __shared__ MergeScratch<1> sm;
   const int per_seq = 2 * a.k + 1;
   const int b = blockIdx.x / per_seq;
   const int r = blockIdx.x - b * per_seq;
@@ -87,10 +87,12 @@ __global__ __launch_bounds__(kRowsThreads) void verify_rows_kernel(VerifyArgs a)
   if (is_target ? (i > g) : (i >= g)) return;          // not verified: no bytes read
 
   const void* row = is_target ? target_row<DT>(a, b, i) : draft_row<DT>(a, b, i);
-  Online acc;
-  acc.init();
-  if (row) sweep_online<DT>(row, a.V, acc);
-  const MS ms = block_merge(acc, sm);
+  Online acc[1];
+  acc[0].init();
+  if (row) sweep_online<DT>(row, a.V, acc[0]);
+  MS merged[1];
+  block_merge<1>(acc, sm, merged);
+  const MS ms = merged[0];
   if (threadIdx.x == 0) {
     float zx = __builtin_nanf("");
     if (i < a.k && row) {
