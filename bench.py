@@ -141,7 +141,7 @@ def main():
 
     # ---- the same K steps again with hipEvents around every kernel launch
     hip = Hip()
-    names = {Bd.SV_KERNEL_ROW_STATS: "row_stats_kernel", Bd.SV_KERNEL_ACCEPT_ESTIMATE: "accept_estimate_kernel",
+    names = {Bd.SV_KERNEL_ROW_STATS: "row_stats_stash_kernel", Bd.SV_KERNEL_ACCEPT_ESTIMATE: "accept_estimate_kernel",
              Bd.SV_KERNEL_SELECT_LENGTH: "select_batch_kernel", Bd.SV_KERNEL_VERIFY_ROWS: "verify_rows_kernel",
              Bd.SV_KERNEL_VERIFY_MASS: "verify_mass_kernel", Bd.SV_KERNEL_VERIFY_PICK: "verify_pick_kernel"}
     ev = {kid: [(hip.event(), hip.event()) for _ in range(args.steps)] for kid in names}
@@ -162,7 +162,7 @@ def main():
     row_bytes = V * eb
     verify_rows = B * (2 * k + 1)
     stats_rows = 2 * B * k
-    alg = {"verify_rows_kernel": verify_rows * row_bytes, "row_stats_kernel": stats_rows * row_bytes,
+    alg = {"verify_rows_kernel": verify_rows * row_bytes, "row_stats_stash_kernel": stats_rows * row_bytes,
            "verify_mass_kernel": 0, "verify_pick_kernel": 0, "accept_estimate_kernel": 0,
            "select_batch_kernel": 0}
     kernels = {}
