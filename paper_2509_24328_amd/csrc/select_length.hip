@@ -14,6 +14,12 @@
 #include "sv_device.hpp"
 #include "sv_host.hpp"
 
+// Phase marks: empty in the library; a profiling build may define
+// SV_PHASE_MARK(n) to record a clock at the boundaries of the kernel's phases.
+#ifndef SV_PHASE_MARK
+#define SV_PHASE_MARK(n)
+#endif
+
 namespace sv {
 
 constexpr int kSelThreads = 1024;
@@ -62,14 +68,14 @@ __global__ __launch_bounds__(kSelThreads) void select_batch_kernel(
     int32_t* total_M) {
   __shared__ double key_c[kSelMax];     // sort keys, later the running sums E_M
   __shared__ int key_i[kSelMax];        // first the raw estimates (as float bits), then key indices
-  __shared__ int cnt[kSelMax];          // selected tokens per sequence
   __shared__ int part[kSelThreads];
   __shared__ int m_star;
   const int tid = threadIdx.x, nt = blockDim.x;
   const int n = B * k;
-  int npad = 16;                       // a power of two >= max(n, 16)
+  int npad = kWave;                    // a power of two >= max(n, 64)
   while (npad < n) npad <<= 1;
 
+  SV_PHASE_MARK(0)
   // estimates into LDS with one round of coalesced loads
   float* p_lds = reinterpret_cast<float*>(key_i);
   for (int j = tid; j < n; j += nt) p_lds[j] = p_hat[j];
@@ -80,7 +86,6 @@ __global__ __launch_bounds__(kSelThreads) void select_batch_kernel(
       acc = acc * clean_p(p_lds[b * k + j]);
       key_c[b * k + j] = acc;
     }
-    cnt[b] = 0;
   }
   __syncthreads();
   for (int j = tid; j < npad; j += nt) {
@@ -89,6 +94,7 @@ __global__ __launch_bounds__(kSelThreads) void select_batch_kernel(
   if (tid == 0) m_star = n;
   __syncthreads();
 
+  SV_PHASE_MARK(1)
   // bitonic sort, "before" order ascending in position
   if (npad <= nt) {
     // one key per lane, held in registers: partners closer than a wavefront are
@@ -134,33 +140,87 @@ __global__ __launch_bounds__(kSelThreads) void select_batch_kernel(
     }
   }
 
-  // E_M in selection order, one lane: key_c[M-1] becomes E_M.  The padding keys
-  // sort last, so running over whole batches of 16 never touches E_1..E_n.
-  if (tid == 0) {
-    double E = 0.0;
-    for (int j0 = 0; j0 < npad; j0 += 16) {   // batches of loads keep LDS latency off the add chain
-      double v[16];
+  SV_PHASE_MARK(2)
+  // First peak of the estimated goodput G_M = E_M / latency[M], G_0 = 0:
+  // M* = first M >= 0 with not (G_{M+1} > G_M).  E_M is DEFINED as the running
+  // sum in selection order (fp64, one addition after another), so that the
+  // integer outputs do not depend on a reduction tree.  Fast path: a parallel
+  // scan gives sums E'_M that differ from E_M by at most 2 n u E_M (all terms are
+  // non-negative, u = 2^-53); wherever |G'_{M+1} - G'_M| exceeds the resulting
+  // bound the comparison is already decided.  Only if an undecided comparison
+  // comes before the first decided stop does one lane run the ordered sum.
+  bool need_exact = npad > nt;                     // more than one key per lane: no fast path
+  if (!need_exact) {
+    __shared__ double wave_tot[kSelThreads / kWave];
+    __shared__ double wave_last_g[kSelThreads / kWave];
+    __shared__ int first_stop, first_open;
+    if (tid == 0) { first_stop = n; first_open = n; }
+    const int lane = tid & (kWave - 1), wave = tid >> 6;
+    double e = (tid < n) ? key_c[tid] : 0.0;       // inclusive scan: e becomes E'_{tid+1}
 #pragma unroll
-      for (int q = 0; q < 16; ++q) v[q] = key_c[j0 + q];
+    for (int off = 1; off < kWave; off <<= 1) {
+      int lo = __double2loint(e), hi = __double2hiint(e);
+      lo = __shfl_up(lo, off, kWave);
+      hi = __shfl_up(hi, off, kWave);
+      if (lane >= off) e += __hiloint2double(hi, lo);
+    }
+    if (lane == kWave - 1) wave_tot[wave] = e;
+    __syncthreads();
+    for (int w = 0; w < wave; ++w) e += wave_tot[w];
+    const double g_nxt = (tid < n) ? e / (double)latency[tid + 1] : 0.0;    // G'_{tid+1}
+    if (lane == kWave - 1) wave_last_g[wave] = g_nxt;
+    __syncthreads();
+    int lo = __double2loint(g_nxt), hi = __double2hiint(g_nxt);
+    lo = __shfl_up(lo, 1, kWave);
+    hi = __shfl_up(hi, 1, kWave);
+    double g_cur = __hiloint2double(hi, lo);                                 // G'_{tid}
+    if (lane == 0) g_cur = (wave == 0) ? 0.0 : wave_last_g[wave - 1];
+    if (tid < n) {
+      const double bound = 8.0 * (double)(n + 2) * 1.1102230246251565e-16 * fmax(g_nxt, g_cur);
+      const double d = g_nxt - g_cur;
+      if (d < -bound) atomicMin(&first_stop, tid);
+      else if (!(d > bound)) atomicMin(&first_open, tid);                    // undecided (or NaN)
+    }
+    __syncthreads();
+    if (first_open < first_stop) need_exact = true;  // block-uniform
+    else if (tid == 0) m_star = first_stop;
+  }
+  SV_PHASE_MARK(3)
+  if (need_exact) {
+    // ordered sum by one lane: key_c[M-1] becomes E_M.  The padding keys sort
+    // last, so running over whole batches of 16 never touches E_1..E_n.
+    __syncthreads();
+    if (tid == 0) {
+      double E = 0.0;
+      for (int j0 = 0; j0 < npad; j0 += 16) {   // batches of loads keep LDS latency off the add chain
+        double v[16];
 #pragma unroll
-      for (int q = 0; q < 16; ++q) { E += v[q]; v[q] = E; }
+        for (int q = 0; q < 16; ++q) v[q] = key_c[j0 + q];
 #pragma unroll
-      for (int q = 0; q < 16; ++q) key_c[j0 + q] = v[q];
+        for (int q = 0; q < 16; ++q) { E += v[q]; v[q] = E; }
+#pragma unroll
+        for (int q = 0; q < 16; ++q) key_c[j0 + q] = v[q];
+      }
+    }
+    __syncthreads();
+    for (int M = tid; M < n; M += nt) {
+      const double g_cur = (M == 0) ? 0.0 : key_c[M - 1] / (double)latency[M];
+      const double g_nxt = key_c[M] / (double)latency[M + 1];
+      if (!(g_nxt > g_cur)) atomicMin(&m_star, M);
     }
   }
   __syncthreads();
-  // goodput G_M = E_M / latency[M]; M* = first M >= 0 with not (G_{M+1} > G_M)
-  for (int M = tid; M < n; M += nt) {
-    const double g_cur = (M == 0) ? 0.0 : key_c[M - 1] / (double)latency[M];
-    const double g_nxt = key_c[M] / (double)latency[M + 1];
-    if (!(g_nxt > g_cur)) atomicMin(&m_star, M);
-  }
-  __syncthreads();
+  SV_PHASE_MARK(4)
   const int M = m_star;
+  int* cnt = reinterpret_cast<int*>(key_c);      // the keys are dead: selected tokens per sequence
+  for (int b = tid; b < B; b += nt) cnt[b] = 0;
+  __syncthreads();
   for (int r = tid; r < M; r += nt) atomicAdd(&cnt[key_i[r] / k], 1);
   if (tid == 0) *total_M = M;
   __syncthreads();
+  SV_PHASE_MARK(5)
   offsets_scan(cnt, B, gamma, t_offsets, part);
+  SV_PHASE_MARK(6)
 }
 
 __global__ __launch_bounds__(kSelThreads) void select_per_sequence_kernel(

@@ -217,18 +217,34 @@ __device__ __forceinline__ double kappa_l32(const MS& r) {
   return (double)ref_of(r.m) + log2(r.s);
 }
 
+// Fold the `split` partial normalisers of one row (consecutive entries).
+__device__ __forceinline__ MS fold_parts(const float* m, const double* s, int split) {
+  MS r;
+  r.m = m[0];
+  for (int p = 1; p < split; ++p) r.m = fmaxf(r.m, m[p]);
+  const float cr = ref_of(r.m);
+  r.s = 0.0;
+  for (int p = 0; p < split; ++p) r.s += s[p] * (double)exp2_fast(ref_of(m[p]) - cr);
+  return r;
+}
+
 // ---------------------------------------------------------------------------
-// Sweep of one row: online accumulation by the whole workgroup.
+// Sweep of part `part` of `split` of one row: online accumulation by the whole
+// workgroup.  Parts are contiguous runs of whole 16-byte vectors (the last one
+// also takes the scalar tail); rows that do not start on 16 bytes are split by
+// elements and read with scalar loads.
 // ---------------------------------------------------------------------------
 template <int DT>
-__device__ __forceinline__ void sweep_online(const void* row, int V, Online& acc) {
+__device__ __forceinline__ void sweep_online(const void* row, int V, int part, int split, Online& acc) {
   constexpr int EPV = Elem<DT>::per_vec;
   const int tid = threadIdx.x, nt = blockDim.x;
   if (aligned16(row)) {
     const u32x4* p = reinterpret_cast<const u32x4*>(row);
     const int nvec = V / EPV;
-    int i = tid;
-    for (; i + 3 * nt < nvec; i += 4 * nt) {
+    const int per = (nvec + split - 1) / split;
+    const int end = min(nvec, (part + 1) * per);
+    int i = part * per + tid;
+    for (; i + 3 * nt < end; i += 4 * nt) {
       const u32x4 q0 = __builtin_nontemporal_load(p + i);
       const u32x4 q1 = __builtin_nontemporal_load(p + i + nt);
       const u32x4 q2 = __builtin_nontemporal_load(p + i + 2 * nt);
@@ -239,15 +255,18 @@ __device__ __forceinline__ void sweep_online(const void* row, int V, Online& acc
       unpack<DT>(q2, f); acc.add(f);
       unpack<DT>(q3, f); acc.add(f);
     }
-    for (; i < nvec; i += nt) {
+    for (; i < end; i += nt) {
       const u32x4 q = __builtin_nontemporal_load(p + i);
       float f[EPV];
       unpack<DT>(q, f);
       acc.add(f);
     }
-    for (int v = nvec * EPV + tid; v < V; v += nt) acc.add1(load_elem<DT>(row, v));
+    if (part == split - 1)
+      for (int v = nvec * EPV + tid; v < V; v += nt) acc.add1(load_elem<DT>(row, v));
   } else {
-    for (int v = tid; v < V; v += nt) acc.add1(load_elem<DT>(row, v));
+    const int per = (V + split - 1) / split;
+    const int end = min(V, (part + 1) * per);
+    for (int v = part * per + tid; v < end; v += nt) acc.add1(load_elem<DT>(row, v));
   }
 }
 

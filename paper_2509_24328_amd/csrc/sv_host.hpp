@@ -14,6 +14,7 @@ struct Plan;
 
 constexpr int kChunk = 8192;          // vocabulary entries per sampling chunk
 constexpr size_t kWsAlign = 256;
+constexpr int kMaxSplit = 8;          // a row may be swept by up to 8 workgroups
 
 inline hipStream_t as_stream(sv_stream_t s) { return reinterpret_cast<hipStream_t>(s); }
 
@@ -25,10 +26,10 @@ inline int n_chunks(int V) { return (V + kChunk - 1) / kChunk; }
 
 // Workspace carve-up for sv_verify_sample.  All offsets are multiples of 256.
 struct VerifyWs {
-  double* s_t;        // [B*(k+1)] sum relative to c(m) of each target row
-  double* s_d;        // [B*k]     same for draft rows
-  float* m_t;         // [B*(k+1)] row maxima
-  float* m_d;         // [B*k]
+  double* s_t;        // [B*(k+1)*kMaxSplit] partial sums relative to c(m) of each target row
+  double* s_d;        // [B*k*kMaxSplit]     same for draft rows
+  float* m_t;         // [B*(k+1)*kMaxSplit] partial maxima
+  float* m_d;         // [B*k*kMaxSplit]
   float* zx_t;        // [B*k] target logit of the drafted token
   float* zx_d;        // [B*k] draft logit of the drafted token
   double* mass_r;     // [B*C] residual mass of each chunk of the sampling row
@@ -45,10 +46,10 @@ inline VerifyWs carve_verify_ws(void* base, int B, int k, int V) {
   size_t off = 0;
   const size_t rt = (size_t)B * (k + 1), rd = (size_t)B * k, bc = (size_t)B * n_chunks(V);
   auto take = [&](size_t bytes) { char* q = p ? p + off : nullptr; off += ws_round(bytes); return q; };
-  w.s_t = reinterpret_cast<double*>(take(rt * 8));
-  w.s_d = reinterpret_cast<double*>(take(rd * 8));
-  w.m_t = reinterpret_cast<float*>(take(rt * 4));
-  w.m_d = reinterpret_cast<float*>(take(rd * 4));
+  w.s_t = reinterpret_cast<double*>(take(rt * kMaxSplit * 8));
+  w.s_d = reinterpret_cast<double*>(take(rd * kMaxSplit * 8));
+  w.m_t = reinterpret_cast<float*>(take(rt * kMaxSplit * 4));
+  w.m_d = reinterpret_cast<float*>(take(rd * kMaxSplit * 4));
   w.zx_t = reinterpret_cast<float*>(take(rd * 4));
   w.zx_d = reinterpret_cast<float*>(take(rd * 4));
   w.mass_r = reinterpret_cast<double*>(take(bc * 8));

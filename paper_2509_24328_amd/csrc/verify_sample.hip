@@ -2,27 +2,32 @@
 // prefix of every sequence (Sec. 4.2 last paragraph of the SV paper; the
 // accept / residual / bonus rule is the standard speculative-sampling one).
 //
-// Three kernels on the caller's stream:
+// Four kernels on the caller's stream:
 //
-//  1. verify_rows_kernel   one workgroup per logit row that the step needs
+//  1. verify_rows_kernel   1..8 workgroups per logit row that the step needs
 //     (target rows 0..gamma_b, draft rows 0..gamma_b-1 of every sequence).
-//     Streams the row once with 128-bit loads and keeps a per-lane online
-//     (max, sum-exp); writes the row's (m, s) and the logit of the drafted
-//     token.  Rows outside the verification length exit without reading.
-//     HBM-bound: V * elem_size bytes per row.
+//     Each streams its part of the row once with 128-bit loads and keeps a
+//     per-lane online (max, sum-exp); writes the part's (m, s) and the logit
+//     of the drafted token.  Rows outside the verification length exit without
+//     reading.  HBM-bound: V * elem_size bytes per row.
 //
-//  2. verify_mass_kernel   grid (chunks, B).  Every workgroup re-derives the
-//     sequence's accept count from the row scalars in fp64 (k <= 64 positions,
-//     one wavefront), then sums its 8192-entry chunk of the sampling row:
-//     residual max(0, P_t - P_d) and P_t.  Touches B rows (pairs) only.
+//  2. verify_accept_kernel  one wavefront per sequence, one lane per drafted
+//     position (k <= 64): folds the row partials, forms the acceptance ratios
+//     in fp64, draws the Philox uniforms, counts the leading accepts and
+//     writes the accepted tokens and the plan of the sampling stage.
 //
-//  3. verify_pick_kernel   one workgroup per sequence: scans the chunk masses in
+//  3. verify_mass_kernel   grid (chunks, B): sums its 8192-entry chunk of the
+//     sampling row: residual max(0, P_t - P_d) and P_t.  Touches B rows (pairs).
+//
+//  4. verify_pick_kernel   one workgroup per sequence: scans the chunk masses in
 //     order (fp64), locates the chunk holding u' * W, stages that chunk's
 //     weights in LDS and finds the token with a block prefix scan.
 //
-// Kernel boundaries carry the cross-workgroup hand-offs (row scalars, chunk
-// masses): device-scope fences inside a kernel were measured to cost far more
-// than a launch on this part.
+// Kernel boundaries carry the cross-workgroup hand-offs (row scalars, plan,
+// chunk masses): device-scope fences inside a kernel were measured to cost far
+// more than a launch on this part.
+#include <algorithm>
+
 #include "sv_device.hpp"
 #include "sv_host.hpp"
 
@@ -41,6 +46,7 @@ struct VerifyArgs {
   const int32_t* x;
   const int32_t* gamma;       // nullable
   int B, k, V;
+  int split;                  // workgroups per row in verify_rows_kernel
   uint32_t seed_lo, seed_hi, step;
   int32_t* out_tokens;
   int32_t* n_accept;
@@ -72,6 +78,16 @@ __device__ __forceinline__ const void* draft_row(const VerifyArgs& a, int b, int
   return static_cast<const char*>(a.z_d) + ((size_t)b * a.k + i) * a.V * Elem<DT>::bytes;
 }
 
+// Normaliser of a whole row from the partials its workgroups left.
+__device__ __forceinline__ MS target_ms(const VerifyArgs& a, int b, int i) {
+  const int idx = (b * (a.k + 1) + i) * a.split;
+  return fold_parts(a.ws.m_t + idx, a.ws.s_t + idx, a.split);
+}
+__device__ __forceinline__ MS draft_ms(const VerifyArgs& a, int b, int i) {
+  const int idx = (b * a.k + i) * a.split;
+  return fold_parts(a.ws.m_d + idx, a.ws.s_d + idx, a.split);
+}
+
 // ---------------------------------------------------------------------------
 // kernel 1: row normalisers
 // ---------------------------------------------------------------------------
@@ -79,8 +95,10 @@ template <int DT>
 __global__ __launch_bounds__(kRowsThreads) void verify_rows_kernel(VerifyArgs a) {
   __shared__ MergeScratch<1> sm;
   const int per_seq = 2 * a.k + 1;
-  const int b = blockIdx.x / per_seq;
-  const int r = blockIdx.x - b * per_seq;
+  const int slot = blockIdx.x / a.split;
+  const int part = blockIdx.x - slot * a.split;
+  const int b = slot / per_seq;
+  const int r = slot - b * per_seq;
   const bool is_target = r <= a.k;
   const int i = is_target ? r : r - (a.k + 1);
   const int g = gamma_of(a, b);
@@ -89,26 +107,26 @@ __global__ __launch_bounds__(kRowsThreads) void verify_rows_kernel(VerifyArgs a)
   const void* row = is_target ? target_row<DT>(a, b, i) : draft_row<DT>(a, b, i);
   Online acc[1];
   acc[0].init();
-  if (row) sweep_online<DT>(row, a.V, acc[0]);
+  if (row) sweep_online<DT>(row, a.V, part, a.split, acc[0]);
   MS merged[1];
   block_merge<1>(acc, sm, merged);
   const MS ms = merged[0];
   if (threadIdx.x == 0) {
     float zx = __builtin_nanf("");
-    if (i < a.k && row) {
+    if (part == 0 && i < a.k && row) {
       const int tok = a.x[b * a.k + i];
       if (tok >= 0 && tok < a.V) zx = load_elem<DT>(row, tok);
     }
     if (is_target) {
-      const int idx = b * (a.k + 1) + i;
+      const int idx = (b * (a.k + 1) + i) * a.split + part;
       a.ws.m_t[idx] = ms.m;
       a.ws.s_t[idx] = ms.s;                 // s = 0 for a missing row => bad row
-      if (i < a.k) a.ws.zx_t[b * a.k + i] = zx;
+      if (part == 0 && i < a.k) a.ws.zx_t[b * a.k + i] = zx;
     } else {
-      const int idx = b * a.k + i;
+      const int idx = (b * a.k + i) * a.split + part;
       a.ws.m_d[idx] = ms.m;
       a.ws.s_d[idx] = ms.s;
-      a.ws.zx_d[idx] = zx;
+      if (part == 0) a.ws.zx_d[b * a.k + i] = zx;
     }
   }
 }
@@ -141,7 +159,7 @@ struct ProbRow {
 // their own contiguous 32-entry segments hit different banks.
 __device__ __forceinline__ int skew(int p) { return p + (p >> 5); }
 
-// What the pick kernel needs to know about a sequence, written by the mass kernel.
+// What the sampling stage needs to know about a sequence, written by the accept kernel.
 struct alignas(16) Plan {
   double lse_t, lse_d;
   int n;               // accepted count = position that is sampled
@@ -152,92 +170,86 @@ struct alignas(16) Plan {
 
 static_assert(sizeof(Plan) == 32, "workspace carve-up reserves 32 bytes per sequence");
 
+// grid (B), one wavefront: accept count of the sequence in fp64 (one lane per
+// drafted position, k <= 64), its flags, and the plan for the sampling stage.
+template <int DT>
+__global__ __launch_bounds__(kWave) void verify_accept_kernel(VerifyArgs a) {
+  const int b = blockIdx.x;
+  const int i = threadIdx.x;
+  const int k = a.k, V = a.V;
+  const int g = gamma_of(a, b);
+  const bool evaluated = i < g;
+  bool accept = true;
+  uint32_t fl = 0;
+  double rho = __builtin_nan("");
+  double lse_t = __builtin_nan(""), lse_d = __builtin_nan("");
+  bool have_target = false;
+  if (i <= g) {                                   // target rows 0..g (row g: bonus position)
+    have_target = target_row<DT>(a, b, i) != nullptr;
+    lse_t = lse_from_ms(target_ms(a, b, i));
+  }
+  if (evaluated) {
+    lse_d = lse_from_ms(draft_ms(a, b, i));
+    const int tok = a.x[b * k + i];
+    if (tok < 0 || tok >= V) {
+      fl |= SV_FLAG_BAD_TOKEN;
+    } else if (isnan(lse_t) || isnan(lse_d)) {
+      fl |= SV_FLAG_BAD_ROW;
+    } else {
+      const double lt = (double)a.ws.zx_t[b * k + i] - lse_t;
+      const double ld = (double)a.ws.zx_d[b * k + i] - lse_d;
+      rho = exp(lt - ld);                         // -inf - -inf = NaN: rejected
+    }
+    const U4 r = philox4x32_10((uint32_t)i, (uint32_t)b, 0u, a.step, a.seed_lo, a.seed_hi);
+    const double u = unit_from_word(r.w[0]);
+    accept = u < rho;                             // false for NaN
+    if (!isnan(rho) && fabs(u - fmin(1.0, rho)) < 1e-6) fl |= SV_FLAG_NEAR_TIE;
+  }
+  const unsigned long long rej = __ballot(evaluated && !accept);
+  const int n = rej ? (int)__builtin_ctzll(rej) : g;          // leading accepts
+  // flags of the positions that were actually evaluated: 0..min(n, g-1)
+  if (!(evaluated && i <= n)) fl = 0;
+  for (int off = 32; off >= 1; off >>= 1) fl |= __shfl_xor(fl, off, kWave);
+  if (a.ratio && i < k) a.ratio[b * k + i] = (evaluated && i <= n) ? (float)rho : __builtin_nanf("");
+  int32_t* out = a.out_tokens + (size_t)b * (k + 1);
+  for (int j = i; j <= k; j += kWave) out[j] = (j < n) ? a.x[b * k + j] : -1;
+  if (i == n) {                                   // the lane of the sampled position writes the plan
+    uint32_t flags = fl;
+    bool resid = n < g;
+    const bool target_ok = have_target && !isnan(lse_t);
+    if (resid && isnan(lse_d)) {                  // unusable draft row: draw from the target instead
+      resid = false;
+      flags |= SV_FLAG_BAD_ROW | SV_FLAG_RESIDUAL_FALLBACK;
+    }
+    if (!target_ok) flags |= SV_FLAG_BAD_ROW;
+    Plan pl;
+    pl.lse_t = lse_t; pl.lse_d = resid ? lse_d : 0.0; pl.n = n; pl.flags = flags;
+    pl.resid = resid ? 1 : 0; pl.target_ok = target_ok ? 1 : 0;
+    a.ws.plan[b] = pl;
+    a.n_accept[b] = n;
+  }
+}
+
 struct MassShared {
   BlockScratch red;
-  int n;
-  uint32_t flags;
 };
 
-// grid (chunks, B): accept count (re-derived per workgroup: k <= 64 positions,
-// one wavefront, fp64) and the mass of one chunk of the sampling row.
+// grid (chunks, B): residual and target mass of one chunk of the sampling row.
 template <int DT>
 __global__ __launch_bounds__(kSampleThreads) void verify_mass_kernel(VerifyArgs a) {
   __shared__ MassShared sh;
   const int b = blockIdx.y, c = blockIdx.x, C = gridDim.x;
   const int tid = threadIdx.x;
-  const int k = a.k, V = a.V;
-  const int g = gamma_of(a, b);
-
-  // ---- accept count: one lane per drafted position, wavefront 0 ----------
-  if (tid < kWave) {
-    const int i = tid;
-    bool evaluated = i < g;
-    bool accept = true;
-    uint32_t fl = 0;
-    double rho = __builtin_nan("");
-    if (evaluated) {
-      const MS mt{a.ws.m_t[b * (k + 1) + i], a.ws.s_t[b * (k + 1) + i]};
-      const MS md{a.ws.m_d[b * k + i], a.ws.s_d[b * k + i]};
-      const double lse_t = lse_from_ms(mt), lse_d = lse_from_ms(md);
-      const int tok = a.x[b * k + i];
-      if (tok < 0 || tok >= V) {
-        fl |= SV_FLAG_BAD_TOKEN;
-      } else if (isnan(lse_t) || isnan(lse_d)) {
-        fl |= SV_FLAG_BAD_ROW;
-      } else {
-        const double lt = (double)a.ws.zx_t[b * k + i] - lse_t;
-        const double ld = (double)a.ws.zx_d[b * k + i] - lse_d;
-        rho = exp(lt - ld);        // -inf - -inf = NaN: rejected
-      }
-      const U4 r = philox4x32_10((uint32_t)i, (uint32_t)b, 0u, a.step, a.seed_lo, a.seed_hi);
-      const double u = unit_from_word(r.w[0]);
-      accept = u < rho;            // false for NaN
-      if (!isnan(rho) && fabs(u - fmin(1.0, rho)) < 1e-6) fl |= SV_FLAG_NEAR_TIE;
-    }
-    const unsigned long long rej = __ballot(evaluated && !accept);
-    const int n = rej ? (int)__builtin_ctzll(rej) : g;       // leading accepts
-    // flags of the positions that were actually evaluated: 0..min(n, g-1)
-    if (!(evaluated && i <= n)) fl = 0;
-    for (int off = 32; off >= 1; off >>= 1) fl |= __shfl_xor(fl, off, kWave);
-    if (c == 0 && a.ratio && i < k) a.ratio[b * k + i] = (evaluated && i <= n) ? (float)rho : __builtin_nanf("");
-    if (tid == 0) { sh.n = n; sh.flags = fl; }
-  }
-  __syncthreads();
-  const int n = sh.n;
-  uint32_t flags = sh.flags;
-
-  // ---- sampling row and its normalisers -----------------------------------
+  const int V = a.V;
+  const Plan pl = a.ws.plan[b];
+  const int n = pl.n;
+  const bool target_ok = pl.target_ok != 0, resid = pl.resid != 0;
   const void* row_t = target_row<DT>(a, b, n);
-  bool resid = n < g;
   const void* row_d = resid ? draft_row<DT>(a, b, n) : nullptr;
-  const double lse_t = lse_from_ms(MS{a.ws.m_t[b * (k + 1) + n], a.ws.s_t[b * (k + 1) + n]});
-  double lse_d = 0.0;
-  const bool target_ok = row_t && !isnan(lse_t);
   ProbRow pt, pd;
-  pt.set(target_ok ? lse_t : 0.0);
-  if (resid) {
-    lse_d = lse_from_ms(MS{a.ws.m_d[b * k + n], a.ws.s_d[b * k + n]});
-    if (isnan(lse_d)) {            // unusable draft row: draw from the target instead
-      resid = false;
-      flags |= SV_FLAG_BAD_ROW | SV_FLAG_RESIDUAL_FALLBACK;
-    } else {
-      pd.set(lse_d);
-    }
-  }
-  if (!target_ok) flags |= SV_FLAG_BAD_ROW;
-  if (c == 0) {
-    if (tid == 0) {
-      Plan pl;
-      pl.lse_t = lse_t; pl.lse_d = lse_d; pl.n = n; pl.flags = flags;
-      pl.resid = resid ? 1 : 0; pl.target_ok = target_ok ? 1 : 0;
-      a.ws.plan[b] = pl;
-      a.n_accept[b] = n;
-    }
-    int32_t* out = a.out_tokens + (size_t)b * (k + 1);
-    for (int i = tid; i <= k; i += blockDim.x) out[i] = (i < n) ? a.x[b * k + i] : -1;
-  }
+  pt.set(target_ok ? pl.lse_t : 0.0);
+  pd.set(pl.lse_d);
 
-  // ---- mass of this chunk --------------------------------------------------
   const int v0 = c * kChunk, v1 = min(V, v0 + kChunk);
   float acc_r = 0.f, acc_t = 0.f;
   if (target_ok) {
@@ -411,12 +423,26 @@ __global__ __launch_bounds__(kSampleThreads) void verify_pick_kernel(VerifyArgs 
   a.flags[b] = fl;
 }
 
+// Workgroups per row: enough of them to spread the rows evenly over the CUs
+// (1088 rows on 256 CUs leave some CUs a fifth more work than others), but
+// never parts shorter than 8192 entries.
+static int rows_split(int rows, int V) {
+  int s = (4096 + rows - 1) / rows;
+  s = std::min(s, std::max(1, V / 8192));
+  return std::max(1, std::min(s, kMaxSplit));
+}
+
 template <int DT>
 static int launch_verify(const VerifyArgs& a, hipStream_t st) {
   const int rows = a.B * (2 * a.k + 1);
   {
     TapScope tap(SV_KERNEL_VERIFY_ROWS, st);
-    hipLaunchKernelGGL(verify_rows_kernel<DT>, dim3(rows), dim3(kRowsThreads), 0, st, a);
+    hipLaunchKernelGGL(verify_rows_kernel<DT>, dim3(rows * a.split), dim3(kRowsThreads), 0, st, a);
+  }
+  if (launch_status() != SV_OK) return SV_ERR_LAUNCH;
+  {
+    TapScope tap(SV_KERNEL_VERIFY_ACCEPT, st);
+    hipLaunchKernelGGL(verify_accept_kernel<DT>, dim3(a.B), dim3(kWave), 0, st, a);
   }
   if (launch_status() != SV_OK) return SV_ERR_LAUNCH;
   const int C = n_chunks(a.V);
@@ -443,7 +469,7 @@ extern "C" int sv_verify_sample(const void* z_t, const int32_t* t_offsets_or_nul
   SV_REQUIRE(dtype == SV_F32 || dtype == SV_BF16, SV_ERR_DTYPE);
   SV_REQUIRE(B >= 0 && k >= 1 && V >= 1, SV_ERR_INVALID_ARG);
   SV_REQUIRE(k <= SV_MAX_K && n_chunks(V) <= kMaxChunks, SV_ERR_TOO_LARGE);
-  SV_REQUIRE((long long)B * (2 * k + 1) <= 0x7fffffffLL && B <= 65535, SV_ERR_TOO_LARGE);
+  SV_REQUIRE((long long)B * (2 * k + 1) * kMaxSplit <= 0x7fffffffLL && B <= 65535, SV_ERR_TOO_LARGE);
   if (B == 0) return SV_OK;
   SV_REQUIRE(z_t && z_d && x && out_tokens && n_accept && flags, SV_ERR_NULL);
   SV_REQUIRE(!t_offsets_or_null || n_t_rows >= 0, SV_ERR_INVALID_ARG);
@@ -459,6 +485,7 @@ extern "C" int sv_verify_sample(const void* z_t, const int32_t* t_offsets_or_nul
   a.z_t = z_t; a.t_offsets = t_offsets_or_null; a.n_t_rows = n_t_rows;
   a.z_d = z_d; a.x = x; a.gamma = gamma_or_null;
   a.B = B; a.k = k; a.V = V;
+  a.split = rows_split(B * (2 * k + 1), V);
   a.seed_lo = (uint32_t)(seed & 0xffffffffu); a.seed_hi = (uint32_t)(seed >> 32); a.step = step;
   a.out_tokens = out_tokens; a.n_accept = n_accept; a.flags = flags; a.ratio = ratio_or_null;
   a.ws = carve_verify_ws(ws, B, k, V);
