@@ -24,15 +24,29 @@ __device__ __forceinline__ bool near_edge(float v, const float* edges, int n) {
   return false;
 }
 
+constexpr int kEdgeLds = 1024;    // edges of both axes kept in LDS when they fit
+
 __global__ void accept_estimate_kernel(const float* S, const float* A, int n,
                                        const float* edges_s, int n_s,
                                        const float* edges_a, int n_a,
                                        const float* table, float* p_hat, uint8_t* edge_flag) {
+  // the edge arrays are walked by every lane: fetch them once, in one round of
+  // loads together with S and A, instead of one dependent load per edge
+  __shared__ float e_lds[kEdgeLds];
   const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  const bool in_lds = n_s + n_a + 2 <= kEdgeLds;
+  float s = 0.f, a = 0.f;
+  if (j < n) { s = S[j]; a = A[j]; }
+  if (in_lds) {
+    for (int t = threadIdx.x; t < n_s + n_a + 2; t += blockDim.x)
+      e_lds[t] = (t <= n_s) ? edges_s[t] : edges_a[t - n_s - 1];
+    __syncthreads();
+  }
   if (j >= n) return;
-  const float s = S[j], a = A[j];
-  p_hat[j] = table[bin_of(s, edges_s, n_s) * n_a + bin_of(a, edges_a, n_a)];
-  if (edge_flag) edge_flag[j] = (near_edge(s, edges_s, n_s) || near_edge(a, edges_a, n_a)) ? 1 : 0;
+  const float* es = in_lds ? e_lds : edges_s;
+  const float* ea = in_lds ? e_lds + n_s + 1 : edges_a;
+  p_hat[j] = table[bin_of(s, es, n_s) * n_a + bin_of(a, ea, n_a)];
+  if (edge_flag) edge_flag[j] = (near_edge(s, es, n_s) || near_edge(a, ea, n_a)) ? 1 : 0;
 }
 
 }  // namespace sv

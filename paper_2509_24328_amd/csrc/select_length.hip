@@ -24,6 +24,7 @@ namespace sv {
 
 constexpr int kSelThreads = 1024;
 constexpr int kSelMax = SV_SELECT_MAX_KEYS;   // power of two
+constexpr int kMergeMax = kSelMax / 2;         // keys sorted by pairwise merging (upper half = second buffer)
 
 __device__ __forceinline__ double clean_p(float p) {
   if (isnan(p)) return 0.0;
@@ -95,34 +96,39 @@ __global__ __launch_bounds__(kSelThreads) void select_batch_kernel(
   __syncthreads();
 
   SV_PHASE_MARK(1)
-  // bitonic sort, "before" order ascending in position
-  if (npad <= nt) {
-    // one key per lane, held in registers: partners closer than a wavefront are
-    // exchanged by lane shuffles, farther ones through LDS
-    double c = key_c[tid < npad ? tid : 0];
-    int idx = key_i[tid < npad ? tid : 0];
-    for (int size = 2; size <= npad; size <<= 1) {
-      for (int stride = size >> 1; stride > 0; stride >>= 1) {
-        double pc;
-        int pi;
-        if (stride >= kWave) {
-          __syncthreads();
-          if (tid < npad) { key_c[tid] = c; key_i[tid] = idx; }
-          __syncthreads();
-          pc = key_c[(tid ^ stride) & (npad - 1)];
-          pi = key_i[(tid ^ stride) & (npad - 1)];
-        } else {
-          pc = shfl_xor_f64(c, stride);
-          pi = __shfl_xor(idx, stride, kWave);
+  // Sort into selection order.  Every sequence's keys are already in order
+  // (c is non-increasing along a sequence), so up to kMergeMax keys are merged
+  // pairwise, list lengths k, 2k, 4k, ...: a key's new position is its position
+  // in its own list plus the number of keys of the partner list that come
+  // before it, found by binary search.  Ties between the two lists go to the
+  // left one (lower sequence indices), which is the tie order of the keys.
+  if (n <= kMergeMax) {
+    // ping-pong between the lower and the upper half of the key arrays
+    int src = 0, dst = kMergeMax;
+    for (int len = k; len < n; len <<= 1) {
+      for (int p = tid; p < n; p += nt) {
+        const int base = (p / (2 * len)) * (2 * len);
+        const int mid = min(n, base + len), end = min(n, base + 2 * len);
+        const bool left = p < mid;
+        const double c = key_c[src + p];
+        int lo = left ? mid : base, hi = left ? end : mid;
+        const int first = lo;
+        while (lo < hi) {
+          const int probe = (lo + hi) >> 1;
+          const double v = key_c[src + probe];
+          if (left ? (v > c) : (v >= c)) lo = probe + 1; else hi = probe;
         }
-        const bool up = (tid & size) == 0, lower = (tid & stride) == 0;
-        const bool mine_first = key_before(c, idx, pc, pi);
-        if ((lower == up) ? !mine_first : mine_first) { c = pc; idx = pi; }
+        const int q = base + (left ? p - base : p - mid) + (lo - first);
+        key_c[dst + q] = c;
+        key_i[dst + q] = key_i[src + p];
       }
+      __syncthreads();
+      const int t = src; src = dst; dst = t;
     }
-    __syncthreads();
-    if (tid < npad) { key_c[tid] = c; key_i[tid] = idx; }
-    __syncthreads();
+    if (src != 0) {                              // odd number of rounds: bring the result down
+      for (int p = tid; p < n; p += nt) { key_c[p] = key_c[src + p]; key_i[p] = key_i[src + p]; }
+      __syncthreads();
+    }
   } else {
     for (int size = 2; size <= npad; size <<= 1) {
       for (int stride = size >> 1; stride > 0; stride >>= 1) {
