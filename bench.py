@@ -88,6 +88,8 @@ def main():
     import numpy as np
     import torch
 
+    import __graft_entry__
+    __graft_entry__.ensure_built()          # loads what is built; builds only if nothing is
     import paper_2509_24328_amd as P
     from paper_2509_24328_amd import binding as Bd
     import svgen

@@ -144,6 +144,33 @@ constexpr int kLdsVecs = 2432;       // vector pairs parked in LDS (2 * 2432 * 1
 constexpr int kLdsIters = (kLdsVecs + kStashThreads - 1) / kStashThreads;
 constexpr size_t kStashLdsBytes = 2 * (size_t)kLdsVecs * 16;
 
+// Per-pair constants of sweep 2, formed once (fp64 log2 is ~100 instructions)
+// by lanes 0 and 1 of wavefront 0 after the merge and shared through LDS.
+struct PairConsts {
+  double lse[2];      // natural-log normalisers (NaN: bad row)
+  double kappa[2];    // L32-consistent log2 normalisers
+};
+
+// Folds the per-wavefront partials left by the first half of block_merge and
+// publishes the constants.  Must be called by all threads; ends with a barrier.
+__device__ __forceinline__ void publish_pair_consts(const Online (&on)[2], MergeScratch<2>& mg, PairConsts& pc) {
+  const int wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+#pragma unroll
+  for (int r = 0; r < 2; ++r) {
+    const float mw = wave_max_f32(on[r].m);
+    const double sw = wave_sum_f64((double)on[r].s * (double)exp2_fast(on[r].c - ref_of(mw)));
+    if ((threadIdx.x & 63) == 0) { mg.m[r][wave] = mw; mg.s[r][wave] = sw; }
+  }
+  __syncthreads();
+  if (threadIdx.x < 2) {
+    const int r = threadIdx.x;
+    const MS ms = fold_parts(mg.m[r], mg.s[r], nw);
+    pc.lse[r] = lse_from_ms(ms);
+    pc.kappa[r] = kappa_l32(ms);
+  }
+  __syncthreads();
+}
+
 // 16 bytes per lane from global memory straight into LDS: lane l of the
 // wavefront writes lds_wave_base + 16 * l (global_load_lds_dwordx4).
 __device__ __forceinline__ void load_to_lds(const u32x4* src, u32x4* lds_wave_base) {
@@ -164,6 +191,7 @@ __global__ __launch_bounds__(kStashThreads) void row_stats_stash_kernel(StatsArg
   extern __shared__ u32x4 park[];                      // [kLdsVecs] draft, then [kLdsVecs] companion
   __shared__ BlockScratch sm;
   __shared__ MergeScratch<2> mg;
+  __shared__ PairConsts consts;
   constexpr int EPV = Elem<DT>::per_vec;
   constexpr uint32_t kNegInfWord = (DT == DT_BF16) ? 0xFF80FF80u : 0xFF800000u;
   const int tid = threadIdx.x;
@@ -245,17 +273,15 @@ __global__ __launch_bounds__(kStashThreads) void row_stats_stash_kernel(StatsArg
     }
   }
   SV_PHASE_MARK(4)
-  MS merged[2];
-  block_merge<2>(on, mg, merged);
-  const MS msd = merged[0], msc = merged[1];
-  const double lse_d = lse_from_ms(msd), lse_c = lse_from_ms(msc);
+  publish_pair_consts(on, mg, consts);
+  const double lse_d = consts.lse[0], lse_c = consts.lse[1];
   const bool bad = isnan(lse_d) || isnan(lse_c);
 
   SV_PHASE_MARK(5)
   // ---- sweep 2: rest of the pair from L2/HBM (newest first), then LDS, then registers
   double S = __builtin_nan(""), KL = __builtin_nan("");
   if (!bad) {
-    const double kappa_d = kappa_l32(msd), kappa_c = kappa_l32(msc);
+    const double kappa_d = consts.kappa[0], kappa_c = consts.kappa[1];
     MinAcc<WITH_KL> acc;
     acc.kd = (float)kappa_d;
     acc.kc = (float)kappa_c;
@@ -292,9 +318,13 @@ __global__ __launch_bounds__(kStashThreads) void row_stats_stash_kernel(StatsArg
       __builtin_amdgcn_sched_barrier(0);
     }
     SV_PHASE_MARK(8)
-    const double f_d = exp2(-tail_d);
-    S = f_d * block_sum_f64((double)acc.acc_s, sm);
-    if (WITH_KL) KL = f_d * kLn2 * block_sum_f64((double)acc.acc_kl, sm);
+    S = block_sum_f64((double)acc.acc_s, sm);
+    if (WITH_KL) KL = block_sum_f64((double)acc.acc_kl, sm);
+    if (tid == 0) {
+      const double f_d = exp2(-tail_d);
+      S *= f_d;
+      KL *= f_d * kLn2;
+    }
   }
   SV_PHASE_MARK(9)
   if (tid == 0) stats_epilogue<DT, WITH_KL>(a, pair, pd, pc, lse_d, lse_c, S, KL);
@@ -304,6 +334,7 @@ template <int DT, bool WITH_KL>
 __global__ __launch_bounds__(kStatsThreads) void row_stats_kernel(StatsArgs a) {
   __shared__ BlockScratch sm;
   __shared__ MergeScratch<2> mg;
+  __shared__ PairConsts consts;
   const int pair = blockIdx.x;                       // b * k + i
   const size_t row_bytes = (size_t)a.V * Elem<DT>::bytes;
   const void* rd = static_cast<const char*>(a.z_d) + pair * row_bytes;
@@ -313,10 +344,8 @@ __global__ __launch_bounds__(kStatsThreads) void row_stats_kernel(StatsArgs a) {
   on[0].init();
   on[1].init();
   sweep_online_pair<DT>(rd, rc, a.V, on[0], on[1]);
-  MS merged[2];
-  block_merge<2>(on, mg, merged);
-  const MS msd = merged[0], msc = merged[1];
-  const double lse_d = lse_from_ms(msd), lse_c = lse_from_ms(msc);
+  publish_pair_consts(on, mg, consts);
+  const double lse_d = consts.lse[0], lse_c = consts.lse[1];
   const bool bad = isnan(lse_d) || isnan(lse_c);
 
   double S = __builtin_nan(""), KL = __builtin_nan("");
@@ -326,16 +355,20 @@ __global__ __launch_bounds__(kStatsThreads) void row_stats_kernel(StatsArgs a) {
     // P_d = f_d 2^(a_d),  P_c = f_d 2^(a_c + delta),
     // f_d = 2^(-tail_d), delta = tail_d - tail_c, so one scalar factor at the
     // end removes the rounding of both heads.
-    const double kappa_d = kappa_l32(msd), kappa_c = kappa_l32(msc);
+    const double kappa_d = consts.kappa[0], kappa_c = consts.kappa[1];
     MinAcc<WITH_KL> acc;
     acc.kd = (float)kappa_d;
     acc.kc = (float)kappa_c;
     const double tail_d = kappa_d - (double)acc.kd, tail_c = kappa_c - (double)acc.kc;
     acc.delta = (float)(tail_d - tail_c);
     visit_range<DT, true>(rd, rc, 0, a.V, [&](int, float zd, float zc) { acc.add(zd, zc); });
-    const double f_d = exp2(-tail_d);
-    S = f_d * block_sum_f64((double)acc.acc_s, sm);
-    if (WITH_KL) KL = f_d * kLn2 * block_sum_f64((double)acc.acc_kl, sm);
+    S = block_sum_f64((double)acc.acc_s, sm);
+    if (WITH_KL) KL = block_sum_f64((double)acc.acc_kl, sm);
+    if (threadIdx.x == 0) {
+      const double f_d = exp2(-tail_d);
+      S *= f_d;
+      KL *= f_d * kLn2;
+    }
   }
   if (threadIdx.x == 0) stats_epilogue<DT, WITH_KL>(a, pair, rd, rc, lse_d, lse_c, S, KL);
 }

@@ -275,7 +275,7 @@ __device__ __forceinline__ void sweep_online(const void* row, int V, int part, i
 // vocabulary index (PAIR = true) with the whole workgroup: f(v, za, zb).
 // Vector loads when both rows start on 16 bytes and v0 is a vector multiple.
 // ---------------------------------------------------------------------------
-template <int DT, bool PAIR, class F>
+template <int DT, bool PAIR, int UNROLL = 2, class F>
 __device__ __forceinline__ void visit_range(const void* a, const void* b, int v0, int v1, F&& f) {
   constexpr int EPV = Elem<DT>::per_vec;
   const int tid = threadIdx.x, nt = blockDim.x;
@@ -285,17 +285,20 @@ __device__ __forceinline__ void visit_range(const void* a, const void* b, int v0
     const u32x4* pb = reinterpret_cast<const u32x4*>(b);
     const int i1 = v1 / EPV;
     int i = v0 / EPV + tid;
-    for (; i + nt < i1; i += 2 * nt) {
-      const u32x4 qa0 = pa[i], qa1 = pa[i + nt];
-      u32x4 qb0 = qa0, qb1 = qa1;
-      if (PAIR) { qb0 = pb[i]; qb1 = pb[i + nt]; }
-      float fa[EPV], fb[EPV];
-      unpack<DT>(qa0, fa); unpack<DT>(qb0, fb);
+    for (; i + (UNROLL - 1) * nt < i1; i += UNROLL * nt) {      // UNROLL vector (pairs) in flight per lane
+      u32x4 qa[UNROLL], qb[UNROLL];
 #pragma unroll
-      for (int j = 0; j < EPV; ++j) f(i * EPV + j, fa[j], fb[j]);
-      unpack<DT>(qa1, fa); unpack<DT>(qb1, fb);
+      for (int u = 0; u < UNROLL; ++u) {
+        qa[u] = pa[i + u * nt];
+        qb[u] = PAIR ? pb[i + u * nt] : qa[u];
+      }
 #pragma unroll
-      for (int j = 0; j < EPV; ++j) f((i + nt) * EPV + j, fa[j], fb[j]);
+      for (int u = 0; u < UNROLL; ++u) {
+        float fa[EPV], fb[EPV];
+        unpack<DT>(qa[u], fa); unpack<DT>(qb[u], fb);
+#pragma unroll
+        for (int j = 0; j < EPV; ++j) f((i + u * nt) * EPV + j, fa[j], fb[j]);
+      }
     }
     for (; i < i1; i += nt) {
       const u32x4 qa = pa[i];

@@ -254,13 +254,13 @@ __global__ __launch_bounds__(kSampleThreads) void verify_mass_kernel(VerifyArgs 
   float acc_r = 0.f, acc_t = 0.f;
   if (target_ok) {
     if (resid) {
-      visit_range<DT, true>(row_t, row_d, v0, v1, [&](int, float zt, float zd) {
+      visit_range<DT, true, 4>(row_t, row_d, v0, v1, [&](int, float zt, float zd) {
         const float p = pt.p(zt);
         acc_t += p;
         acc_r += fmaxf(0.f, p - pd.p(zd));
       });
     } else {
-      visit_range<DT, false>(row_t, nullptr, v0, v1, [&](int, float zt, float) { acc_t += pt.p(zt); });
+      visit_range<DT, false, 4>(row_t, nullptr, v0, v1, [&](int, float zt, float) { acc_t += pt.p(zt); });
     }
   }
   const double mass_r = block_sum_f64((double)acc_r, sh.red);
@@ -358,11 +358,11 @@ __global__ __launch_bounds__(kSampleThreads) void verify_pick_kernel(VerifyArgs 
   const int w0 = chunk * kChunk, w1 = min(V, w0 + kChunk);
   for (int j = (w1 - w0) + tid; j < kChunk; j += blockDim.x) sh.w[skew(j)] = 0.f;
   if (use_resid) {
-    visit_range<DT, true>(row_t, row_d, w0, w1, [&](int v, float zt, float zd) {
+    visit_range<DT, true, 4>(row_t, row_d, w0, w1, [&](int v, float zt, float zd) {
       sh.w[skew(v - w0)] = fmaxf(0.f, pt.p(zt) - pd.p(zd));
     });
   } else {
-    visit_range<DT, false>(row_t, nullptr, w0, w1, [&](int v, float zt, float) { sh.w[skew(v - w0)] = pt.p(zt); });
+    visit_range<DT, false, 4>(row_t, nullptr, w0, w1, [&](int v, float zt, float) { sh.w[skew(v - w0)] = pt.p(zt); });
   }
   __syncthreads();
 

@@ -24,6 +24,10 @@ SMALL = [
     (2, 3, 2, 20000, "bf16"),     # heavy-tailed rows
     (1, 2, 5, 7, "bf16"),         # tiny vocabulary
     (0, 2, 2, 1, "f32"),          # single-entry vocabulary
+    (1, 2, 3, 8, "bf16"),         # one 16-byte vector per row (aligned path, everything in registers)
+    (0, 3, 2, 4, "f32"),          # the same for fp32
+    (3, 2, 2, 5128, "bf16"),      # aligned rows shorter than the register share of the parking kernel
+    (3, 1, 2, 131072 + 64, "bf16"),  # reaches past the register and LDS shares into the re-read region
 ]
 
 
