@@ -178,6 +178,56 @@ int sv_verify_sample(const void* z_t, const int32_t* t_offsets_or_null, int n_t_
                      float* ratio_or_null,
                      void* ws, size_t ws_bytes, sv_stream_t stream);
 
+/* ------------------------------------------------------------------------
+ * Profile construction and information gain: the offline pass that produces
+ * the table sv_accept_estimate looks up (appendix definition of the observed
+ * P(T_i | S, A); Sec. 7.3 "Information Gain from S and A", Table 1).
+ * ------------------------------------------------------------------------ */
+
+/*
+ * Acceptance ratio p_t(x)/p_d(x) of EVERY drafted position (no early stop, no
+ * sampling); X = min(1, ratio) is the acceptance probability the profile bins.
+ *   z_t   dense [B, t_rows_per_seq, V], t_rows_per_seq = k or k+1 (a bonus row,
+ *         if present, is not read);  z_d [B,k,V];  x [B,k] int32        in
+ *   ratio [B,k] float                out  NaN for bad rows / tokens
+ *   flags_or_null [B,k] uint32       out  SV_FLAG_BAD_ROW / SV_FLAG_BAD_TOKEN
+ * Same workspace as sv_verify_sample.
+ */
+int sv_accept_ratio(const void* z_t, int t_rows_per_seq, const void* z_d, const int32_t* x,
+                    int B, int k, int V, int dtype,
+                    float* ratio, uint32_t* flags_or_null,
+                    void* ws, size_t ws_bytes, sv_stream_t stream);
+
+/*
+ * Equal-count ("adaptive": smaller bins where samples are denser) edges of one
+ * axis: edges[0] = lo, edges[n_bins] = hi, edges[j] = the floor(j*m/n_bins)-th
+ * smallest (0-based) of the m non-NaN samples (lo when m = 0).
+ *   values [n] float   in;   edges [n_bins+1] float   out.   Limit: n <= 8192.
+ */
+int sv_quantile_edges(const float* values, int n, int n_bins, float lo, float hi,
+                      float* edges, sv_stream_t stream);
+
+/*
+ * Add n samples to the joint histogram counts[n_s, n_a, n_x] (uint32) and to
+ * the per-cell sums sum_x[n_s, n_a] (double) of X = clip(ratio, 0, 1).  Cells
+ * follow the bin rule of sv_accept_estimate; the X bin is
+ * min(n_x-1, floor(X * n_x)) in float32.  Samples with a NaN in S, A or ratio
+ * are skipped.  The caller zeroes counts and sum_x before the first batch.
+ * Limit: n_x <= 1024.
+ */
+int sv_profile_accumulate(const float* S, const float* A, const float* ratio, int n,
+                          const float* edges_s, int n_s, const float* edges_a, int n_a, int n_x,
+                          uint32_t* counts, double* sum_x, sv_stream_t stream);
+
+/*
+ * table[n_s, n_a] (float) = mean X of each cell, empty cells = the global mean
+ * (0 when there is no sample); info[0..2] (double) = H(X), H(X | S,A) and the
+ * information gain I(X; S,A) = H(X) - H(X | S,A), in bits, over the binned
+ * variables.
+ */
+int sv_profile_finalize(const uint32_t* counts, const double* sum_x, int n_s, int n_a, int n_x,
+                        float* table, double* info, sv_stream_t stream);
+
 /*
  * Timing taps for benchmarks (not part of the method): while a pair of
  * hipEvent_t handles is set for `kernel`, every launch of that kernel records

@@ -24,7 +24,8 @@ SV_SELECT_MAX_KEYS = 4096
 SV_MAX_K = 64
 
 EXPORTS = ("sv_strerror", "sv_workspace_bytes", "sv_row_stats", "sv_accept_estimate",
-           "sv_select_length", "sv_verify_sample", "sv_set_timing_events")
+           "sv_select_length", "sv_verify_sample", "sv_set_timing_events", "sv_accept_ratio",
+           "sv_quantile_edges", "sv_profile_accumulate", "sv_profile_finalize")
 (SV_KERNEL_ROW_STATS, SV_KERNEL_ACCEPT_ESTIMATE, SV_KERNEL_SELECT_LENGTH, SV_KERNEL_VERIFY_ROWS,
  SV_KERNEL_VERIFY_ACCEPT, SV_KERNEL_VERIFY_MASS, SV_KERNEL_VERIFY_PICK, SV_KERNEL_COUNT) = range(8)
 
@@ -47,6 +48,14 @@ lib.sv_select_length.argtypes = [_vp, _i, _i, _vp, _i, _i, _vp, _vp, _vp, _vp]
 lib.sv_verify_sample.restype = _i
 lib.sv_verify_sample.argtypes = [_vp, _vp, _i, _vp, _vp, _vp, _i, _i, _i, _i, ctypes.c_uint64,
                                  ctypes.c_uint32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+lib.sv_accept_ratio.restype = _i
+lib.sv_accept_ratio.argtypes = [_vp, _i, _vp, _vp, _i, _i, _i, _i, _vp, _vp, _vp, _sz, _vp]
+lib.sv_quantile_edges.restype = _i
+lib.sv_quantile_edges.argtypes = [_vp, _i, _i, ctypes.c_float, ctypes.c_float, _vp, _vp]
+lib.sv_profile_accumulate.restype = _i
+lib.sv_profile_accumulate.argtypes = [_vp, _vp, _vp, _i, _vp, _i, _vp, _i, _i, _vp, _vp, _vp]
+lib.sv_profile_finalize.restype = _i
+lib.sv_profile_finalize.argtypes = [_vp, _vp, _i, _i, _i, _vp, _vp, _vp]
 lib.sv_set_timing_events.restype = _i
 lib.sv_set_timing_events.argtypes = [_i, _vp, _vp]
 
@@ -124,3 +133,26 @@ def sv_verify_sample(z_t, t_offsets, z_d, x, gamma, seed, step, out_tokens, n_ac
 def sv_set_timing_events(kernel, start_event, stop_event):
     """start_event / stop_event: raw hipEvent_t handles (ints / c_void_p) or None."""
     _check(lib.sv_set_timing_events(kernel, start_event, stop_event))
+
+
+def sv_accept_ratio(z_t, z_d, x, ratio, flags=None, ws=None, stream=None):
+    B, k, V = z_d.shape
+    _check(lib.sv_accept_ratio(_ptr(z_t), z_t.shape[1], _ptr(z_d), _ptr(x), B, k, V, _dtype_tag(z_d),
+                               _ptr(ratio), _ptr(flags), _ptr(ws), 0 if ws is None else ws.numel(),
+                               _stream(stream)))
+
+
+def sv_quantile_edges(values, n_bins, lo, hi, edges, stream=None):
+    _check(lib.sv_quantile_edges(_ptr(values), values.numel(), n_bins, lo, hi, _ptr(edges), _stream(stream)))
+
+
+def sv_profile_accumulate(S, A, ratio, edges_s, edges_a, n_x, counts, sum_x, stream=None):
+    _check(lib.sv_profile_accumulate(_ptr(S), _ptr(A), _ptr(ratio), S.numel(), _ptr(edges_s),
+                                     edges_s.numel() - 1, _ptr(edges_a), edges_a.numel() - 1, n_x,
+                                     _ptr(counts), _ptr(sum_x), _stream(stream)))
+
+
+def sv_profile_finalize(counts, sum_x, table, info, stream=None):
+    n_s, n_a, n_x = counts.shape
+    _check(lib.sv_profile_finalize(_ptr(counts), _ptr(sum_x), n_s, n_a, n_x, _ptr(table), _ptr(info),
+                                   _stream(stream)))

@@ -2,29 +2,11 @@
 // (appendix definition of the observed probability in the SV paper).
 // One lane per (sequence, position); the profile table and its edges are a few
 // hundred floats and stay in cache.  Launch-latency bound.
+#include "sv_bins.hpp"
 #include "sv_device.hpp"
 #include "sv_host.hpp"
 
 namespace sv {
-
-// Half-open bins [e_j, e_{j+1}), top bin closed, outside values clamped, NaN -> 0.
-__device__ __forceinline__ int bin_of(float v, const float* edges, int n) {
-  if (isnan(v)) return 0;
-  int idx = 0;
-  for (int j = 1; j <= n; ++j)
-    if (edges[j] <= v) idx = j;
-  return min(idx, n - 1);
-}
-
-// |v - e_j| <= 1e-5 in fp32 for an interior edge, or v is NaN.
-__device__ __forceinline__ bool near_edge(float v, const float* edges, int n) {
-  if (isnan(v)) return true;
-  for (int j = 1; j < n; ++j)
-    if (fabsf(__fsub_rn(v, edges[j])) <= 1e-5f) return true;
-  return false;
-}
-
-constexpr int kEdgeLds = 1024;    // edges of both axes kept in LDS when they fit
 
 __global__ void accept_estimate_kernel(const float* S, const float* A, int n,
                                        const float* edges_s, int n_s,
@@ -34,14 +16,9 @@ __global__ void accept_estimate_kernel(const float* S, const float* A, int n,
   // loads together with S and A, instead of one dependent load per edge
   __shared__ float e_lds[kEdgeLds];
   const int j = blockIdx.x * blockDim.x + threadIdx.x;
-  const bool in_lds = n_s + n_a + 2 <= kEdgeLds;
   float s = 0.f, a = 0.f;
   if (j < n) { s = S[j]; a = A[j]; }
-  if (in_lds) {
-    for (int t = threadIdx.x; t < n_s + n_a + 2; t += blockDim.x)
-      e_lds[t] = (t <= n_s) ? edges_s[t] : edges_a[t - n_s - 1];
-    __syncthreads();
-  }
+  const bool in_lds = stage_edges(e_lds, edges_s, n_s, edges_a, n_a);
   if (j >= n) return;
   const float* es = in_lds ? e_lds : edges_s;
   const float* ea = in_lds ? e_lds + n_s + 1 : edges_a;

@@ -47,6 +47,8 @@ struct VerifyArgs {
   const int32_t* gamma;       // nullable
   int B, k, V;
   int split;                  // workgroups per row in verify_rows_kernel
+  int t_seq_rows;             // rows per sequence of a dense z_t (k + 1, or k without bonus rows)
+  int with_bonus;             // 0: target row gamma_b (bonus position) is not needed
   uint32_t seed_lo, seed_hi, step;
   int32_t* out_tokens;
   int32_t* n_accept;
@@ -68,7 +70,7 @@ __device__ __forceinline__ const void* target_row(const VerifyArgs& a, int b, in
     row = (long)a.t_offsets[b] + i;
     if (row < 0 || row >= a.n_t_rows) return nullptr;
   } else {
-    row = (long)b * (a.k + 1) + i;
+    row = (long)b * a.t_seq_rows + i;
   }
   return static_cast<const char*>(a.z_t) + (size_t)row * a.V * Elem<DT>::bytes;
 }
@@ -102,7 +104,7 @@ __global__ __launch_bounds__(kRowsThreads) void verify_rows_kernel(VerifyArgs a)
   const bool is_target = r <= a.k;
   const int i = is_target ? r : r - (a.k + 1);
   const int g = gamma_of(a, b);
-  if (is_target ? (i > g) : (i >= g)) return;          // not verified: no bytes read
+  if (i >= (is_target ? g + a.with_bonus : g)) return;   // not needed: no bytes read
 
   const void* row = is_target ? target_row<DT>(a, b, i) : draft_row<DT>(a, b, i);
   Online acc[1];
@@ -158,6 +160,31 @@ struct ProbRow {
 // LDS position of weight p: one padding word per 32 so that threads walking
 // their own contiguous 32-entry segments hit different banks.
 __device__ __forceinline__ int skew(int p) { return p + (p >> 5); }
+
+// grid (B), one wavefront: p_t(x)/p_d(x) of EVERY drafted position (profiling
+// pass: no early stop, no sampling), from the row partials of verify_rows_kernel.
+__global__ __launch_bounds__(kWave) void accept_ratio_kernel(VerifyArgs a, float* ratio, uint32_t* flags) {
+  const int b = blockIdx.x, k = a.k;
+  for (int i = threadIdx.x; i < k; i += kWave) {
+    uint32_t fl = 0;
+    double rho = __builtin_nan("");
+    const int tok = a.x[b * k + i];
+    if (tok < 0 || tok >= a.V) {
+      fl |= SV_FLAG_BAD_TOKEN;
+    } else {
+      const double lse_t = lse_from_ms(target_ms(a, b, i)), lse_d = lse_from_ms(draft_ms(a, b, i));
+      if (isnan(lse_t) || isnan(lse_d)) {
+        fl |= SV_FLAG_BAD_ROW;
+      } else {
+        const double lt = (double)a.ws.zx_t[b * k + i] - lse_t;
+        const double ld = (double)a.ws.zx_d[b * k + i] - lse_d;
+        rho = exp(lt - ld);
+      }
+    }
+    ratio[b * k + i] = (float)rho;
+    if (flags) flags[b * k + i] = fl;
+  }
+}
 
 // What the sampling stage needs to know about a sequence, written by the accept kernel.
 struct alignas(16) Plan {
@@ -486,9 +513,49 @@ extern "C" int sv_verify_sample(const void* z_t, const int32_t* t_offsets_or_nul
   a.z_d = z_d; a.x = x; a.gamma = gamma_or_null;
   a.B = B; a.k = k; a.V = V;
   a.split = rows_split(B * (2 * k + 1), V);
+  a.t_seq_rows = k + 1;
+  a.with_bonus = 1;
   a.seed_lo = (uint32_t)(seed & 0xffffffffu); a.seed_hi = (uint32_t)(seed >> 32); a.step = step;
   a.out_tokens = out_tokens; a.n_accept = n_accept; a.flags = flags; a.ratio = ratio_or_null;
   a.ws = carve_verify_ws(ws, B, k, V);
   return dtype == SV_F32 ? launch_verify<DT_F32>(a, as_stream(stream))
                          : launch_verify<DT_BF16>(a, as_stream(stream));
+}
+
+extern "C" int sv_accept_ratio(const void* z_t, int t_rows_per_seq, const void* z_d, const int32_t* x,
+                               int B, int k, int V, int dtype, float* ratio, uint32_t* flags_or_null,
+                               void* ws, size_t ws_bytes, sv_stream_t stream) {
+  using namespace sv;
+  SV_REQUIRE(dtype == SV_F32 || dtype == SV_BF16, SV_ERR_DTYPE);
+  SV_REQUIRE(B >= 0 && k >= 1 && V >= 1, SV_ERR_INVALID_ARG);
+  SV_REQUIRE(t_rows_per_seq == k || t_rows_per_seq == k + 1, SV_ERR_INVALID_ARG);
+  SV_REQUIRE((long long)B * (2 * k + 1) * kMaxSplit <= 0x7fffffffLL, SV_ERR_TOO_LARGE);
+  if (B == 0) return SV_OK;
+  SV_REQUIRE(z_t && z_d && x && ratio, SV_ERR_NULL);
+  const int eb = elem_bytes(dtype);
+  SV_REQUIRE(is_aligned(z_t, eb) && is_aligned(z_d, eb) && is_aligned(x, 4) && is_aligned(ratio, 4) &&
+                 is_aligned(flags_or_null, 4),
+             SV_ERR_ALIGN);
+  SV_REQUIRE(ws && is_aligned(ws, kWsAlign) && ws_bytes >= sv_workspace_bytes(B, k, V, dtype),
+             SV_ERR_WORKSPACE);
+  VerifyArgs a = {};
+  a.z_t = z_t; a.t_offsets = nullptr; a.n_t_rows = 0;
+  a.z_d = z_d; a.x = x; a.gamma = nullptr;
+  a.B = B; a.k = k; a.V = V;
+  a.split = rows_split(B * 2 * k, V);
+  a.t_seq_rows = t_rows_per_seq;
+  a.with_bonus = 0;
+  a.ws = carve_verify_ws(ws, B, k, V);
+  hipStream_t st = as_stream(stream);
+  const int rows = B * (2 * k + 1);               // the bonus slots exit at once
+  {
+    TapScope tap(SV_KERNEL_VERIFY_ROWS, st);
+    if (dtype == SV_F32)
+      hipLaunchKernelGGL(verify_rows_kernel<DT_F32>, dim3(rows * a.split), dim3(kRowsThreads), 0, st, a);
+    else
+      hipLaunchKernelGGL(verify_rows_kernel<DT_BF16>, dim3(rows * a.split), dim3(kRowsThreads), 0, st, a);
+  }
+  if (launch_status() != SV_OK) return SV_ERR_LAUNCH;
+  hipLaunchKernelGGL(accept_ratio_kernel, dim3(B), dim3(kWave), 0, st, a, ratio, flags_or_null);
+  return launch_status();
 }

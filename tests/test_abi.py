@@ -74,3 +74,37 @@ def test_argument_errors_are_reported_before_any_launch():
     assert sl(nl=16) == Bd.SV_ERR_INVALID_ARG
     assert sl(B=4097, k=1, nl=5000) == Bd.SV_ERR_TOO_LARGE
     assert sl(p=None) == Bd.SV_ERR_NULL
+
+
+def test_profile_pass_argument_errors():
+    L = Bd.lib
+    p = ctypes.c_void_p(256 * 1024)
+    odd = ctypes.c_void_p(256 * 1024 + 1)
+    big = 1 << 30
+    ar = lambda **kw: L.sv_accept_ratio(kw.get("zt", p), kw.get("tr", 3), p, p, 2, kw.get("k", 2), 8,
+                                        kw.get("dt", 1), kw.get("ratio", p), None, kw.get("ws", p), big, None)
+    assert ar(dt=9) == Bd.SV_ERR_DTYPE
+    assert ar(tr=5) == Bd.SV_ERR_INVALID_ARG
+    assert ar(zt=None) == Bd.SV_ERR_NULL
+    assert ar(ratio=odd) == Bd.SV_ERR_ALIGN
+    assert ar(ws=None) == Bd.SV_ERR_WORKSPACE
+    qe = lambda **kw: L.sv_quantile_edges(kw.get("v", p), kw.get("n", 10), kw.get("nb", 4),
+                                          ctypes.c_float(0), ctypes.c_float(1), kw.get("e", p), None)
+    assert qe(n=-1) == Bd.SV_ERR_INVALID_ARG
+    assert qe(nb=0) == Bd.SV_ERR_INVALID_ARG
+    assert qe(n=8193) == Bd.SV_ERR_TOO_LARGE
+    assert qe(e=None) == Bd.SV_ERR_NULL
+    assert qe(v=None) == Bd.SV_ERR_NULL
+    pa = lambda **kw: L.sv_profile_accumulate(kw.get("S", p), p, p, kw.get("n", 4), p, 5, p, 5,
+                                              kw.get("nx", 10), p, kw.get("sx", p), None)
+    assert pa(n=-2) == Bd.SV_ERR_INVALID_ARG
+    assert pa(nx=0) == Bd.SV_ERR_INVALID_ARG
+    assert pa(nx=2000) == Bd.SV_ERR_TOO_LARGE
+    assert pa(S=None) == Bd.SV_ERR_NULL
+    assert pa(sx=ctypes.c_void_p(256 * 1024 + 4)) == Bd.SV_ERR_ALIGN
+    pf = lambda **kw: L.sv_profile_finalize(kw.get("c", p), p, kw.get("ns", 5), 5, kw.get("nx", 10), p,
+                                            kw.get("info", p), None)
+    assert pf(ns=0) == Bd.SV_ERR_INVALID_ARG
+    assert pf(nx=1025) == Bd.SV_ERR_TOO_LARGE
+    assert pf(c=None) == Bd.SV_ERR_NULL
+    assert pf(info=ctypes.c_void_p(256 * 1024 + 4)) == Bd.SV_ERR_ALIGN
