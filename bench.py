@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--config", type=int, default=3, help="0-based index into svgen.CONFIGS")
     ap.add_argument("--copies", type=int, default=4, help="distinct input copies rotated over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile-pass", action="store_true",
+                    help="skip the timing of the profile-construction pass")
     ap.add_argument("--cpu-seqs", type=int, default=0, help="sequences the oracle is timed on (0 = auto)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for rocprofv3 byte counters)")
@@ -228,6 +230,64 @@ def main():
                   "gamma_equal": bool(np.array_equal(got["gamma"], rg)) if nseq == B else None}
         assert bad == 0 and s_err < 1e-5 and a_err < 1e-5, parity
 
+    # ---- profile-construction pass (the offline step before the hot path), timed
+    # on a held-out batch of the same recipe: S, A from sv_row_stats, X from
+    # sv_accept_ratio, 10x10 uniform grid, histogram, table + information gain
+    profile_pass = None
+    if not args.no_profile_pass:
+        held = svgen.make_config(args.config, seed=5000 + args.config, device="cuda")
+        ratio = f32(B, k)
+        n_s = n_a = 10
+        n_x = 10
+        counts = torch.zeros((n_s, n_a, n_x), dtype=torch.int32, device="cuda")
+        sum_x = torch.zeros((n_s, n_a), dtype=torch.float64, device="cuda")
+        ptable = f32(n_s, n_a)
+        info = torch.zeros(3, dtype=torch.float64, device="cuda")
+
+        def profile_once():
+            P.sv_row_stats(held["z_d"], held["z_c"], held["x"], lse_d, lse_c, S, A, None, None, ws, stream)
+            P.sv_accept_ratio(held["z_t"], held["z_d"], held["x"], ratio, None, ws, stream)
+            counts.zero_()
+            sum_x.zero_()
+            P.sv_profile_accumulate(S, A, ratio, d_es, d_ea, n_x, counts, sum_x, stream)
+            P.sv_profile_finalize(counts, sum_x, ptable, info, stream)
+
+        for _ in range(3):
+            profile_once()
+        torch.cuda.synchronize()
+        reps = 20
+        pe = [(hip.event(), hip.event()) for _ in range(reps)]
+        p0 = time.perf_counter()
+        for i in range(reps):
+            P.sv_set_timing_events(Bd.SV_KERNEL_VERIFY_ROWS, pe[i][0], pe[i][1])
+            profile_once()
+        P.sv_set_timing_events(Bd.SV_KERNEL_VERIFY_ROWS, None, None)
+        torch.cuda.synchronize()
+        p1 = time.perf_counter()
+        ratio_rows_us = float(np.mean([hip.elapsed_ms(a, b) for a, b in pe]) * 1e3)
+        ratio_bytes = 2 * B * k * row_bytes
+        hinfo = info.cpu().numpy()
+        profile_pass = {"samples": B * k, "grid": f"{n_s}x{n_a} uniform, {n_x} X bins",
+                        "ms_per_pass": round((p1 - p0) * 1e3 / reps, 4),
+                        "accept_ratio_rows_kernel_us": round(ratio_rows_us, 2),
+                        "accept_ratio_rows_kernel_GBps": round(ratio_bytes / ratio_rows_us * 1e-3, 1),
+                        "H_X_bits": round(float(hinfo[0]), 4), "H_X_given_SA_bits": round(float(hinfo[1]), 4),
+                        "info_gain_bits": round(float(hinfo[2]), 4)}
+        if not args.no_cpu_baseline:
+            from oracle import profile_oracle as PO
+            nq = min(B, 8)                       # a slice keeps the oracle leg short
+            hz = {n: svgen.to_numpy_bits(held[n][:nq]) for n in ("z_t", "z_d", "z_c")}
+            hx = held["x"][:nq].cpu().numpy()
+            rs_ = O.row_stats(hz["z_d"], hz["z_c"], hx)
+            rr_, _ = PO.accept_probability_ratio(hz["z_t"], hz["z_d"], hx)
+            P.sv_row_stats(held["z_d"], held["z_c"], held["x"], lse_d, lse_c, S, A, None, None, ws, stream)
+            torch.cuda.synchronize()
+            got_ratio = ratio.cpu().numpy()[:nq]
+            rel = float(np.max(np.abs(got_ratio - rr_) / np.abs(rr_)))
+            relS = float(np.max(np.abs(S.cpu().numpy()[:nq] - rs_["S"]) / rs_["S"]))
+            profile_pass["parity"] = {"sequences_checked": nq, "max_rel_err_ratio": rel, "max_rel_err_S": relS}
+            assert rel < 1e-5 and relS < 1e-5, profile_pass
+
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)
@@ -256,6 +316,7 @@ def main():
         "kernels": kernels,
         "sum_kernel_us": round(sum(us.values()), 2),
         "parity": parity,
+        "profile_pass": profile_pass,
         "mean_gamma_selected": float(np.mean(got["gamma"])),
         "mean_accepted_full_verify": float(np.mean(got["n_accept"])),
         "setup_s": round(time.time() - t_setup, 1),
