@@ -92,18 +92,22 @@ size_t sv_workspace_bytes(int B, int k, int V, int dtype);
  *   P_d = softmax(z_d[b,i,:]),  P_c = softmax(z_c[b,i,:])
  *   S[b,i] = sum_v min(P_d(v), P_c(v))
  *   A[b,i] = min(1, P_c(x[b,i]) / P_d(x[b,i]))          (1 when P_d(x) = 0)
- * plus the row log-sum-exps and, optionally, KL(P_d || P_c).
+ * plus the row log-sum-exps and, optionally, KL(P_d || P_c), the draft entropy
+ * H(P_d) in nats and the draft's probability of its own token P_d(x) (the signals
+ * of the entropy- and probability-based predictors the paper compares with,
+ * Sec. 2 "Predicting Speculation Accuracy").
  *   z_d, z_c   [B,k,V] dtype        in
  *   x          [B,k]   int32        in   drafted token ids
  *   lse_d, lse_c, S, A [B,k] float  out  (NaN for bad rows; A NaN for bad tokens)
- *   kl_or_null [B,k] float          out  optional
+ *   kl_or_null, entropy_d_or_null, pd_x_or_null [B,k] float   out  optional
  *   flags_or_null [B,k] uint32      out  optional, SV_FLAG_BAD_ROW / SV_FLAG_BAD_TOKEN
  * B, k, V >= 1.  B = 0 is accepted and does nothing.
  */
 int sv_row_stats(const void* z_d, const void* z_c, const int32_t* x,
                  int B, int k, int V, int dtype,
                  float* lse_d, float* lse_c, float* S, float* A,
-                 float* kl_or_null, uint32_t* flags_or_null,
+                 float* kl_or_null, float* entropy_d_or_null, float* pd_x_or_null,
+                 uint32_t* flags_or_null,
                  void* ws, size_t ws_bytes, sv_stream_t stream);
 
 /*

@@ -109,6 +109,8 @@ def row_stats(z_d, z_c, x):
       A            : min(1, P_c(x) / P_d(x)), evaluated in log space
       TV           : max(0, 1 - S)
       KL           : sum_{v: P_d(v) > 0} P_d(v) (log P_d(v) - log P_c(v))
+      H_d          : draft entropy -sum_{v: P_d(v) > 0} P_d(v) log P_d(v), nats
+      pd_x         : P_d(x), the draft's probability of its own drafted token
       flags        : FLAG_BAD_ROW / FLAG_BAD_TOKEN bits (uint32)
     If P_d(x) = 0 the ratio is taken as saturated, A = 1.
     """
@@ -116,7 +118,7 @@ def row_stats(z_d, z_c, x):
     z_c = np.asarray(z_c)
     x = np.asarray(x)
     B, k, V = z_d.shape
-    out = {n: np.full((B, k), np.nan) for n in ("lse_d", "lse_c", "S", "A", "TV", "KL")}
+    out = {n: np.full((B, k), np.nan) for n in ("lse_d", "lse_c", "S", "A", "TV", "KL", "H_d", "pd_x")}
     flags = np.zeros((B, k), dtype=np.uint32)
     for b in range(B):
         for i in range(k):
@@ -135,10 +137,12 @@ def row_stats(z_d, z_c, x):
             pos = p_d > 0
             with np.errstate(invalid="ignore"):
                 out["KL"][b, i] = np.sum(p_d[pos] * (lp_d[pos] - lp_c[pos]))
+            out["H_d"][b, i] = -np.sum(p_d[pos] * lp_d[pos])
             t = int(x[b, i])
             if t < 0 or t >= V:
                 flags[b, i] |= FLAG_BAD_TOKEN
                 continue
+            out["pd_x"][b, i] = p_d[t]
             if lp_d[t] == -np.inf:
                 out["A"][b, i] = 1.0
             else:

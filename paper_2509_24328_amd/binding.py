@@ -40,7 +40,8 @@ lib.sv_strerror.argtypes = [_i]
 lib.sv_workspace_bytes.restype = _sz
 lib.sv_workspace_bytes.argtypes = [_i, _i, _i, _i]
 lib.sv_row_stats.restype = _i
-lib.sv_row_stats.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+lib.sv_row_stats.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz,
+                             _vp]
 lib.sv_accept_estimate.restype = _i
 lib.sv_accept_estimate.argtypes = [_vp, _vp, _i, _vp, _i, _vp, _i, _vp, _vp, _vp, _vp]
 lib.sv_select_length.restype = _i
@@ -101,11 +102,13 @@ def alloc_workspace(B, k, V, dtype, device="cuda"):
     return torch.empty(n, dtype=torch.uint8, device=device)
 
 
-def sv_row_stats(z_d, z_c, x, lse_d, lse_c, S, A, kl=None, flags=None, ws=None, stream=None):
+def sv_row_stats(z_d, z_c, x, lse_d, lse_c, S, A, kl=None, flags=None, ws=None, stream=None,
+                 entropy_d=None, pd_x=None):
     B, k, V = z_d.shape
     _check(lib.sv_row_stats(_ptr(z_d), _ptr(z_c), _ptr(x), B, k, V, _dtype_tag(z_d),
-                            _ptr(lse_d), _ptr(lse_c), _ptr(S), _ptr(A), _ptr(kl), _ptr(flags),
-                            _ptr(ws), 0 if ws is None else ws.numel(), _stream(stream)))
+                            _ptr(lse_d), _ptr(lse_c), _ptr(S), _ptr(A), _ptr(kl), _ptr(entropy_d),
+                            _ptr(pd_x), _ptr(flags), _ptr(ws), 0 if ws is None else ws.numel(),
+                            _stream(stream)))
 
 
 def sv_accept_estimate(S, A, edges_s, edges_a, table, p_hat, edge_flag=None, stream=None):

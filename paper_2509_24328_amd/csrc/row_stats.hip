@@ -7,7 +7,11 @@
 // both normalisers before the element-wise comparison, so a second sweep over
 // the pair is unavoidable; it accumulates
 //     min(P_d, P_c) = 2^min(a_d, a_c),  a = z * L32 - kappa   (one exp per entry)
-// and, on request, KL(P_d || P_c) = ln2 * sum_v P_d (a_d - a_c).
+// and, on request, KL(P_d || P_c) = ln2 * sum_v P_d (a_d - a_c) and the draft
+// entropy H(P_d) = -ln2 * sum_v P_d log2 P_d; the draft's probability of its own
+// token, P_d(x), is a free by-product of the epilogue.  (Draft entropy and
+// draft-token probability are the signals of the prior acceptance predictors
+// discussed in Sec. 2 of the paper.)
 // A = min(1, P_c(x) / P_d(x)) is a scalar epilogue in fp64.
 //
 // Two kernels:
@@ -41,6 +45,8 @@ struct StatsArgs {
   float* S;
   float* A;
   float* kl;          // nullable
+  float* entropy_d;   // nullable
+  float* pd_x;        // nullable
   uint32_t* flags;    // nullable
 };
 
@@ -87,6 +93,7 @@ template <bool WITH_KL>
 struct MinAcc {
   float kd, kc, delta;
   float acc_s = 0.f, acc_kl = 0.f;
+  float acc_pa = 0.f, acc_p = 0.f;     // sum P_d * log2-arg and sum P_d (draft entropy)
   __device__ __forceinline__ void add(float zd, float zc) {
     const float ad = __builtin_fmaf(zd, kL32, -kd);
     const float ac = __builtin_fmaf(zc, kL32, -kc) + delta;
@@ -95,6 +102,9 @@ struct MinAcc {
       acc_s += fminf(pd, exp2_fast(ac));
       const float t = pd * (ad - ac);          // 0 * inf when P_d underflows: dropped below
       acc_kl += (pd > 0.f) ? t : 0.f;
+      const float u = pd * ad;
+      acc_pa += (pd > 0.f) ? u : 0.f;
+      acc_p += pd;
     } else {
       acc_s += exp2_fast(fminf(ad, ac));
     }
@@ -109,7 +119,7 @@ struct MinAcc {
       add(fd[j], fc[j]);
       // both sums advance together: otherwise all S terms are formed first and
       // the exponents wait in scratch for the KL terms
-      if (WITH_KL && (j & 1)) asm volatile("" : "+v"(acc_s), "+v"(acc_kl));
+      if (WITH_KL && (j & 1)) asm volatile("" : "+v"(acc_s), "+v"(acc_kl), "+v"(acc_pa), "+v"(acc_p));
     }
   }
 };
@@ -117,10 +127,10 @@ struct MinAcc {
 // Scalar epilogue shared by both kernels: A, flags and the stores.
 template <int DT, bool WITH_KL>
 __device__ __forceinline__ void stats_epilogue(const StatsArgs& a, int pair, const void* rd, const void* rc,
-                                               double lse_d, double lse_c, double S, double KL) {
+                                               double lse_d, double lse_c, double S, double KL, double H_d) {
   const bool bad = isnan(lse_d) || isnan(lse_c);
   uint32_t fl = bad ? SV_FLAG_BAD_ROW : 0u;
-  double A = __builtin_nan("");
+  double A = __builtin_nan(""), pdx = __builtin_nan("");
   if (!bad) {
     const int tok = a.x[pair];
     if (tok < 0 || tok >= a.V) {
@@ -129,13 +139,16 @@ __device__ __forceinline__ void stats_epilogue(const StatsArgs& a, int pair, con
       const double ld = (double)load_elem<DT>(rd, tok) - lse_d;
       const double lc = (double)load_elem<DT>(rc, tok) - lse_c;
       A = (ld == -INFINITY) ? 1.0 : fmin(1.0, exp(lc - ld));
+      pdx = exp(ld);
     }
   }
   a.lse_d[pair] = (float)lse_d;
   a.lse_c[pair] = (float)lse_c;
   a.S[pair] = (float)S;
   a.A[pair] = (float)A;
-  if (WITH_KL) a.kl[pair] = (float)KL;
+  if (WITH_KL && a.kl) a.kl[pair] = (float)KL;
+  if (WITH_KL && a.entropy_d) a.entropy_d[pair] = (float)H_d;
+  if (a.pd_x) a.pd_x[pair] = (float)pdx;
   if (a.flags) a.flags[pair] = fl;
 }
 
@@ -279,7 +292,7 @@ __global__ __launch_bounds__(kStashThreads) void row_stats_stash_kernel(StatsArg
 
   SV_PHASE_MARK(5)
   // ---- sweep 2: rest of the pair from L2/HBM (newest first), then LDS, then registers
-  double S = __builtin_nan(""), KL = __builtin_nan("");
+  double S = __builtin_nan(""), KL = __builtin_nan(""), H_d = __builtin_nan("");
   if (!bad) {
     const double kappa_d = consts.kappa[0], kappa_c = consts.kappa[1];
     MinAcc<WITH_KL> acc;
@@ -319,15 +332,20 @@ __global__ __launch_bounds__(kStashThreads) void row_stats_stash_kernel(StatsArg
     }
     SV_PHASE_MARK(8)
     S = block_sum_f64((double)acc.acc_s, sm);
-    if (WITH_KL) KL = block_sum_f64((double)acc.acc_kl, sm);
+    if (WITH_KL) {
+      KL = block_sum_f64((double)acc.acc_kl, sm);
+      const double pa = block_sum_f64((double)acc.acc_pa, sm), p1 = block_sum_f64((double)acc.acc_p, sm);
+      H_d = pa - tail_d * p1;                  // sum 2^(a_d) * log2 P_d, still without f_d
+    }
     if (tid == 0) {
       const double f_d = exp2(-tail_d);
       S *= f_d;
       KL *= f_d * kLn2;
+      H_d *= -f_d * kLn2;
     }
   }
   SV_PHASE_MARK(9)
-  if (tid == 0) stats_epilogue<DT, WITH_KL>(a, pair, pd, pc, lse_d, lse_c, S, KL);
+  if (tid == 0) stats_epilogue<DT, WITH_KL>(a, pair, pd, pc, lse_d, lse_c, S, KL, H_d);
 }
 
 template <int DT, bool WITH_KL>
@@ -348,7 +366,7 @@ __global__ __launch_bounds__(kStatsThreads) void row_stats_kernel(StatsArgs a) {
   const double lse_d = consts.lse[0], lse_c = consts.lse[1];
   const bool bad = isnan(lse_d) || isnan(lse_c);
 
-  double S = __builtin_nan(""), KL = __builtin_nan("");
+  double S = __builtin_nan(""), KL = __builtin_nan(""), H_d = __builtin_nan("");
   if (!bad) {
     // kappa = log2-domain normaliser consistent with the L32 exponent scale,
     // split into an fp32 head and a tail.  With a = z*L32 - head:
@@ -363,14 +381,19 @@ __global__ __launch_bounds__(kStatsThreads) void row_stats_kernel(StatsArgs a) {
     acc.delta = (float)(tail_d - tail_c);
     visit_range<DT, true>(rd, rc, 0, a.V, [&](int, float zd, float zc) { acc.add(zd, zc); });
     S = block_sum_f64((double)acc.acc_s, sm);
-    if (WITH_KL) KL = block_sum_f64((double)acc.acc_kl, sm);
+    if (WITH_KL) {
+      KL = block_sum_f64((double)acc.acc_kl, sm);
+      const double pa = block_sum_f64((double)acc.acc_pa, sm), p1 = block_sum_f64((double)acc.acc_p, sm);
+      H_d = pa - tail_d * p1;
+    }
     if (threadIdx.x == 0) {
       const double f_d = exp2(-tail_d);
       S *= f_d;
       KL *= f_d * kLn2;
+      H_d *= -f_d * kLn2;
     }
   }
-  if (threadIdx.x == 0) stats_epilogue<DT, WITH_KL>(a, pair, rd, rc, lse_d, lse_c, S, KL);
+  if (threadIdx.x == 0) stats_epilogue<DT, WITH_KL>(a, pair, rd, rc, lse_d, lse_c, S, KL, H_d);
 }
 
 template <int DT, bool WITH_KL>
@@ -399,7 +422,8 @@ static int launch_stats(const StatsArgs& a, bool rows_aligned, hipStream_t st) {
 extern "C" int sv_row_stats(const void* z_d, const void* z_c, const int32_t* x,
                             int B, int k, int V, int dtype,
                             float* lse_d, float* lse_c, float* S, float* A,
-                            float* kl_or_null, uint32_t* flags_or_null,
+                            float* kl_or_null, float* entropy_d_or_null, float* pd_x_or_null,
+                            uint32_t* flags_or_null,
                             void* ws, size_t ws_bytes, sv_stream_t stream) {
   using namespace sv;
   SV_REQUIRE(dtype == SV_F32 || dtype == SV_BF16, SV_ERR_DTYPE);
@@ -410,14 +434,17 @@ extern "C" int sv_row_stats(const void* z_d, const void* z_c, const int32_t* x,
   const int eb = elem_bytes(dtype);
   SV_REQUIRE(is_aligned(z_d, eb) && is_aligned(z_c, eb), SV_ERR_ALIGN);
   SV_REQUIRE(is_aligned(x, 4) && is_aligned(lse_d, 4) && is_aligned(lse_c, 4) && is_aligned(S, 4) &&
-                 is_aligned(A, 4) && is_aligned(kl_or_null, 4) && is_aligned(flags_or_null, 4),
+                 is_aligned(A, 4) && is_aligned(kl_or_null, 4) && is_aligned(entropy_d_or_null, 4) &&
+                 is_aligned(pd_x_or_null, 4) && is_aligned(flags_or_null, 4),
              SV_ERR_ALIGN);
   SV_REQUIRE(ws && is_aligned(ws, kWsAlign) && ws_bytes >= sv_workspace_bytes(B, k, V, dtype),
              SV_ERR_WORKSPACE);
-  StatsArgs a{z_d, z_c, x, B, k, V, lse_d, lse_c, S, A, kl_or_null, flags_or_null};
+  StatsArgs a{z_d, z_c, x, B, k, V, lse_d, lse_c, S, A, kl_or_null, entropy_d_or_null, pd_x_or_null,
+              flags_or_null};
+  const bool extended = kl_or_null || entropy_d_or_null;   // sums that need P_d of every entry
   const bool rows_aligned = is_aligned(z_d, 16) && is_aligned(z_c, 16) && ((size_t)V * eb) % 16 == 0;
   hipStream_t st = as_stream(stream);
   if (dtype == SV_F32)
-    return kl_or_null ? launch_stats<DT_F32, true>(a, rows_aligned, st) : launch_stats<DT_F32, false>(a, rows_aligned, st);
-  return kl_or_null ? launch_stats<DT_BF16, true>(a, rows_aligned, st) : launch_stats<DT_BF16, false>(a, rows_aligned, st);
+    return extended ? launch_stats<DT_F32, true>(a, rows_aligned, st) : launch_stats<DT_F32, false>(a, rows_aligned, st);
+  return extended ? launch_stats<DT_BF16, true>(a, rows_aligned, st) : launch_stats<DT_BF16, false>(a, rows_aligned, st);
 }

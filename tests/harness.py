@@ -31,10 +31,11 @@ def gpu_row_stats(z_d, z_c, x, with_kl=True):
     B, k, V = z_d.shape
     mk = lambda: torch.full((B, k), -7.0, dtype=torch.float32, device="cuda")
     out = dict(lse_d=mk(), lse_c=mk(), S=mk(), A=mk(), KL=mk() if with_kl else None,
+               H_d=mk() if with_kl else None, pd_x=mk(),
                flags=torch.full((B, k), 0xFFFF, dtype=torch.int32, device="cuda"))
     ws = P.alloc_workspace(B, k, V, P.binding._dtype_tag(z_d))
     P.sv_row_stats(z_d, z_c, x, out["lse_d"], out["lse_c"], out["S"], out["A"], out["KL"],
-                   out["flags"], ws)
+                   out["flags"], ws, entropy_d=out["H_d"], pd_x=out["pd_x"])
     torch.cuda.synchronize()
     return {n: (None if t is None else t.cpu().numpy()) for n, t in out.items()}
 
@@ -102,9 +103,13 @@ def assert_row_stats(got, ref, with_kl=True):
     tv = np.maximum(0, 1 - got["S"].astype(np.float64))
     ok = close(tv, ref["TV"], REL, 2e-6)
     assert ok.all(), ("TV", tv[~ok], ref["TV"][~ok])
+    ok = close(got["pd_x"], ref["pd_x"], REL, 1e-37)
+    assert ok.all(), ("pd_x", got["pd_x"][~ok], ref["pd_x"][~ok])
     if with_kl:
         ok = close(got["KL"], ref["KL"], REL, 2e-6)
         assert ok.all(), ("KL", got["KL"][~ok], ref["KL"][~ok])
+        ok = close(got["H_d"], ref["H_d"], REL, 2e-6)
+        assert ok.all(), ("H_d", got["H_d"][~ok], ref["H_d"][~ok])
     assert np.array_equal(got["flags"].astype(np.uint32), ref["flags"]), "flags"
 
 

@@ -38,7 +38,7 @@ def test_argument_errors_are_reported_before_any_launch():
     odd = ctypes.c_void_p(256 * 1024 + 1)
     big = 1 << 30
     rs = lambda **kw: L.sv_row_stats(kw.get("zd", p), p, p, kw.get("B", 2), kw.get("k", 2),
-                                     kw.get("V", 8), kw.get("dt", 1), p, p, p, p, None, None,
+                                     kw.get("V", 8), kw.get("dt", 1), p, p, p, p, None, None, None, None,
                                      kw.get("ws", p), kw.get("wsb", big), None)
     assert rs(dt=3) == Bd.SV_ERR_DTYPE
     assert rs(k=0) == Bd.SV_ERR_INVALID_ARG

@@ -31,7 +31,7 @@ def test_empty_batch_is_a_no_op():
     e = torch.empty(0, device="cuda")
     ws = P.alloc_workspace(0, 4, 100, P.SV_F32)
     assert P.binding.lib.sv_row_stats(None, None, None, 0, 4, 100, P.SV_F32, None, None, None, None,
-                                      None, None, None, 0, None) == 0
+                                      None, None, None, None, None, 0, None) == 0
     assert P.binding.lib.sv_verify_sample(None, None, 0, None, None, None, 0, 4, 100, P.SV_F32, 0, 0,
                                           None, None, None, None, None, 0, None) == 0
     assert P.binding.lib.sv_accept_estimate(None, None, 0, None, 3, None, 3, None, None, None, None) == 0

@@ -63,6 +63,11 @@ def test_S_equals_library_min_of_softmaxes_and_is_symmetric():
     assert np.allclose(r["TV"], 0.5 * (pd - pc).abs().sum(-1).numpy(), atol=1e-12)
     r2 = O.row_stats(zc, zd, x)
     assert np.allclose(r["S"], r2["S"], rtol=1e-14)
+    import scipy.stats
+    assert np.allclose(r["H_d"], scipy.stats.entropy(pd.numpy(), axis=-1), rtol=1e-12)
+    for b in range(2):
+        for i in range(3):
+            assert abs(r["pd_x"][b, i] - float(pd[b, i, x[b, i]])) < 1e-15
     kl_ref = (pd * (pd.log() - pc.log())).sum(-1).numpy()
     assert np.allclose(r["KL"], kl_ref, rtol=1e-10)
     assert np.all(r["KL"] >= 0)
