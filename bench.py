@@ -38,6 +38,7 @@ def parse():
     ap.add_argument("--config", type=int, default=3, help="0-based index into svgen.CONFIGS")
     ap.add_argument("--copies", type=int, default=4, help="distinct input copies rotated over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay timing")
     ap.add_argument("--no-profile-pass", action="store_true",
                     help="skip the timing of the profile-construction pass")
     ap.add_argument("--cpu-seqs", type=int, default=0, help="sequences the oracle is timed on (0 = auto)")
@@ -142,6 +143,35 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    # ---- the same K steps replayed from HIP graphs (one captured step per input copy)
+    graph_ms = None
+    if not args.no_graph:
+        graphs = []
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for r in range(len(copies)):
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=side):
+                    c = copies[r]
+                    s_ = torch.cuda.current_stream()
+                    P.sv_row_stats(c["z_d"], c["z_c"], c["x"], lse_d, lse_c, S, A, None, None, ws, s_)
+                    P.sv_accept_estimate(S, A, d_es, d_ea, d_tab, p_hat, None, s_)
+                    P.sv_select_length(p_hat, d_lat, P.SV_BATCH_GREEDY, gamma, offs, total, s_)
+                    P.sv_verify_sample(c["z_t"], None, c["z_d"], c["x"], None, 0, r, tokens, n_acc, flags,
+                                       None, ws, s_)
+                graphs.append(g)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        for i in range(args.warmup):
+            graphs[i % len(graphs)].replay()
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        for i in range(args.steps):
+            graphs[i % len(graphs)].replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - g0) * 1e3 / args.steps
 
     # ---- the same K steps again with hipEvents around every kernel launch
     hip = Hip()
@@ -315,6 +345,8 @@ def main():
                         "metric_kernel_frac_of_peak": round(mk_gbs / PEAK_HBM_GBS, 4)},
         "kernels": kernels,
         "sum_kernel_us": round(sum(us.values()), 2),
+        "graph_replay": None if graph_ms is None else {
+            "ms_per_step": round(graph_ms, 5), "rows_per_s": round(rows_per_step / (graph_ms * 1e-3), 1)},
         "parity": parity,
         "profile_pass": profile_pass,
         "mean_gamma_selected": float(np.mean(got["gamma"])),
