@@ -232,6 +232,27 @@ int sv_profile_accumulate(const float* S, const float* A, const float* ratio, in
 int sv_profile_finalize(const uint32_t* counts, const double* sum_x, int n_s, int n_a, int n_x,
                         float* table, double* info, sv_stream_t stream);
 
+/* ------------------------------------------------------------------------
+ * Sampling warps (appendix table "Sampling hyperparameters for each model
+ * series": temperature, top-k, top-p; applied in that order).
+ * ------------------------------------------------------------------------ */
+
+/*
+ * Per-row cutoff such that the warped distribution is soft-max(z / temperature)
+ * restricted to {v : z_v >= cutoff[row]}.  top-k keeps the entries at least as
+ * large as the K-th largest value; top-p then keeps, over those, whole groups of
+ * equal value from the top until their mass reaches top_p.  top_k <= 0 or >= V
+ * and top_p >= 1 switch the respective warp off (cutoff = -inf keeps all).
+ *   z       [rows, V] dtype    in
+ *   cutoff  [rows] float       out  a value of the row, -inf, or NaN for a bad row
+ *   flags_or_null [rows] uint32 out SV_FLAG_BAD_ROW; SV_FLAG_NEAR_TIE when the top-p
+ *                                   decision lies within 1e-6 of top_p
+ * temperature > 0, top_p > 0.
+ */
+int sv_warp_cutoffs(const void* z, int rows, int V, int dtype,
+                    float temperature, int top_k, float top_p,
+                    float* cutoff, uint32_t* flags_or_null, sv_stream_t stream);
+
 /*
  * Timing taps for benchmarks (not part of the method): while a pair of
  * hipEvent_t handles is set for `kernel`, every launch of that kernel records

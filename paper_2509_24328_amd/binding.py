@@ -25,7 +25,7 @@ SV_MAX_K = 64
 
 EXPORTS = ("sv_strerror", "sv_workspace_bytes", "sv_row_stats", "sv_accept_estimate",
            "sv_select_length", "sv_verify_sample", "sv_set_timing_events", "sv_accept_ratio",
-           "sv_quantile_edges", "sv_profile_accumulate", "sv_profile_finalize")
+           "sv_quantile_edges", "sv_profile_accumulate", "sv_profile_finalize", "sv_warp_cutoffs")
 (SV_KERNEL_ROW_STATS, SV_KERNEL_ACCEPT_ESTIMATE, SV_KERNEL_SELECT_LENGTH, SV_KERNEL_VERIFY_ROWS,
  SV_KERNEL_VERIFY_ACCEPT, SV_KERNEL_VERIFY_MASS, SV_KERNEL_VERIFY_PICK, SV_KERNEL_COUNT) = range(8)
 
@@ -57,6 +57,8 @@ lib.sv_profile_accumulate.restype = _i
 lib.sv_profile_accumulate.argtypes = [_vp, _vp, _vp, _i, _vp, _i, _vp, _i, _i, _vp, _vp, _vp]
 lib.sv_profile_finalize.restype = _i
 lib.sv_profile_finalize.argtypes = [_vp, _vp, _i, _i, _i, _vp, _vp, _vp]
+lib.sv_warp_cutoffs.restype = _i
+lib.sv_warp_cutoffs.argtypes = [_vp, _i, _i, _i, ctypes.c_float, _i, ctypes.c_float, _vp, _vp, _vp]
 lib.sv_set_timing_events.restype = _i
 lib.sv_set_timing_events.argtypes = [_i, _vp, _vp]
 
@@ -159,3 +161,10 @@ def sv_profile_finalize(counts, sum_x, table, info, stream=None):
     n_s, n_a, n_x = counts.shape
     _check(lib.sv_profile_finalize(_ptr(counts), _ptr(sum_x), n_s, n_a, n_x, _ptr(table), _ptr(info),
                                    _stream(stream)))
+
+
+def sv_warp_cutoffs(z, temperature, top_k, top_p, cutoff, flags=None, stream=None):
+    V = z.shape[-1]
+    rows = z.numel() // V
+    _check(lib.sv_warp_cutoffs(_ptr(z), rows, V, _dtype_tag(z), temperature, top_k, top_p, _ptr(cutoff),
+                               _ptr(flags), _stream(stream)))

@@ -108,3 +108,18 @@ def test_profile_pass_argument_errors():
     assert pf(nx=1025) == Bd.SV_ERR_TOO_LARGE
     assert pf(c=None) == Bd.SV_ERR_NULL
     assert pf(info=ctypes.c_void_p(256 * 1024 + 4)) == Bd.SV_ERR_ALIGN
+
+
+def test_warp_cutoffs_argument_errors():
+    L = Bd.lib
+    p = ctypes.c_void_p(256 * 1024)
+    f = ctypes.c_float
+    wc = lambda **kw: L.sv_warp_cutoffs(kw.get("z", p), kw.get("rows", 4), kw.get("V", 8), kw.get("dt", 1),
+                                        f(kw.get("T", 0.7)), 20, f(kw.get("P", 0.8)), kw.get("cut", p), None, None)
+    assert wc(dt=2) == Bd.SV_ERR_DTYPE
+    assert wc(T=0.0) == Bd.SV_ERR_INVALID_ARG
+    assert wc(P=0.0) == Bd.SV_ERR_INVALID_ARG
+    assert wc(V=0) == Bd.SV_ERR_INVALID_ARG
+    assert wc(z=None) == Bd.SV_ERR_NULL
+    assert wc(cut=ctypes.c_void_p(256 * 1024 + 2)) == Bd.SV_ERR_ALIGN
+    assert wc(rows=0) == Bd.SV_OK

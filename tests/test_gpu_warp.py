@@ -1,0 +1,79 @@
+"""GPU parity of the sampling-warp cutoffs against the oracle: the kept set
+{v : z_v >= cutoff} must be identical row by row (rows whose top-p decision is
+flagged as a near tie by either side are counted, not compared)."""
+import numpy as np
+import pytest
+import torch
+
+import svgen
+from oracle import sv_oracle as O
+from oracle import warp_oracle as W
+
+import harness as H
+
+pytestmark = pytest.mark.gpu
+
+# (temperature, top_k, top_p): the paper's four model series, then switches and extremes
+PARAMS = [(0.7, 20, 0.8), (0.95, 20, 0.6), (0.6, 0, 0.9), (1.0, 0, 1.0), (1.0, 1, 1.0), (1.0, 50, 1.0),
+          (1.3, 0, 0.5), (0.5, 5, 0.999), (1.0, 0, 1e-6), (2.0, 100000, 0.99)]
+
+
+def _gpu_cutoffs(z, T, K, Pp):
+    P = H.sv()
+    rows = z.numel() // z.shape[-1]
+    cut = torch.full((rows,), 123.0, dtype=torch.float32, device="cuda")
+    flags = torch.full((rows,), 99, dtype=torch.int32, device="cuda")
+    P.sv_warp_cutoffs(z, T, K, Pp, cut, flags)
+    torch.cuda.synchronize()
+    return cut.cpu().numpy(), flags.cpu().numpy().astype(np.uint32)
+
+
+def _compare(z_torch, T, K, Pp):
+    zn = svgen.to_numpy_bits(z_torch)
+    V = zn.shape[-1]
+    rows = zn.reshape(-1, V)
+    got, gflags = _gpu_cutoffs(z_torch.cuda(), T, K, Pp)
+    n_tie = 0
+    for r in range(rows.shape[0]):
+        ref, rflags = W.warp_cutoff(rows[r], T, K, Pp)
+        if rflags & O.FLAG_BAD_ROW:
+            assert np.isnan(got[r]) and gflags[r] & O.FLAG_BAD_ROW
+            continue
+        vals = O.upcast(rows[r])
+        if (rflags | gflags[r]) & O.FLAG_NEAR_TIE:
+            # the two decisions may differ, but only by groups of negligible mass
+            n_tie += 1
+            lo, hi = min(got[r], ref), max(got[r], ref)
+            y = vals / T
+            w = np.exp(y - y.max())
+            between = w[(vals >= lo) & (vals < hi)].sum() / w.sum()
+            assert between <= 4e-6, (r, T, K, Pp, got[r], ref, between)
+            continue
+        assert np.array_equal(vals >= got[r], vals >= ref), (r, T, K, Pp, got[r], ref)
+    return n_tie
+
+
+@pytest.mark.parametrize("T,K,Pp", PARAMS)
+def test_cutoffs_on_config_rows(T, K, Pp):
+    ties = 0
+    for idx, B, k, V, dtype in ((1, 3, 4, 32000, "bf16"), (3, 2, 3, 152064, "bf16"), (2, 2, 2, 20000, "bf16"),
+                                (0, 2, 3, 4099, "f32"), (1, 2, 2, 9, "bf16"), (0, 1, 2, 32000, "f32")):
+        cfg = svgen.make_config(idx, B=B, k=k, V=V, dtype=dtype)
+        ties += _compare(cfg["z_t"], T, K, Pp)
+        ties += _compare(cfg["z_d"], T, K, Pp)
+    assert ties <= 8            # flat rows with groups lighter than the 1e-6 band trip the flag
+
+
+def test_ties_negative_rows_masked_and_bad_rows():
+    rng = np.random.default_rng(0)
+    V = 5000
+    z = np.round(rng.standard_normal((6, V)) * 2) / 2            # few distinct values: massive ties
+    z[1] -= 40.0                                                  # an all-negative row
+    z[2, 100:4000] = -np.inf                                      # masked vocabulary
+    z[3, 7] = np.nan
+    z[4, :] = -np.inf
+    z[5, 9] = np.inf
+    for dtype in (torch.float32, torch.bfloat16):
+        t = torch.from_numpy(z).to(dtype)
+        for T, K, Pp in ((1.0, 10, 1.0), (0.7, 0, 0.9), (0.7, 300, 0.5), (1.0, 4999, 0.9999)):
+            _compare(t, T, K, Pp)
