@@ -254,6 +254,49 @@ int sv_warp_cutoffs(const void* z, int rows, int V, int dtype,
                     float* cutoff, uint32_t* flags_or_null, sv_stream_t stream);
 
 /*
+ * sv_row_stats on warped distributions: P_d = soft-max(z_d / temperature_d) over
+ * {v : z_d[v] >= cutoff_d[row]}, P_c likewise with its own temperature and
+ * cutoffs (the draft and the companion are run with the sampling
+ * hyper-parameters of their model series; Sec. 4.2 for S and A, the appendix
+ * table of sampling hyper-parameters for the warps).  Everything else - shapes,
+ * outputs, flags, workspace, errors - is as for sv_row_stats; lse_d / lse_c are
+ * the normalisers of the warped rows z / T.
+ *   cutoff_d_or_null, cutoff_c_or_null  [B*k] float in  one cutoff per logit row as
+ *        written by sv_warp_cutoffs on the same tensor (NaN or -inf: keep every
+ *        entry); NULL = no cutoff for that tensor
+ * A drafted token outside the draft's support has P_d(x) = 0 and gives A = 1,
+ * as an entry at -inf does in sv_row_stats; KL is +inf when the companion's
+ * support misses part of the draft's.
+ * Temperatures must lie in [1e-3, 1e3], else SV_ERR_INVALID_ARG.
+ */
+int sv_row_stats_warped(const void* z_d, const void* z_c, const int32_t* x,
+                        int B, int k, int V, int dtype,
+                        float temperature_d, const float* cutoff_d_or_null,
+                        float temperature_c, const float* cutoff_c_or_null,
+                        float* lse_d, float* lse_c, float* S, float* A,
+                        float* kl_or_null, float* entropy_d_or_null, float* pd_x_or_null,
+                        uint32_t* flags_or_null,
+                        void* ws, size_t ws_bytes, sv_stream_t stream);
+
+/*
+ * sv_verify_sample on warped distributions (same sources as above; the
+ * accept / residual / bonus rule is unchanged and acts on the warped target and
+ * draft distributions).
+ *   cutoff_t_or_null  [rows of z_t] float in  one cutoff per logit row of z_t, indexed
+ *        like z_t itself (dense: b * (k+1) + i; packed: t_offsets[b] + i)
+ *   cutoff_d_or_null  [B*k] float in
+ * Everything else is as for sv_verify_sample.  Temperatures in [1e-3, 1e3].
+ */
+int sv_verify_sample_warped(const void* z_t, const int32_t* t_offsets_or_null, int n_t_rows,
+                            const void* z_d, const int32_t* x, const int32_t* gamma_or_null,
+                            int B, int k, int V, int dtype,
+                            float temperature_t, const float* cutoff_t_or_null,
+                            float temperature_d, const float* cutoff_d_or_null,
+                            uint64_t seed, uint32_t step,
+                            int32_t* out_tokens, int32_t* n_accept, uint32_t* flags,
+                            float* ratio_or_null, void* ws, size_t ws_bytes, sv_stream_t stream);
+
+/*
  * Timing taps for benchmarks (not part of the method): while a pair of
  * hipEvent_t handles is set for `kernel`, every launch of that kernel records
  * `start_event` immediately before and `stop_event` immediately after it on the

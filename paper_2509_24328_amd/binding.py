@@ -25,7 +25,8 @@ SV_MAX_K = 64
 
 EXPORTS = ("sv_strerror", "sv_workspace_bytes", "sv_row_stats", "sv_accept_estimate",
            "sv_select_length", "sv_verify_sample", "sv_set_timing_events", "sv_accept_ratio",
-           "sv_quantile_edges", "sv_profile_accumulate", "sv_profile_finalize", "sv_warp_cutoffs")
+           "sv_quantile_edges", "sv_profile_accumulate", "sv_profile_finalize", "sv_warp_cutoffs",
+           "sv_row_stats_warped", "sv_verify_sample_warped")
 (SV_KERNEL_ROW_STATS, SV_KERNEL_ACCEPT_ESTIMATE, SV_KERNEL_SELECT_LENGTH, SV_KERNEL_VERIFY_ROWS,
  SV_KERNEL_VERIFY_ACCEPT, SV_KERNEL_VERIFY_MASS, SV_KERNEL_VERIFY_PICK, SV_KERNEL_COUNT) = range(8)
 
@@ -59,6 +60,13 @@ lib.sv_profile_finalize.restype = _i
 lib.sv_profile_finalize.argtypes = [_vp, _vp, _i, _i, _i, _vp, _vp, _vp]
 lib.sv_warp_cutoffs.restype = _i
 lib.sv_warp_cutoffs.argtypes = [_vp, _i, _i, _i, ctypes.c_float, _i, ctypes.c_float, _vp, _vp, _vp]
+_f = ctypes.c_float
+lib.sv_row_stats_warped.restype = _i
+lib.sv_row_stats_warped.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _f, _vp, _f, _vp,
+                                    _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+lib.sv_verify_sample_warped.restype = _i
+lib.sv_verify_sample_warped.argtypes = [_vp, _vp, _i, _vp, _vp, _vp, _i, _i, _i, _i, _f, _vp, _f, _vp,
+                                        ctypes.c_uint64, ctypes.c_uint32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 lib.sv_set_timing_events.restype = _i
 lib.sv_set_timing_events.argtypes = [_i, _vp, _vp]
 
@@ -168,3 +176,24 @@ def sv_warp_cutoffs(z, temperature, top_k, top_p, cutoff, flags=None, stream=Non
     rows = z.numel() // V
     _check(lib.sv_warp_cutoffs(_ptr(z), rows, V, _dtype_tag(z), temperature, top_k, top_p, _ptr(cutoff),
                                _ptr(flags), _stream(stream)))
+
+
+def sv_row_stats_warped(z_d, z_c, x, temperature_d, cutoff_d, temperature_c, cutoff_c, lse_d, lse_c, S, A,
+                        kl=None, flags=None, ws=None, stream=None, entropy_d=None, pd_x=None):
+    B, k, V = z_d.shape
+    _check(lib.sv_row_stats_warped(_ptr(z_d), _ptr(z_c), _ptr(x), B, k, V, _dtype_tag(z_d),
+                                   temperature_d, _ptr(cutoff_d), temperature_c, _ptr(cutoff_c),
+                                   _ptr(lse_d), _ptr(lse_c), _ptr(S), _ptr(A), _ptr(kl), _ptr(entropy_d),
+                                   _ptr(pd_x), _ptr(flags), _ptr(ws), 0 if ws is None else ws.numel(),
+                                   _stream(stream)))
+
+
+def sv_verify_sample_warped(z_t, t_offsets, z_d, x, gamma, temperature_t, cutoff_t, temperature_d, cutoff_d,
+                            seed, step, out_tokens, n_accept, flags, ratio=None, ws=None, stream=None):
+    B, k, V = z_d.shape
+    n_t_rows = z_t.shape[0] if t_offsets is not None else 0
+    _check(lib.sv_verify_sample_warped(_ptr(z_t), _ptr(t_offsets), n_t_rows, _ptr(z_d), _ptr(x), _ptr(gamma),
+                                       B, k, V, _dtype_tag(z_d), temperature_t, _ptr(cutoff_t),
+                                       temperature_d, _ptr(cutoff_d), seed, step, _ptr(out_tokens),
+                                       _ptr(n_accept), _ptr(flags), _ptr(ratio), _ptr(ws),
+                                       0 if ws is None else ws.numel(), _stream(stream)))

@@ -48,14 +48,35 @@ struct StatsArgs {
   float* entropy_d;   // nullable
   float* pd_x;        // nullable
   uint32_t* flags;    // nullable
+  // warped entry point only (the stash kernel is the T = 1, whole-vocabulary path)
+  Scale sc_d, sc_c;       // exponent scales (temperatures) of the two tensors
+  const float* cut_d;     // nullable: support cutoff of every draft row
+  const float* cut_c;     // nullable: support cutoff of every companion row
 };
 
 // Online sweep of two rows at once (more independent loads in flight).
-template <int DT>
+// WARP: each row has its own exponent scale and support cutoff.
+template <int DT, bool WARP>
 __device__ __forceinline__ void sweep_online_pair(const void* ra, const void* rb, int V,
-                                                  Online& acc_a, Online& acc_b) {
+                                                  Online& acc_a, Online& acc_b,
+                                                  const float La, const float Lb, const float cut_a,
+                                                  const float cut_b) {
   constexpr int EPV = Elem<DT>::per_vec;
   const int tid = threadIdx.x, nt = blockDim.x;
+  auto add_vec = [&](const u32x4& q, Online& acc, const float L, const float cut) {
+    float f[EPV];
+    unpack<DT>(q, f);
+    if (WARP) {
+#pragma unroll
+      for (int j = 0; j < EPV; ++j) f[j] = cut_below(f[j], cut);
+    }
+    acc.add(f, L);
+  };
+  auto add_one = [&](int v) {
+    const float za = load_elem<DT>(ra, v), zb = load_elem<DT>(rb, v);
+    acc_a.add1(WARP ? cut_below(za, cut_a) : za, La);
+    acc_b.add1(WARP ? cut_below(zb, cut_b) : zb, Lb);
+  };
   if (aligned16(ra) && aligned16(rb)) {
     const u32x4* pa = reinterpret_cast<const u32x4*>(ra);
     const u32x4* pb = reinterpret_cast<const u32x4*>(rb);
@@ -63,27 +84,19 @@ __device__ __forceinline__ void sweep_online_pair(const void* ra, const void* rb
     int i = tid;
     for (; i + nt < nvec; i += 2 * nt) {
       const u32x4 a0 = pa[i], b0 = pb[i], a1 = pa[i + nt], b1 = pb[i + nt];
-      float f[EPV];
-      unpack<DT>(a0, f); acc_a.add(f);
-      unpack<DT>(b0, f); acc_b.add(f);
-      unpack<DT>(a1, f); acc_a.add(f);
-      unpack<DT>(b1, f); acc_b.add(f);
+      add_vec(a0, acc_a, La, cut_a);
+      add_vec(b0, acc_b, Lb, cut_b);
+      add_vec(a1, acc_a, La, cut_a);
+      add_vec(b1, acc_b, Lb, cut_b);
     }
     for (; i < nvec; i += nt) {
       const u32x4 a0 = pa[i], b0 = pb[i];
-      float f[EPV];
-      unpack<DT>(a0, f); acc_a.add(f);
-      unpack<DT>(b0, f); acc_b.add(f);
+      add_vec(a0, acc_a, La, cut_a);
+      add_vec(b0, acc_b, Lb, cut_b);
     }
-    for (int v = nvec * EPV + tid; v < V; v += nt) {
-      acc_a.add1(load_elem<DT>(ra, v));
-      acc_b.add1(load_elem<DT>(rb, v));
-    }
+    for (int v = nvec * EPV + tid; v < V; v += nt) add_one(v);
   } else {
-    for (int v = tid; v < V; v += nt) {
-      acc_a.add1(load_elem<DT>(ra, v));
-      acc_b.add1(load_elem<DT>(rb, v));
-    }
+    for (int v = tid; v < V; v += nt) add_one(v);
   }
 }
 
@@ -92,11 +105,12 @@ __device__ __forceinline__ void sweep_online_pair(const void* ra, const void* rb
 template <bool WITH_KL>
 struct MinAcc {
   float kd, kc, delta;
+  float Ld = kL32, Lc = kL32;          // exponent scales of the two rows
   float acc_s = 0.f, acc_kl = 0.f;
   float acc_pa = 0.f, acc_p = 0.f;     // sum P_d * log2-arg and sum P_d (draft entropy)
   __device__ __forceinline__ void add(float zd, float zc) {
-    const float ad = __builtin_fmaf(zd, kL32, -kd);
-    const float ac = __builtin_fmaf(zc, kL32, -kc) + delta;
+    const float ad = __builtin_fmaf(zd, Ld, -kd);
+    const float ac = __builtin_fmaf(zc, Lc, -kc) + delta;
     if (WITH_KL) {
       const float pd = exp2_fast(ad);
       acc_s += fminf(pd, exp2_fast(ac));
@@ -125,9 +139,10 @@ struct MinAcc {
 };
 
 // Scalar epilogue shared by both kernels: A, flags and the stores.
-template <int DT, bool WITH_KL>
+template <int DT, bool WITH_KL, bool WARP = false>
 __device__ __forceinline__ void stats_epilogue(const StatsArgs& a, int pair, const void* rd, const void* rc,
-                                               double lse_d, double lse_c, double S, double KL, double H_d) {
+                                               double lse_d, double lse_c, double S, double KL, double H_d,
+                                               const float cut_d = -INFINITY, const float cut_c = -INFINITY) {
   const bool bad = isnan(lse_d) || isnan(lse_c);
   uint32_t fl = bad ? SV_FLAG_BAD_ROW : 0u;
   double A = __builtin_nan(""), pdx = __builtin_nan("");
@@ -136,8 +151,14 @@ __device__ __forceinline__ void stats_epilogue(const StatsArgs& a, int pair, con
     if (tok < 0 || tok >= a.V) {
       fl |= SV_FLAG_BAD_TOKEN;
     } else {
-      const double ld = (double)load_elem<DT>(rd, tok) - lse_d;
-      const double lc = (double)load_elem<DT>(rc, tok) - lse_c;
+      float zxd = load_elem<DT>(rd, tok), zxc = load_elem<DT>(rc, tok);
+      double inv_td = 1.0, inv_tc = 1.0;
+      if (WARP) {
+        zxd = cut_below(zxd, cut_d); zxc = cut_below(zxc, cut_c);
+        inv_td = a.sc_d.inv_t; inv_tc = a.sc_c.inv_t;
+      }
+      const double ld = (double)zxd * inv_td - lse_d;
+      const double lc = (double)zxc * inv_tc - lse_c;
       A = (ld == -INFINITY) ? 1.0 : fmin(1.0, exp(lc - ld));
       pdx = exp(ld);
     }
@@ -166,20 +187,23 @@ struct PairConsts {
 
 // Folds the per-wavefront partials left by the first half of block_merge and
 // publishes the constants.  Must be called by all threads; ends with a barrier.
-__device__ __forceinline__ void publish_pair_consts(const Online (&on)[2], MergeScratch<2>& mg, PairConsts& pc) {
+__device__ __forceinline__ void publish_pair_consts(const Online (&on)[2], MergeScratch<2>& mg, PairConsts& pc,
+                                                    const Scale sc_d = unit_scale(), const Scale sc_c = unit_scale()) {
   const int wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
 #pragma unroll
   for (int r = 0; r < 2; ++r) {
     const float mw = wave_max_f32(on[r].m);
-    const double sw = wave_sum_f64((double)on[r].s * (double)exp2_fast(on[r].c - ref_of(mw)));
+    const float L = r == 0 ? sc_d.L : sc_c.L;
+    const double sw = wave_sum_f64((double)on[r].s * (double)exp2_fast(on[r].c - ref_of(mw, L)));
     if ((threadIdx.x & 63) == 0) { mg.m[r][wave] = mw; mg.s[r][wave] = sw; }
   }
   __syncthreads();
   if (threadIdx.x < 2) {
     const int r = threadIdx.x;
-    const MS ms = fold_parts(mg.m[r], mg.s[r], nw);
-    pc.lse[r] = lse_from_ms(ms);
-    pc.kappa[r] = kappa_l32(ms);
+    const Scale sc = r == 0 ? sc_d : sc_c;
+    const MS ms = fold_parts(mg.m[r], mg.s[r], nw, sc.L);
+    pc.lse[r] = lse_from_ms(ms, sc);
+    pc.kappa[r] = kappa_l32(ms, sc.L);
   }
   __syncthreads();
 }
@@ -348,7 +372,7 @@ __global__ __launch_bounds__(kStashThreads) void row_stats_stash_kernel(StatsArg
   if (tid == 0) stats_epilogue<DT, WITH_KL>(a, pair, pd, pc, lse_d, lse_c, S, KL, H_d);
 }
 
-template <int DT, bool WITH_KL>
+template <int DT, bool WITH_KL, bool WARP>
 __global__ __launch_bounds__(kStatsThreads) void row_stats_kernel(StatsArgs a) {
   __shared__ BlockScratch sm;
   __shared__ MergeScratch<2> mg;
@@ -358,11 +382,18 @@ __global__ __launch_bounds__(kStatsThreads) void row_stats_kernel(StatsArgs a) {
   const void* rd = static_cast<const char*>(a.z_d) + pair * row_bytes;
   const void* rc = static_cast<const char*>(a.z_c) + pair * row_bytes;
 
+  Scale sc_d = unit_scale(), sc_c = unit_scale();
+  float cut_d = -INFINITY, cut_c = -INFINITY;
+  if (WARP) {
+    sc_d = a.sc_d; sc_c = a.sc_c;
+    if (a.cut_d) cut_d = a.cut_d[pair];
+    if (a.cut_c) cut_c = a.cut_c[pair];
+  }
   Online on[2];
   on[0].init();
   on[1].init();
-  sweep_online_pair<DT>(rd, rc, a.V, on[0], on[1]);
-  publish_pair_consts(on, mg, consts);
+  sweep_online_pair<DT, WARP>(rd, rc, a.V, on[0], on[1], sc_d.L, sc_c.L, cut_d, cut_c);
+  publish_pair_consts(on, mg, consts, sc_d, sc_c);
   const double lse_d = consts.lse[0], lse_c = consts.lse[1];
   const bool bad = isnan(lse_d) || isnan(lse_c);
 
@@ -379,7 +410,11 @@ __global__ __launch_bounds__(kStatsThreads) void row_stats_kernel(StatsArgs a) {
     acc.kc = (float)kappa_c;
     const double tail_d = kappa_d - (double)acc.kd, tail_c = kappa_c - (double)acc.kc;
     acc.delta = (float)(tail_d - tail_c);
-    visit_range<DT, true>(rd, rc, 0, a.V, [&](int, float zd, float zc) { acc.add(zd, zc); });
+    acc.Ld = sc_d.L; acc.Lc = sc_c.L;
+    visit_range<DT, true>(rd, rc, 0, a.V, [&](int, float zd, float zc) {
+      if (WARP) { zd = cut_below(zd, cut_d); zc = cut_below(zc, cut_c); }
+      acc.add(zd, zc);
+    });
     S = block_sum_f64((double)acc.acc_s, sm);
     if (WITH_KL) {
       KL = block_sum_f64((double)acc.acc_kl, sm);
@@ -393,12 +428,18 @@ __global__ __launch_bounds__(kStatsThreads) void row_stats_kernel(StatsArgs a) {
       H_d *= -f_d * kLn2;
     }
   }
-  if (threadIdx.x == 0) stats_epilogue<DT, WITH_KL>(a, pair, rd, rc, lse_d, lse_c, S, KL, H_d);
+  if (threadIdx.x == 0)
+    stats_epilogue<DT, WITH_KL, WARP>(a, pair, rd, rc, lse_d, lse_c, S, KL, H_d, cut_d, cut_c);
 }
 
-template <int DT, bool WITH_KL>
+template <int DT, bool WITH_KL, bool WARP>
 static int launch_stats(const StatsArgs& a, bool rows_aligned, hipStream_t st) {
   const dim3 grid(a.B * a.k);
+  if (WARP) {
+    TapScope tap(SV_KERNEL_ROW_STATS, st);
+    hipLaunchKernelGGL((row_stats_kernel<DT, WITH_KL, true>), grid, dim3(kStatsThreads), 0, st, a);
+    return launch_status();
+  }
   if (rows_aligned) {
     // more than 64 KB of dynamic LDS has to be allowed once per kernel
     static bool allowed = false;
@@ -412,9 +453,46 @@ static int launch_stats(const StatsArgs& a, bool rows_aligned, hipStream_t st) {
     hipLaunchKernelGGL((row_stats_stash_kernel<DT, WITH_KL>), grid, dim3(kStashThreads), kStashLdsBytes, st, a);
   } else {
     TapScope tap(SV_KERNEL_ROW_STATS, st);
-    hipLaunchKernelGGL((row_stats_kernel<DT, WITH_KL>), grid, dim3(kStatsThreads), 0, st, a);
+    hipLaunchKernelGGL((row_stats_kernel<DT, WITH_KL, false>), grid, dim3(kStatsThreads), 0, st, a);
   }
   return launch_status();
+}
+
+// Argument checks and launch shared by sv_row_stats and sv_row_stats_warped.
+static int row_stats_checked(const void* z_d, const void* z_c, const int32_t* x, int B, int k, int V, int dtype,
+                             bool warped, const Scale& sc_d, const float* cut_d, const Scale& sc_c,
+                             const float* cut_c, float* lse_d, float* lse_c, float* S, float* A, float* kl,
+                             float* entropy_d, float* pd_x, uint32_t* flags, void* ws, size_t ws_bytes,
+                             sv_stream_t stream) {
+  SV_REQUIRE(dtype == SV_F32 || dtype == SV_BF16, SV_ERR_DTYPE);
+  SV_REQUIRE(B >= 0 && k >= 1 && V >= 1, SV_ERR_INVALID_ARG);
+  SV_REQUIRE((long long)B * k <= 0x7fffffffLL, SV_ERR_TOO_LARGE);
+  if (B == 0) return SV_OK;
+  SV_REQUIRE(z_d && z_c && x && lse_d && lse_c && S && A, SV_ERR_NULL);
+  const int eb = elem_bytes(dtype);
+  SV_REQUIRE(is_aligned(z_d, eb) && is_aligned(z_c, eb), SV_ERR_ALIGN);
+  SV_REQUIRE(is_aligned(x, 4) && is_aligned(lse_d, 4) && is_aligned(lse_c, 4) && is_aligned(S, 4) &&
+                 is_aligned(A, 4) && is_aligned(kl, 4) && is_aligned(entropy_d, 4) && is_aligned(pd_x, 4) &&
+                 is_aligned(flags, 4) && is_aligned(cut_d, 4) && is_aligned(cut_c, 4),
+             SV_ERR_ALIGN);
+  SV_REQUIRE(ws && is_aligned(ws, kWsAlign) && ws_bytes >= sv_workspace_bytes(B, k, V, dtype),
+             SV_ERR_WORKSPACE);
+  StatsArgs a{z_d, z_c, x, B, k, V, lse_d, lse_c, S, A, kl, entropy_d, pd_x, flags, sc_d, sc_c, cut_d, cut_c};
+  const bool extended = kl || entropy_d;   // sums that need P_d of every entry
+  const bool rows_aligned = is_aligned(z_d, 16) && is_aligned(z_c, 16) && ((size_t)V * eb) % 16 == 0;
+  hipStream_t st = as_stream(stream);
+  if (warped) {
+    if (dtype == SV_F32)
+      return extended ? launch_stats<DT_F32, true, true>(a, rows_aligned, st)
+                      : launch_stats<DT_F32, false, true>(a, rows_aligned, st);
+    return extended ? launch_stats<DT_BF16, true, true>(a, rows_aligned, st)
+                    : launch_stats<DT_BF16, false, true>(a, rows_aligned, st);
+  }
+  if (dtype == SV_F32)
+    return extended ? launch_stats<DT_F32, true, false>(a, rows_aligned, st)
+                    : launch_stats<DT_F32, false, false>(a, rows_aligned, st);
+  return extended ? launch_stats<DT_BF16, true, false>(a, rows_aligned, st)
+                  : launch_stats<DT_BF16, false, false>(a, rows_aligned, st);
 }
 
 }  // namespace sv
@@ -426,25 +504,23 @@ extern "C" int sv_row_stats(const void* z_d, const void* z_c, const int32_t* x,
                             uint32_t* flags_or_null,
                             void* ws, size_t ws_bytes, sv_stream_t stream) {
   using namespace sv;
-  SV_REQUIRE(dtype == SV_F32 || dtype == SV_BF16, SV_ERR_DTYPE);
-  SV_REQUIRE(B >= 0 && k >= 1 && V >= 1, SV_ERR_INVALID_ARG);
-  SV_REQUIRE((long long)B * k <= 0x7fffffffLL, SV_ERR_TOO_LARGE);
-  if (B == 0) return SV_OK;
-  SV_REQUIRE(z_d && z_c && x && lse_d && lse_c && S && A, SV_ERR_NULL);
-  const int eb = elem_bytes(dtype);
-  SV_REQUIRE(is_aligned(z_d, eb) && is_aligned(z_c, eb), SV_ERR_ALIGN);
-  SV_REQUIRE(is_aligned(x, 4) && is_aligned(lse_d, 4) && is_aligned(lse_c, 4) && is_aligned(S, 4) &&
-                 is_aligned(A, 4) && is_aligned(kl_or_null, 4) && is_aligned(entropy_d_or_null, 4) &&
-                 is_aligned(pd_x_or_null, 4) && is_aligned(flags_or_null, 4),
-             SV_ERR_ALIGN);
-  SV_REQUIRE(ws && is_aligned(ws, kWsAlign) && ws_bytes >= sv_workspace_bytes(B, k, V, dtype),
-             SV_ERR_WORKSPACE);
-  StatsArgs a{z_d, z_c, x, B, k, V, lse_d, lse_c, S, A, kl_or_null, entropy_d_or_null, pd_x_or_null,
-              flags_or_null};
-  const bool extended = kl_or_null || entropy_d_or_null;   // sums that need P_d of every entry
-  const bool rows_aligned = is_aligned(z_d, 16) && is_aligned(z_c, 16) && ((size_t)V * eb) % 16 == 0;
-  hipStream_t st = as_stream(stream);
-  if (dtype == SV_F32)
-    return extended ? launch_stats<DT_F32, true>(a, rows_aligned, st) : launch_stats<DT_F32, false>(a, rows_aligned, st);
-  return extended ? launch_stats<DT_BF16, true>(a, rows_aligned, st) : launch_stats<DT_BF16, false>(a, rows_aligned, st);
+  return row_stats_checked(z_d, z_c, x, B, k, V, dtype, false, unit_scale(), nullptr, unit_scale(), nullptr,
+                           lse_d, lse_c, S, A, kl_or_null, entropy_d_or_null, pd_x_or_null, flags_or_null, ws,
+                           ws_bytes, stream);
+}
+
+extern "C" int sv_row_stats_warped(const void* z_d, const void* z_c, const int32_t* x,
+                                   int B, int k, int V, int dtype,
+                                   float temperature_d, const float* cutoff_d_or_null,
+                                   float temperature_c, const float* cutoff_c_or_null,
+                                   float* lse_d, float* lse_c, float* S, float* A,
+                                   float* kl_or_null, float* entropy_d_or_null, float* pd_x_or_null,
+                                   uint32_t* flags_or_null,
+                                   void* ws, size_t ws_bytes, sv_stream_t stream) {
+  using namespace sv;
+  Scale sc_d, sc_c;
+  SV_REQUIRE(scale_of(temperature_d, &sc_d) && scale_of(temperature_c, &sc_c), SV_ERR_INVALID_ARG);
+  return row_stats_checked(z_d, z_c, x, B, k, V, dtype, true, sc_d, cutoff_d_or_null, sc_c, cutoff_c_or_null,
+                           lse_d, lse_c, S, A, kl_or_null, entropy_d_or_null, pd_x_or_null, flags_or_null, ws,
+                           ws_bytes, stream);
 }

@@ -6,11 +6,13 @@
 //  * Philox-4x32-10 for the speculative-sampling uniforms
 //
 // A row's normaliser is carried as the pair (m, s): m = the row maximum in raw
-// logit units and s = sum_v 2^(z_v * L32 - c(m)), c(m) = fl32(max(m, -1e38) * L32),
-// where L32 is log2(e) rounded to fp32.  Because L32 / log2(e) = 1 + 1.33e-8 the
-// sum is the soft-max normaliser at a temperature off by that factor; the fp64
+// logit units and s = sum_v 2^(z_v * L - c(m)), c(m) = max(fl32(m * L), -1e38),
+// where L is log2(e) / T rounded to fp32 (T = sampling temperature of the
+// tensor, 1 unless a warped entry point says otherwise; L32 is the T = 1 value).
+// Because L T / log2(e) = 1 + tau1 with |tau1| < 6e-8 (1.33e-8 for L32) the sum
+// is the soft-max normaliser at a temperature off by that factor; the fp64
 // epilogue removes the first-order effect around the row maximum
-// (lse_from_ms), leaving an error below 1.4e-8 * (H - H_inf) of the row.
+// (lse_from_ms), leaving an error below |tau1| * (H - H_inf) of the row.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -24,6 +26,34 @@ constexpr double kLog2e = 1.4426950408889634073599246810019;  // log2 e
 constexpr double kLn2 = 0.69314718055994530941723212145818;
 constexpr double kTauMinus1 = (double)kL32 / kLog2e - 1.0;   // ~ +1.33e-8
 constexpr float kRefFloor = -1.0e38f;                         // keeps c(m) finite
+
+// Exponent scale of one logit tensor: 2^(z L) = e^((z / T) (1 + tau1)).
+struct Scale {
+  float L;        // fl32(log2(e) / T)
+  double l_lo;    // log2(e) / T - L, the part of the scale that fp32 drops
+  double inv_t;   // 1 / T
+  double tau1;    // L T / log2(e) - 1
+};
+
+// T = 1: the constants every unwarped kernel folds at compile time.
+__host__ __device__ constexpr Scale unit_scale() {
+  return Scale{kL32, kLog2e - (double)kL32, 1.0, kTauMinus1};
+}
+
+// Scale of a caller-given temperature; false outside [1e-3, 1e3] (or NaN).
+inline bool scale_of(float temperature, Scale* sc) {
+  if (!(temperature >= 1e-3f && temperature <= 1e3f)) return false;
+  const double t = (double)temperature, l = kLog2e / t;
+  sc->L = (float)l;
+  sc->l_lo = l - (double)sc->L;
+  sc->inv_t = 1.0 / t;
+  sc->tau1 = (double)sc->L * t / kLog2e - 1.0;
+  return true;
+}
+
+// Entries below a row's cutoff are outside the warped distribution's support;
+// NaN entries stay NaN so that a bad row is still seen as one.
+__device__ __forceinline__ float cut_below(float z, float cut) { return z < cut ? -INFINITY : z; }
 
 enum { DT_F32 = 0, DT_BF16 = 1 };
 
@@ -67,26 +97,26 @@ __device__ __forceinline__ bool aligned16(const void* p) {
 }
 
 // ---------------------------------------------------------------------------
-// online (max, sum 2^(z L32 - c)) accumulator, one per lane
+// online (max, sum 2^(z L - c)) accumulator, one per lane
 // ---------------------------------------------------------------------------
 struct Online {
   float m;   // running maximum (raw units); -inf before the first element
-  float c;   // fl32(max(m, kRefFloor) * L32)
-  float s;   // sum of 2^(z*L32 - c) so far
+  float c;   // max(fl32(m * L), kRefFloor)
+  float s;   // sum of 2^(z*L - c) so far
 
-  __device__ __forceinline__ void init() { m = -INFINITY; c = kRefFloor * kL32; s = 0.f; }
+  __device__ __forceinline__ void init() { m = -INFINITY; c = kRefFloor; s = 0.f; }
 
   template <int N>
-  __device__ __forceinline__ void add(const float (&z)[N]) {
+  __device__ __forceinline__ void add(const float (&z)[N], const float L = kL32) {
     float mx = m;
 #pragma unroll
     for (int j = 0; j + 1 < N; j += 2) mx = fmaxf(fmaxf(mx, z[j]), z[j + 1]);   // v_max3_f32
     if (N & 1) mx = fmaxf(mx, z[N - 1]);
-    const float cn = fmaxf(mx, kRefFloor) * kL32;
+    const float cn = fmaxf(mx * L, kRefFloor);
     const float scale = exp2_fast(c - cn);
     float e[N];
 #pragma unroll
-    for (int j = 0; j < N; ++j) e[j] = exp2_fast(__builtin_fmaf(z[j], kL32, -cn));
+    for (int j = 0; j < N; ++j) e[j] = exp2_fast(__builtin_fmaf(z[j], L, -cn));
     // pairwise tree so that no single chain carries all roundings
     float t = 0.f;
     if constexpr (N == 8) {
@@ -102,10 +132,10 @@ struct Online {
     c = cn;
   }
 
-  __device__ __forceinline__ void add1(float z) {
+  __device__ __forceinline__ void add1(float z, const float L = kL32) {
     const float mx = fmaxf(m, z);
-    const float cn = fmaxf(mx, kRefFloor) * kL32;
-    s = __builtin_fmaf(s, exp2_fast(c - cn), exp2_fast(__builtin_fmaf(z, kL32, -cn)));
+    const float cn = fmaxf(mx * L, kRefFloor);
+    s = __builtin_fmaf(s, exp2_fast(c - cn), exp2_fast(__builtin_fmaf(z, L, -cn)));
     m = mx;
     c = cn;
   }
@@ -117,7 +147,7 @@ struct MS {
   double s;
 };
 
-__device__ __forceinline__ float ref_of(float m) { return fmaxf(m, kRefFloor) * kL32; }
+__device__ __forceinline__ float ref_of(float m, const float L = kL32) { return fmaxf(m * L, kRefFloor); }
 
 __device__ __forceinline__ double shfl_xor_f64(double v, int mask) {
   int lo = __double2loint(v), hi = __double2hiint(v);
@@ -179,12 +209,13 @@ struct MergeScratch {
 };
 
 template <int NR>
-__device__ __forceinline__ void block_merge(const Online (&o)[NR], MergeScratch<NR>& sm, MS (&out)[NR]) {
+__device__ __forceinline__ void block_merge(const Online (&o)[NR], MergeScratch<NR>& sm, MS (&out)[NR],
+                                            const float L = kL32) {
   const int wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
 #pragma unroll
   for (int r = 0; r < NR; ++r) {
     const float mw = wave_max_f32(o[r].m);
-    const double sw = wave_sum_f64((double)o[r].s * (double)exp2_fast(o[r].c - ref_of(mw)));
+    const double sw = wave_sum_f64((double)o[r].s * (double)exp2_fast(o[r].c - ref_of(mw, L)));
     if ((threadIdx.x & 63) == 0) { sm.m[r][wave] = mw; sm.s[r][wave] = sw; }
   }
   __syncthreads();
@@ -192,39 +223,40 @@ __device__ __forceinline__ void block_merge(const Online (&o)[NR], MergeScratch<
   for (int r = 0; r < NR; ++r) {
     float m = sm.m[r][0];
     for (int w = 1; w < nw; ++w) m = fmaxf(m, sm.m[r][w]);
-    const float cr = ref_of(m);
+    const float cr = ref_of(m, L);
     double acc = 0.0;
-    for (int w = 0; w < nw; ++w) acc += sm.s[r][w] * (double)exp2_fast(ref_of(sm.m[r][w]) - cr);
+    for (int w = 0; w < nw; ++w) acc += sm.s[r][w] * (double)exp2_fast(ref_of(sm.m[r][w], L) - cr);
     out[r].m = m;
     out[r].s = acc;
   }
 }
 
 // Row normaliser in fp64 from (m, s):  log2-domain kappa = c(m) + log2 s is the
-// log2 of sum_v 2^(z_v L32); the natural-log LSE follows after removing the
-// temperature offset around the maximum.  Bad rows (NaN, +inf, no finite
-// entry) give NaN.
-__device__ __forceinline__ double lse_from_ms(const MS& r) {
+// log2 of sum_v 2^(z_v L); the natural-log LSE of the row z / T follows after
+// removing the temperature offset around the maximum.  Bad rows (NaN, +inf, no
+// finite entry) give NaN.
+__device__ __forceinline__ double lse_from_ms(const MS& r, const Scale sc = unit_scale()) {
   if (!(r.s > 0.0) || !isfinite(r.s) || !isfinite(r.m)) return __builtin_nan("");
-  const double kappa = (double)ref_of(r.m) + log2(r.s);
-  return kappa * kLn2 - kTauMinus1 * (double)r.m;
+  const double kappa = (double)ref_of(r.m, sc.L) + log2(r.s);
+  return kappa * kLn2 - sc.tau1 * ((double)r.m * sc.inv_t);
 }
 
-// log2 of sum_v 2^(z_v L32): the normaliser that makes 2^(z L32 - kappa) sum to
-// one.  Those probabilities are the soft-max at temperature L32/log2(e); entry
-// v deviates from the exact one by a relative 1.33e-8 * (z_v - E_p[z]).
-__device__ __forceinline__ double kappa_l32(const MS& r) {
-  return (double)ref_of(r.m) + log2(r.s);
+// log2 of sum_v 2^(z_v L): the normaliser that makes 2^(z L - kappa) sum to
+// one.  Those probabilities are the soft-max of z / T at temperature 1 + tau1;
+// entry v deviates from the exact one by a relative tau1 * (y_v - E_p[y]),
+// y = z / T (1.33e-8 per unit for L32).
+__device__ __forceinline__ double kappa_l32(const MS& r, const float L = kL32) {
+  return (double)ref_of(r.m, L) + log2(r.s);
 }
 
 // Fold the `split` partial normalisers of one row (consecutive entries).
-__device__ __forceinline__ MS fold_parts(const float* m, const double* s, int split) {
+__device__ __forceinline__ MS fold_parts(const float* m, const double* s, int split, const float L = kL32) {
   MS r;
   r.m = m[0];
   for (int p = 1; p < split; ++p) r.m = fmaxf(r.m, m[p]);
-  const float cr = ref_of(r.m);
+  const float cr = ref_of(r.m, L);
   r.s = 0.0;
-  for (int p = 0; p < split; ++p) r.s += s[p] * (double)exp2_fast(ref_of(m[p]) - cr);
+  for (int p = 0; p < split; ++p) r.s += s[p] * (double)exp2_fast(ref_of(m[p], L) - cr);
   return r;
 }
 
@@ -234,10 +266,24 @@ __device__ __forceinline__ MS fold_parts(const float* m, const double* s, int sp
 // also takes the scalar tail); rows that do not start on 16 bytes are split by
 // elements and read with scalar loads.
 // ---------------------------------------------------------------------------
-template <int DT>
-__device__ __forceinline__ void sweep_online(const void* row, int V, int part, int split, Online& acc) {
+template <int DT, bool CUT = false>
+__device__ __forceinline__ void sweep_online(const void* row, int V, int part, int split, Online& acc,
+                                             const float L = kL32, const float cut = -INFINITY) {
   constexpr int EPV = Elem<DT>::per_vec;
   const int tid = threadIdx.x, nt = blockDim.x;
+  auto add_vec = [&](const u32x4& q) {
+    float f[EPV];
+    unpack<DT>(q, f);
+    if (CUT) {
+#pragma unroll
+      for (int j = 0; j < EPV; ++j) f[j] = cut_below(f[j], cut);
+    }
+    acc.add(f, L);
+  };
+  auto add_one = [&](int v) {
+    const float z = load_elem<DT>(row, v);
+    acc.add1(CUT ? cut_below(z, cut) : z, L);
+  };
   if (aligned16(row)) {
     const u32x4* p = reinterpret_cast<const u32x4*>(row);
     const int nvec = V / EPV;
@@ -249,24 +295,15 @@ __device__ __forceinline__ void sweep_online(const void* row, int V, int part, i
       const u32x4 q1 = __builtin_nontemporal_load(p + i + nt);
       const u32x4 q2 = __builtin_nontemporal_load(p + i + 2 * nt);
       const u32x4 q3 = __builtin_nontemporal_load(p + i + 3 * nt);
-      float f[EPV];
-      unpack<DT>(q0, f); acc.add(f);
-      unpack<DT>(q1, f); acc.add(f);
-      unpack<DT>(q2, f); acc.add(f);
-      unpack<DT>(q3, f); acc.add(f);
+      add_vec(q0); add_vec(q1); add_vec(q2); add_vec(q3);
     }
-    for (; i < end; i += nt) {
-      const u32x4 q = __builtin_nontemporal_load(p + i);
-      float f[EPV];
-      unpack<DT>(q, f);
-      acc.add(f);
-    }
+    for (; i < end; i += nt) add_vec(__builtin_nontemporal_load(p + i));
     if (part == split - 1)
-      for (int v = nvec * EPV + tid; v < V; v += nt) acc.add1(load_elem<DT>(row, v));
+      for (int v = nvec * EPV + tid; v < V; v += nt) add_one(v);
   } else {
     const int per = (V + split - 1) / split;
     const int end = min(V, (part + 1) * per);
-    for (int v = part * per + tid; v < end; v += nt) acc.add1(load_elem<DT>(row, v));
+    for (int v = part * per + tid; v < end; v += nt) add_one(v);
   }
 }
 

@@ -54,6 +54,9 @@ struct VerifyArgs {
   int32_t* n_accept;
   uint32_t* flags;
   float* ratio;               // nullable
+  Scale sc_t, sc_d;           // exponent scales (temperatures) of the two tensors
+  const float* cut_t;         // nullable: support cutoff of every row of z_t
+  const float* cut_d;         // nullable: support cutoff of every row of z_d
   VerifyWs ws;
 };
 
@@ -62,17 +65,31 @@ __device__ __forceinline__ int gamma_of(const VerifyArgs& a, int b) {
   return min(max(g, 0), a.k);
 }
 
+// Row number in z_t of target position (b, i), or -1 when a packed offset
+// points outside z_t.
+__device__ __forceinline__ long target_index(const VerifyArgs& a, int b, int i) {
+  if (a.t_offsets) {
+    const long row = (long)a.t_offsets[b] + i;
+    return (row < 0 || row >= a.n_t_rows) ? -1 : row;
+  }
+  return (long)b * a.t_seq_rows + i;
+}
+
 // Target row of (b, i), or nullptr when a packed offset points outside z_t.
 template <int DT>
 __device__ __forceinline__ const void* target_row(const VerifyArgs& a, int b, int i) {
-  long row;
-  if (a.t_offsets) {
-    row = (long)a.t_offsets[b] + i;
-    if (row < 0 || row >= a.n_t_rows) return nullptr;
-  } else {
-    row = (long)b * a.t_seq_rows + i;
-  }
+  const long row = target_index(a, b, i);
+  if (row < 0) return nullptr;
   return static_cast<const char*>(a.z_t) + (size_t)row * a.V * Elem<DT>::bytes;
+}
+
+// Support cutoffs of the warped entry point (-inf: the whole vocabulary).
+__device__ __forceinline__ float target_cut(const VerifyArgs& a, int b, int i) {
+  const long row = target_index(a, b, i);
+  return (a.cut_t && row >= 0) ? a.cut_t[row] : -INFINITY;
+}
+__device__ __forceinline__ float draft_cut(const VerifyArgs& a, int b, int i) {
+  return a.cut_d ? a.cut_d[b * a.k + i] : -INFINITY;
 }
 
 template <int DT>
@@ -83,17 +100,17 @@ __device__ __forceinline__ const void* draft_row(const VerifyArgs& a, int b, int
 // Normaliser of a whole row from the partials its workgroups left.
 __device__ __forceinline__ MS target_ms(const VerifyArgs& a, int b, int i) {
   const int idx = (b * (a.k + 1) + i) * a.split;
-  return fold_parts(a.ws.m_t + idx, a.ws.s_t + idx, a.split);
+  return fold_parts(a.ws.m_t + idx, a.ws.s_t + idx, a.split, a.sc_t.L);
 }
 __device__ __forceinline__ MS draft_ms(const VerifyArgs& a, int b, int i) {
   const int idx = (b * a.k + i) * a.split;
-  return fold_parts(a.ws.m_d + idx, a.ws.s_d + idx, a.split);
+  return fold_parts(a.ws.m_d + idx, a.ws.s_d + idx, a.split, a.sc_d.L);
 }
 
 // ---------------------------------------------------------------------------
 // kernel 1: row normalisers
 // ---------------------------------------------------------------------------
-template <int DT>
+template <int DT, bool CUT>
 __global__ __launch_bounds__(kRowsThreads) void verify_rows_kernel(VerifyArgs a) {
   __shared__ MergeScratch<1> sm;
   const int per_seq = 2 * a.k + 1;
@@ -107,17 +124,21 @@ __global__ __launch_bounds__(kRowsThreads) void verify_rows_kernel(VerifyArgs a)
   if (i >= (is_target ? g + a.with_bonus : g)) return;   // not needed: no bytes read
 
   const void* row = is_target ? target_row<DT>(a, b, i) : draft_row<DT>(a, b, i);
+  const float L = is_target ? a.sc_t.L : a.sc_d.L;
+  float cut = -INFINITY;
+  if (CUT) cut = is_target ? target_cut(a, b, i) : draft_cut(a, b, i);
   Online acc[1];
   acc[0].init();
-  if (row) sweep_online<DT>(row, a.V, part, a.split, acc[0]);
+  if (row) sweep_online<DT, CUT>(row, a.V, part, a.split, acc[0], L, cut);
   MS merged[1];
-  block_merge<1>(acc, sm, merged);
+  block_merge<1>(acc, sm, merged, L);
   const MS ms = merged[0];
   if (threadIdx.x == 0) {
     float zx = __builtin_nanf("");
     if (part == 0 && i < a.k && row) {
       const int tok = a.x[b * a.k + i];
       if (tok >= 0 && tok < a.V) zx = load_elem<DT>(row, tok);
+      if (CUT) zx = cut_below(zx, cut);
     }
     if (is_target) {
       const int idx = (b * (a.k + 1) + i) * a.split + part;
@@ -136,22 +157,24 @@ __global__ __launch_bounds__(kRowsThreads) void verify_rows_kernel(VerifyArgs a)
 // ---------------------------------------------------------------------------
 // kernel 2: accept count, chunk masses, token
 // ---------------------------------------------------------------------------
-// Probability of one vocabulary entry: 2^(z L - kappa) with L = log2 e carried
-// as L32 + l_lo and kappa = k_hi + k_lo, so that neither the rounding of the
-// constant nor that of the row normaliser biases every entry of a row the
-// same way: p = e * (1 + ln2 * (z l_lo - k_lo)), e = 2^(z L32 - k_hi).
+// Probability of one vocabulary entry: 2^(z l - kappa) with l = log2(e) / T
+// carried as L + l_lo and kappa = k_hi + k_lo, so that neither the rounding of
+// the scale nor that of the row normaliser biases every entry of a row the
+// same way: p = e * (1 + ln2 * (z l_lo - k_lo)), e = 2^(z L - k_hi).
 struct ProbRow {
+  float L;         // fl32(log2(e) / T)
   float k_hi;      // fl32(kappa)
-  float lo_mul;    // ln2 * (log2 e - L32)
+  float lo_mul;    // ln2 * (log2(e) / T - L)
   float lo_add;    // -ln2 * (kappa - k_hi)
-  __device__ __forceinline__ void set(double lse) {
+  __device__ __forceinline__ void set(double lse, const Scale& sc) {
     const double kappa = lse * kLog2e;
+    L = sc.L;
     k_hi = (float)kappa;
-    lo_mul = (float)(kLn2 * (kLog2e - (double)kL32));
+    lo_mul = (float)(kLn2 * sc.l_lo);
     lo_add = (float)(-kLn2 * (kappa - (double)k_hi));
   }
   __device__ __forceinline__ float p(float z) const {
-    const float e = exp2_fast(__builtin_fmaf(z, kL32, -k_hi));
+    const float e = exp2_fast(__builtin_fmaf(z, L, -k_hi));
     const float corr = __builtin_fmaf(z, lo_mul, lo_add);
     return e > 0.f ? __builtin_fmaf(e, corr, e) : 0.f;   // z = -inf: corr is inf, mass is 0
   }
@@ -172,12 +195,12 @@ __global__ __launch_bounds__(kWave) void accept_ratio_kernel(VerifyArgs a, float
     if (tok < 0 || tok >= a.V) {
       fl |= SV_FLAG_BAD_TOKEN;
     } else {
-      const double lse_t = lse_from_ms(target_ms(a, b, i)), lse_d = lse_from_ms(draft_ms(a, b, i));
+      const double lse_t = lse_from_ms(target_ms(a, b, i), a.sc_t), lse_d = lse_from_ms(draft_ms(a, b, i), a.sc_d);
       if (isnan(lse_t) || isnan(lse_d)) {
         fl |= SV_FLAG_BAD_ROW;
       } else {
-        const double lt = (double)a.ws.zx_t[b * k + i] - lse_t;
-        const double ld = (double)a.ws.zx_d[b * k + i] - lse_d;
+        const double lt = (double)a.ws.zx_t[b * k + i] * a.sc_t.inv_t - lse_t;
+        const double ld = (double)a.ws.zx_d[b * k + i] * a.sc_d.inv_t - lse_d;
         rho = exp(lt - ld);
       }
     }
@@ -213,18 +236,18 @@ __global__ __launch_bounds__(kWave) void verify_accept_kernel(VerifyArgs a) {
   bool have_target = false;
   if (i <= g) {                                   // target rows 0..g (row g: bonus position)
     have_target = target_row<DT>(a, b, i) != nullptr;
-    lse_t = lse_from_ms(target_ms(a, b, i));
+    lse_t = lse_from_ms(target_ms(a, b, i), a.sc_t);
   }
   if (evaluated) {
-    lse_d = lse_from_ms(draft_ms(a, b, i));
+    lse_d = lse_from_ms(draft_ms(a, b, i), a.sc_d);
     const int tok = a.x[b * k + i];
     if (tok < 0 || tok >= V) {
       fl |= SV_FLAG_BAD_TOKEN;
     } else if (isnan(lse_t) || isnan(lse_d)) {
       fl |= SV_FLAG_BAD_ROW;
     } else {
-      const double lt = (double)a.ws.zx_t[b * k + i] - lse_t;
-      const double ld = (double)a.ws.zx_d[b * k + i] - lse_d;
+      const double lt = (double)a.ws.zx_t[b * k + i] * a.sc_t.inv_t - lse_t;
+      const double ld = (double)a.ws.zx_d[b * k + i] * a.sc_d.inv_t - lse_d;
       rho = exp(lt - ld);                         // -inf - -inf = NaN: rejected
     }
     const U4 r = philox4x32_10((uint32_t)i, (uint32_t)b, 0u, a.step, a.seed_lo, a.seed_hi);
@@ -262,7 +285,7 @@ struct MassShared {
 };
 
 // grid (chunks, B): residual and target mass of one chunk of the sampling row.
-template <int DT>
+template <int DT, bool CUT>
 __global__ __launch_bounds__(kSampleThreads) void verify_mass_kernel(VerifyArgs a) {
   __shared__ MassShared sh;
   const int b = blockIdx.y, c = blockIdx.x, C = gridDim.x;
@@ -274,20 +297,26 @@ __global__ __launch_bounds__(kSampleThreads) void verify_mass_kernel(VerifyArgs 
   const void* row_t = target_row<DT>(a, b, n);
   const void* row_d = resid ? draft_row<DT>(a, b, n) : nullptr;
   ProbRow pt, pd;
-  pt.set(target_ok ? pl.lse_t : 0.0);
-  pd.set(pl.lse_d);
+  pt.set(target_ok ? pl.lse_t : 0.0, a.sc_t);
+  pd.set(pl.lse_d, a.sc_d);
+  float cut_t = -INFINITY, cut_d = -INFINITY;
+  if (CUT) { cut_t = target_cut(a, b, n); if (resid) cut_d = draft_cut(a, b, n); }
 
   const int v0 = c * kChunk, v1 = min(V, v0 + kChunk);
   float acc_r = 0.f, acc_t = 0.f;
   if (target_ok) {
     if (resid) {
       visit_range<DT, true, 4>(row_t, row_d, v0, v1, [&](int, float zt, float zd) {
+        if (CUT) { zt = cut_below(zt, cut_t); zd = cut_below(zd, cut_d); }
         const float p = pt.p(zt);
         acc_t += p;
         acc_r += fmaxf(0.f, p - pd.p(zd));
       });
     } else {
-      visit_range<DT, false, 4>(row_t, nullptr, v0, v1, [&](int, float zt, float) { acc_t += pt.p(zt); });
+      visit_range<DT, false, 4>(row_t, nullptr, v0, v1, [&](int, float zt, float) {
+        if (CUT) zt = cut_below(zt, cut_t);
+        acc_t += pt.p(zt);
+      });
     }
   }
   const double mass_r = block_sum_f64((double)acc_r, sh.red);
@@ -315,7 +344,7 @@ static_assert(sizeof(double) * 2 * kMaxChunks <= sizeof(float) * (kChunk + kChun
 
 // grid (B): scan the chunk masses of the sequence, locate the chunk holding
 // u' * W, stage its weights in LDS and find the token with a block prefix scan.
-template <int DT>
+template <int DT, bool CUT>
 __global__ __launch_bounds__(kSampleThreads) void verify_pick_kernel(VerifyArgs a, int C) {
   __shared__ PickShared sh;
   const int b = blockIdx.x;
@@ -328,8 +357,10 @@ __global__ __launch_bounds__(kSampleThreads) void verify_pick_kernel(VerifyArgs 
   const void* row_t = target_row<DT>(a, b, n);
   const void* row_d = resid ? draft_row<DT>(a, b, n) : nullptr;
   ProbRow pt, pd;
-  pt.set(target_ok ? pl.lse_t : 0.0);
-  pd.set(resid ? pl.lse_d : 0.0);
+  pt.set(target_ok ? pl.lse_t : 0.0, a.sc_t);
+  pd.set(resid ? pl.lse_d : 0.0, a.sc_d);
+  float cut_t = -INFINITY, cut_d = -INFINITY;
+  if (CUT) { cut_t = target_cut(a, b, n); if (resid) cut_d = draft_cut(a, b, n); }
 
   for (int j = tid; j < C; j += blockDim.x) {          // all chunk masses in one round of loads
     sh.mass[j] = a.ws.mass_r[(size_t)b * C + j];
@@ -386,10 +417,14 @@ __global__ __launch_bounds__(kSampleThreads) void verify_pick_kernel(VerifyArgs 
   for (int j = (w1 - w0) + tid; j < kChunk; j += blockDim.x) sh.w[skew(j)] = 0.f;
   if (use_resid) {
     visit_range<DT, true, 4>(row_t, row_d, w0, w1, [&](int v, float zt, float zd) {
+      if (CUT) { zt = cut_below(zt, cut_t); zd = cut_below(zd, cut_d); }
       sh.w[skew(v - w0)] = fmaxf(0.f, pt.p(zt) - pd.p(zd));
     });
   } else {
-    visit_range<DT, false, 4>(row_t, nullptr, w0, w1, [&](int v, float zt, float) { sh.w[skew(v - w0)] = pt.p(zt); });
+    visit_range<DT, false, 4>(row_t, nullptr, w0, w1, [&](int v, float zt, float) {
+      if (CUT) zt = cut_below(zt, cut_t);
+      sh.w[skew(v - w0)] = pt.p(zt);
+    });
   }
   __syncthreads();
 
@@ -459,12 +494,12 @@ static int rows_split(int rows, int V) {
   return std::max(1, std::min(s, kMaxSplit));
 }
 
-template <int DT>
+template <int DT, bool CUT>
 static int launch_verify(const VerifyArgs& a, hipStream_t st) {
   const int rows = a.B * (2 * a.k + 1);
   {
     TapScope tap(SV_KERNEL_VERIFY_ROWS, st);
-    hipLaunchKernelGGL(verify_rows_kernel<DT>, dim3(rows * a.split), dim3(kRowsThreads), 0, st, a);
+    hipLaunchKernelGGL((verify_rows_kernel<DT, CUT>), dim3(rows * a.split), dim3(kRowsThreads), 0, st, a);
   }
   if (launch_status() != SV_OK) return SV_ERR_LAUNCH;
   {
@@ -475,14 +510,53 @@ static int launch_verify(const VerifyArgs& a, hipStream_t st) {
   const int C = n_chunks(a.V);
   {
     TapScope tap(SV_KERNEL_VERIFY_MASS, st);
-    hipLaunchKernelGGL(verify_mass_kernel<DT>, dim3(C, a.B), dim3(kSampleThreads), 0, st, a);
+    hipLaunchKernelGGL((verify_mass_kernel<DT, CUT>), dim3(C, a.B), dim3(kSampleThreads), 0, st, a);
   }
   if (launch_status() != SV_OK) return SV_ERR_LAUNCH;
   {
     TapScope tap(SV_KERNEL_VERIFY_PICK, st);
-    hipLaunchKernelGGL(verify_pick_kernel<DT>, dim3(a.B), dim3(kSampleThreads), 0, st, a, C);
+    hipLaunchKernelGGL((verify_pick_kernel<DT, CUT>), dim3(a.B), dim3(kSampleThreads), 0, st, a, C);
   }
   return launch_status();
+}
+
+// Argument checks and launch shared by sv_verify_sample (T = 1, no cutoffs)
+// and sv_verify_sample_warped.
+static int verify_sample_checked(const void* z_t, const int32_t* t_offsets, int n_t_rows, const void* z_d,
+                                 const int32_t* x, const int32_t* gamma, int B, int k, int V, int dtype,
+                                 const Scale& sc_t, const float* cut_t, const Scale& sc_d, const float* cut_d,
+                                 uint64_t seed, uint32_t step, int32_t* out_tokens, int32_t* n_accept,
+                                 uint32_t* flags, float* ratio, void* ws, size_t ws_bytes, sv_stream_t stream) {
+  SV_REQUIRE(dtype == SV_F32 || dtype == SV_BF16, SV_ERR_DTYPE);
+  SV_REQUIRE(B >= 0 && k >= 1 && V >= 1, SV_ERR_INVALID_ARG);
+  SV_REQUIRE(k <= SV_MAX_K && n_chunks(V) <= kMaxChunks, SV_ERR_TOO_LARGE);
+  SV_REQUIRE((long long)B * (2 * k + 1) * kMaxSplit <= 0x7fffffffLL && B <= 65535, SV_ERR_TOO_LARGE);
+  if (B == 0) return SV_OK;
+  SV_REQUIRE(z_t && z_d && x && out_tokens && n_accept && flags, SV_ERR_NULL);
+  SV_REQUIRE(!t_offsets || n_t_rows >= 0, SV_ERR_INVALID_ARG);
+  const int eb = elem_bytes(dtype);
+  SV_REQUIRE(is_aligned(z_t, eb) && is_aligned(z_d, eb), SV_ERR_ALIGN);
+  SV_REQUIRE(is_aligned(x, 4) && is_aligned(out_tokens, 4) && is_aligned(n_accept, 4) &&
+                 is_aligned(flags, 4) && is_aligned(t_offsets, 4) && is_aligned(gamma, 4) &&
+                 is_aligned(ratio, 4) && is_aligned(cut_t, 4) && is_aligned(cut_d, 4),
+             SV_ERR_ALIGN);
+  SV_REQUIRE(ws && is_aligned(ws, kWsAlign) && ws_bytes >= sv_workspace_bytes(B, k, V, dtype),
+             SV_ERR_WORKSPACE);
+  VerifyArgs a;
+  a.z_t = z_t; a.t_offsets = t_offsets; a.n_t_rows = n_t_rows;
+  a.z_d = z_d; a.x = x; a.gamma = gamma;
+  a.B = B; a.k = k; a.V = V;
+  a.split = rows_split(B * (2 * k + 1), V);
+  a.t_seq_rows = k + 1;
+  a.with_bonus = 1;
+  a.seed_lo = (uint32_t)(seed & 0xffffffffu); a.seed_hi = (uint32_t)(seed >> 32); a.step = step;
+  a.out_tokens = out_tokens; a.n_accept = n_accept; a.flags = flags; a.ratio = ratio;
+  a.sc_t = sc_t; a.sc_d = sc_d; a.cut_t = cut_t; a.cut_d = cut_d;
+  a.ws = carve_verify_ws(ws, B, k, V);
+  hipStream_t st = as_stream(stream);
+  if (cut_t || cut_d)
+    return dtype == SV_F32 ? launch_verify<DT_F32, true>(a, st) : launch_verify<DT_BF16, true>(a, st);
+  return dtype == SV_F32 ? launch_verify<DT_F32, false>(a, st) : launch_verify<DT_BF16, false>(a, st);
 }
 
 }  // namespace sv
@@ -493,33 +567,25 @@ extern "C" int sv_verify_sample(const void* z_t, const int32_t* t_offsets_or_nul
                                 int32_t* out_tokens, int32_t* n_accept, uint32_t* flags,
                                 float* ratio_or_null, void* ws, size_t ws_bytes, sv_stream_t stream) {
   using namespace sv;
-  SV_REQUIRE(dtype == SV_F32 || dtype == SV_BF16, SV_ERR_DTYPE);
-  SV_REQUIRE(B >= 0 && k >= 1 && V >= 1, SV_ERR_INVALID_ARG);
-  SV_REQUIRE(k <= SV_MAX_K && n_chunks(V) <= kMaxChunks, SV_ERR_TOO_LARGE);
-  SV_REQUIRE((long long)B * (2 * k + 1) * kMaxSplit <= 0x7fffffffLL && B <= 65535, SV_ERR_TOO_LARGE);
-  if (B == 0) return SV_OK;
-  SV_REQUIRE(z_t && z_d && x && out_tokens && n_accept && flags, SV_ERR_NULL);
-  SV_REQUIRE(!t_offsets_or_null || n_t_rows >= 0, SV_ERR_INVALID_ARG);
-  const int eb = elem_bytes(dtype);
-  SV_REQUIRE(is_aligned(z_t, eb) && is_aligned(z_d, eb), SV_ERR_ALIGN);
-  SV_REQUIRE(is_aligned(x, 4) && is_aligned(out_tokens, 4) && is_aligned(n_accept, 4) &&
-                 is_aligned(flags, 4) && is_aligned(t_offsets_or_null, 4) &&
-                 is_aligned(gamma_or_null, 4) && is_aligned(ratio_or_null, 4),
-             SV_ERR_ALIGN);
-  SV_REQUIRE(ws && is_aligned(ws, kWsAlign) && ws_bytes >= sv_workspace_bytes(B, k, V, dtype),
-             SV_ERR_WORKSPACE);
-  VerifyArgs a;
-  a.z_t = z_t; a.t_offsets = t_offsets_or_null; a.n_t_rows = n_t_rows;
-  a.z_d = z_d; a.x = x; a.gamma = gamma_or_null;
-  a.B = B; a.k = k; a.V = V;
-  a.split = rows_split(B * (2 * k + 1), V);
-  a.t_seq_rows = k + 1;
-  a.with_bonus = 1;
-  a.seed_lo = (uint32_t)(seed & 0xffffffffu); a.seed_hi = (uint32_t)(seed >> 32); a.step = step;
-  a.out_tokens = out_tokens; a.n_accept = n_accept; a.flags = flags; a.ratio = ratio_or_null;
-  a.ws = carve_verify_ws(ws, B, k, V);
-  return dtype == SV_F32 ? launch_verify<DT_F32>(a, as_stream(stream))
-                         : launch_verify<DT_BF16>(a, as_stream(stream));
+  return verify_sample_checked(z_t, t_offsets_or_null, n_t_rows, z_d, x, gamma_or_null, B, k, V, dtype,
+                               unit_scale(), nullptr, unit_scale(), nullptr, seed, step, out_tokens, n_accept,
+                               flags, ratio_or_null, ws, ws_bytes, stream);
+}
+
+extern "C" int sv_verify_sample_warped(const void* z_t, const int32_t* t_offsets_or_null, int n_t_rows,
+                                       const void* z_d, const int32_t* x, const int32_t* gamma_or_null,
+                                       int B, int k, int V, int dtype,
+                                       float temperature_t, const float* cutoff_t_or_null,
+                                       float temperature_d, const float* cutoff_d_or_null,
+                                       uint64_t seed, uint32_t step,
+                                       int32_t* out_tokens, int32_t* n_accept, uint32_t* flags,
+                                       float* ratio_or_null, void* ws, size_t ws_bytes, sv_stream_t stream) {
+  using namespace sv;
+  Scale sc_t, sc_d;
+  SV_REQUIRE(scale_of(temperature_t, &sc_t) && scale_of(temperature_d, &sc_d), SV_ERR_INVALID_ARG);
+  return verify_sample_checked(z_t, t_offsets_or_null, n_t_rows, z_d, x, gamma_or_null, B, k, V, dtype,
+                               sc_t, cutoff_t_or_null, sc_d, cutoff_d_or_null, seed, step, out_tokens, n_accept,
+                               flags, ratio_or_null, ws, ws_bytes, stream);
 }
 
 extern "C" int sv_accept_ratio(const void* z_t, int t_rows_per_seq, const void* z_d, const int32_t* x,
@@ -545,15 +611,16 @@ extern "C" int sv_accept_ratio(const void* z_t, int t_rows_per_seq, const void* 
   a.split = rows_split(B * 2 * k, V);
   a.t_seq_rows = t_rows_per_seq;
   a.with_bonus = 0;
+  a.sc_t = unit_scale(); a.sc_d = unit_scale();
   a.ws = carve_verify_ws(ws, B, k, V);
   hipStream_t st = as_stream(stream);
   const int rows = B * (2 * k + 1);               // the bonus slots exit at once
   {
     TapScope tap(SV_KERNEL_VERIFY_ROWS, st);
     if (dtype == SV_F32)
-      hipLaunchKernelGGL(verify_rows_kernel<DT_F32>, dim3(rows * a.split), dim3(kRowsThreads), 0, st, a);
+      hipLaunchKernelGGL((verify_rows_kernel<DT_F32, false>), dim3(rows * a.split), dim3(kRowsThreads), 0, st, a);
     else
-      hipLaunchKernelGGL(verify_rows_kernel<DT_BF16>, dim3(rows * a.split), dim3(kRowsThreads), 0, st, a);
+      hipLaunchKernelGGL((verify_rows_kernel<DT_BF16, false>), dim3(rows * a.split), dim3(kRowsThreads), 0, st, a);
   }
   if (launch_status() != SV_OK) return SV_ERR_LAUNCH;
   hipLaunchKernelGGL(accept_ratio_kernel, dim3(B), dim3(kWave), 0, st, a, ratio, flags_or_null);

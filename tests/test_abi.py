@@ -123,3 +123,25 @@ def test_warp_cutoffs_argument_errors():
     assert wc(z=None) == Bd.SV_ERR_NULL
     assert wc(cut=ctypes.c_void_p(256 * 1024 + 2)) == Bd.SV_ERR_ALIGN
     assert wc(rows=0) == Bd.SV_OK
+
+
+def test_warped_entry_points_reject_bad_temperatures():
+    L = Bd.lib
+    p = ctypes.c_void_p(256 * 1024)
+    f = ctypes.c_float
+    rs = lambda Td, Tc, dt=1: L.sv_row_stats_warped(p, p, p, 2, 2, 64, dt, f(Td), None, f(Tc), None,
+                                                    p, p, p, p, None, None, None, None, p, 1 << 20, None)
+    vs = lambda Tt, Td, dt=1: L.sv_verify_sample_warped(p, None, 0, p, p, None, 2, 2, 64, dt, f(Tt), None,
+                                                        f(Td), None, 1, 0, p, p, p, None, p, 1 << 20, None)
+    for call in (rs, vs):
+        assert call(0.0, 1.0) == Bd.SV_ERR_INVALID_ARG
+        assert call(1.0, -1.0) == Bd.SV_ERR_INVALID_ARG
+        assert call(float("nan"), 1.0) == Bd.SV_ERR_INVALID_ARG
+        assert call(1.0, 1e4) == Bd.SV_ERR_INVALID_ARG
+        assert call(1.0, 1.0, dt=7) == Bd.SV_ERR_DTYPE
+    # a misaligned cutoff array is refused before anything is launched
+    bad = ctypes.c_void_p(256 * 1024 + 2)
+    assert L.sv_row_stats_warped(p, p, p, 2, 2, 64, 1, f(1.0), bad, f(1.0), None, p, p, p, p, None, None, None,
+                                 None, p, 1 << 20, None) == Bd.SV_ERR_ALIGN
+    assert L.sv_verify_sample_warped(p, None, 0, p, p, None, 2, 2, 64, 1, f(1.0), None, f(1.0), bad, 1, 0, p, p,
+                                     p, None, p, 1 << 20, None) == Bd.SV_ERR_ALIGN
