@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay timing")
     ap.add_argument("--no-profile-pass", action="store_true",
                     help="skip the timing of the profile-construction pass")
+    ap.add_argument("--no-warped", action="store_true",
+                    help="skip the timing of the step on temperature/top-k/top-p warped distributions")
     ap.add_argument("--cpu-seqs", type=int, default=0, help="sequences the oracle is timed on (0 = auto)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for rocprofv3 byte counters)")
@@ -55,12 +57,17 @@ class Hip:
         self.lib.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
         self.lib.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
         self.lib.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.lib.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
 
     def event(self):
         e = ctypes.c_void_p()
         rc = self.lib.hipEventCreate(ctypes.byref(e))
         assert rc == 0, f"hipEventCreate -> {rc}"
         return e
+
+    def record(self, e, stream_handle):
+        rc = self.lib.hipEventRecord(e, ctypes.c_void_p(stream_handle))
+        assert rc == 0, f"hipEventRecord -> {rc}"
 
     def elapsed_ms(self, a, b):
         ms = ctypes.c_float()
@@ -318,6 +325,69 @@ def main():
             profile_pass["parity"] = {"sequences_checked": nq, "max_rel_err_ratio": rel, "max_rel_err_S": relS}
             assert rel < 1e-5 and relS < 1e-5, profile_pass
 
+    # ---- the same step on warped distributions (temperature 0.7, top-k 20, top-p 0.8
+    # for all three models: one row of the paper's table of sampling hyper-parameters):
+    # three cutoff passes, then the warped indicators and the warped verification
+    warped_step = None
+    if not args.no_warped:
+        wT, wK, wP = float(np.float32(0.7)), 20, 0.8
+        c0 = copies[0]
+        cut_t, cut_d, cut_c = f32(B * (k + 1)), f32(B * k), f32(B * k)
+
+        def warped_once(i):
+            P.sv_warp_cutoffs(c0["z_t"], wT, wK, wP, cut_t, None, stream)
+            P.sv_warp_cutoffs(c0["z_d"], wT, wK, wP, cut_d, None, stream)
+            P.sv_warp_cutoffs(c0["z_c"], wT, wK, wP, cut_c, None, stream)
+            P.sv_row_stats_warped(c0["z_d"], c0["z_c"], c0["x"], wT, cut_d, wT, cut_c, lse_d, lse_c, S, A,
+                                  None, None, ws, stream)
+            P.sv_accept_estimate(S, A, d_es, d_ea, d_tab, p_hat, None, stream)
+            P.sv_select_length(p_hat, d_lat, P.SV_BATCH_GREEDY, gamma, offs, total, stream)
+            P.sv_verify_sample_warped(c0["z_t"], None, c0["z_d"], c0["x"], None, wT, cut_t, wT, cut_d, 0, i,
+                                      tokens, n_acc, flags, None, ws, stream)
+
+        for i in range(3):
+            warped_once(i)
+        torch.cuda.synchronize()
+        reps = 20
+        w0 = time.perf_counter()
+        for i in range(reps):
+            warped_once(i)
+        torch.cuda.synchronize()
+        w1 = time.perf_counter()
+        ce0, ce1 = hip.event(), hip.event()
+        torch.cuda.synchronize()
+        # the cutoff pass alone (all three tensors), bracketed by events on the launch stream
+        hip.record(ce0, stream.cuda_stream)
+        P.sv_warp_cutoffs(c0["z_t"], wT, wK, wP, cut_t, None, stream)
+        P.sv_warp_cutoffs(c0["z_d"], wT, wK, wP, cut_d, None, stream)
+        P.sv_warp_cutoffs(c0["z_c"], wT, wK, wP, cut_c, None, stream)
+        hip.record(ce1, stream.cuda_stream)
+        torch.cuda.synchronize()
+        warped_step = {"temperature": 0.7, "top_k": wK, "top_p": wP,
+                       "ms_per_step": round((w1 - w0) * 1e3 / reps, 4),
+                       "cutoff_pass_us": round(hip.elapsed_ms(ce0, ce1) * 1e3, 1),
+                       "cutoff_rows": B * (3 * k + 1)}
+        if not args.no_cpu_baseline:
+            from oracle import warp_oracle as WO
+            nq = min(B, 4)
+            zt_n, zd_n, zc_n = (svgen.to_numpy_bits(c0[n][:nq]) for n in ("z_t", "z_d", "z_c"))
+            xq = c0["x"][:nq].cpu().numpy()
+            y_t, _, f_t = WO.warp_rows(zt_n, wT, wK, wP)
+            y_d, _, f_d = WO.warp_rows(zd_n, wT, wK, wP)
+            y_c, _, f_c = WO.warp_rows(zc_n, wT, wK, wP)
+            warped_once(7)
+            torch.cuda.synchronize()
+            rs_ = O.row_stats(y_d, y_c, xq)
+            rv_ = O.verify_sample(y_t, y_d, xq, seed=0, step=7)
+            near = (f_t.any(1) | f_d.any(1) | f_c.any(1)) | ((rv_["flags"] & O.FLAG_NEAR_TIE) != 0)
+            okq = ~near
+            # disjoint supports give S = 0 exactly on both sides
+            relS = float(np.max(np.abs(S.cpu().numpy()[:nq] - rs_["S"]) / np.maximum(rs_["S"], 1e-30)))
+            same = bool(np.array_equal(n_acc.cpu().numpy()[:nq][okq], rv_["n_accept"][okq]))
+            warped_step["parity"] = {"sequences_checked": int(okq.sum()), "max_rel_err_S": relS,
+                                     "n_accept_equal": same}
+            assert relS < 1e-5 and same, warped_step
+
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)
@@ -349,6 +419,7 @@ def main():
             "ms_per_step": round(graph_ms, 5), "rows_per_s": round(rows_per_step / (graph_ms * 1e-3), 1)},
         "parity": parity,
         "profile_pass": profile_pass,
+        "warped_step": warped_step,
         "mean_gamma_selected": float(np.mean(got["gamma"])),
         "mean_accepted_full_verify": float(np.mean(got["n_accept"])),
         "setup_s": round(time.time() - t_setup, 1),

@@ -246,7 +246,7 @@ int sv_profile_finalize(const uint32_t* counts, const double* sum_x, int n_s, in
  *   z       [rows, V] dtype    in
  *   cutoff  [rows] float       out  a value of the row, -inf, or NaN for a bad row
  *   flags_or_null [rows] uint32 out SV_FLAG_BAD_ROW; SV_FLAG_NEAR_TIE when the top-p
- *                                   decision lies within 1e-6 of top_p
+ *                                   decision lies within 3e-6 of top_p
  * temperature > 0, top_p > 0.
  */
 int sv_warp_cutoffs(const void* z, int rows, int V, int dtype,

@@ -266,7 +266,8 @@ __device__ __forceinline__ MS fold_parts(const float* m, const double* s, int sp
 // also takes the scalar tail); rows that do not start on 16 bytes are split by
 // elements and read with scalar loads.
 // ---------------------------------------------------------------------------
-template <int DT, bool CUT = false>
+// NT: the row is not read again soon (non-temporal loads).
+template <int DT, bool CUT = false, bool NT = true>
 __device__ __forceinline__ void sweep_online(const void* row, int V, int part, int split, Online& acc,
                                              const float L = kL32, const float cut = -INFINITY) {
   constexpr int EPV = Elem<DT>::per_vec;
@@ -290,14 +291,15 @@ __device__ __forceinline__ void sweep_online(const void* row, int V, int part, i
     const int per = (nvec + split - 1) / split;
     const int end = min(nvec, (part + 1) * per);
     int i = part * per + tid;
+    auto load = [&](int j) { return NT ? __builtin_nontemporal_load(p + j) : p[j]; };
     for (; i + 3 * nt < end; i += 4 * nt) {
-      const u32x4 q0 = __builtin_nontemporal_load(p + i);
-      const u32x4 q1 = __builtin_nontemporal_load(p + i + nt);
-      const u32x4 q2 = __builtin_nontemporal_load(p + i + 2 * nt);
-      const u32x4 q3 = __builtin_nontemporal_load(p + i + 3 * nt);
+      const u32x4 q0 = load(i);
+      const u32x4 q1 = load(i + nt);
+      const u32x4 q2 = load(i + 2 * nt);
+      const u32x4 q3 = load(i + 3 * nt);
       add_vec(q0); add_vec(q1); add_vec(q2); add_vec(q3);
     }
-    for (; i < end; i += nt) add_vec(__builtin_nontemporal_load(p + i));
+    for (; i < end; i += nt) add_vec(load(i));
     if (part == split - 1)
       for (int v = nvec * EPV + tid; v < V; v += nt) add_one(v);
   } else {

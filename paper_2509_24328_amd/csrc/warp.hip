@@ -3,17 +3,24 @@
 // that the warped distribution is soft-max(z / T) restricted to {v : z_v >= cutoff}.
 // Entries of equal value are kept or dropped together.
 //
-// One workgroup per row, radix selection on an order-preserving 32-bit key of
-// the logit (11 + 11 + 10 bits; bfloat16 rows are resolved after two levels
-// because their low 16 bits are constant):
-//   sweep 1  row maximum (and NaN / +inf detection)
-//   sweep 2  level-0 histograms of all entries: count and mass 2^((z-m) L/T)
-//   top-k    descend with count histograms of the entries under the current
-//            prefix (one sweep per further level); masses ride along
-//   top-p    over the survivors of top-k: level 0 comes from the saved level-0
-//            masses, further levels need one sweep each
-// Masses are summed with LDS float atomics (order not fixed, ~1e-7 relative):
-// a top-p decision within 1e-6 of P is flagged SV_FLAG_NEAR_TIE.
+// One workgroup per row.  Both warps only concern the upper tail of the row, so
+// the kernel first tries to settle them on a short list of candidates:
+//   sweep 1  per-lane online (max, sum-exp): row maximum m, normaliser Z, bad-row
+//            detection; the 512 lane maxima are distinct entries of the row, so the
+//            K-th largest of them is a lower bound of the K-th largest entry
+//   select   tau = that bound (top-k), or the 384-th largest lane maximum (top-p
+//            alone: a guess that leaves a few hundred to a few thousand candidates)
+//   sweep 2  (from cache) append every entry >= tau to a list in LDS
+//   settle   sort the list, read off the K-th largest value, walk the groups of equal
+//            value until their mass reaches P
+// The list is exact whenever it holds at least K entries and (top-p alone) at
+// least P of the row's mass.  Otherwise - flat rows, huge K, more than 4096
+// candidates - the general path takes over: radix selection on an order-preserving
+// 32-bit key of the logit (11 + 11 + 10 bits; bfloat16 rows are resolved after two
+// levels), one histogram sweep of counts and masses per level.
+// Masses are fp32 exponentials summed in fp64 (candidate path) or with LDS float
+// atomics (general path); a top-p decision within 3e-6 of P is flagged
+// SV_FLAG_NEAR_TIE.
 #include "sv_device.hpp"
 #include "sv_host.hpp"
 
@@ -21,6 +28,9 @@ namespace sv {
 
 constexpr int kWarpThreads = 512;
 constexpr int kBins = 2048;
+constexpr int kCand = 4096;          // capacity of the candidate list
+constexpr int kGuessRank = 384;      // top-p alone: tau = this rank among the lane maxima
+constexpr double kNearTie = 3e-6;    // flagged band of a top-p decision
 
 __device__ __forceinline__ uint32_t okey(float f) {            // ascending order-preserving key
   const uint32_t u = __float_as_uint(f);
@@ -41,11 +51,23 @@ __device__ __forceinline__ bool under_prefix(uint32_t key, uint32_t prefix, int 
   return level == 0 || (key >> (level_shift(level) + level_bits(level))) == prefix;
 }
 
-struct WarpShared {
+struct alignas(16) WarpShared {
   BlockScratch red;
-  uint32_t cnt[kBins];
-  float mass[kBins];
-  float mass0[kBins];        // level-0 masses, kept for the top-p pass
+  MergeScratch<1> mg;
+  union {
+    struct {                   // general path
+      uint32_t cnt[kBins];
+      float mass[kBins];
+      float mass0[kBins];      // level-0 masses, kept for the top-p pass
+    };
+    struct {                   // candidate path
+      float cand[kCand];       // candidate values, then sorted descending
+      float w[kCand];          // their masses 2^(z lt - c_ref)
+      float lane_max[kWarpThreads];
+    };
+  };
+  float tau, theta;
+  int n_cand, settled;
   int sel_digit;
   uint32_t sel_count_above;
   double sel_mass_above;
@@ -68,7 +90,7 @@ __device__ __forceinline__ void scan_bins(WarpShared& sh, int nbins, bool by_cou
     if (!by_count && c > 0 && total_for_tie > 0.0) {
       // the candidate group boundaries at this level: flag a decision that sits on P
       const double fr = (m_above + mm) / total_for_tie, want = target / total_for_tie;
-      if (fabs(fr - want) < 1e-6) sh.near_tie = 1;
+      if (fabs(fr - want) < kNearTie) sh.near_tie = 1;
     }
     if (hit || d == 0) { found = d; sh.sel_mass_bin = mm; break; }
     c_above += c;
@@ -79,38 +101,15 @@ __device__ __forceinline__ void scan_bins(WarpShared& sh, int nbins, bool by_cou
   sh.sel_mass_above = m_above;
 }
 
+// General path: radix selection over the whole row (m = row maximum, finite).
+// Returns the cutoff in every thread; sets sh.near_tie.
 template <int DT>
-__global__ __launch_bounds__(kWarpThreads) void warp_cutoffs_kernel(const void* z, int V, float lt, int top_k,
-                                                                    float top_p, float* cutoff, uint32_t* flags) {
-  __shared__ WarpShared sh;
+__device__ __noinline__ float general_cutoff(const void* row, int V, float lt, int top_k, float top_p, float m,
+                                             WarpShared& sh) {
   const int tid = threadIdx.x;
-  const void* row = static_cast<const char*>(z) + (size_t)blockIdx.x * V * Elem<DT>::bytes;
   constexpr int kLevels = (DT == DT_BF16) ? 2 : 3;
-
-  // sweep 1: maximum, bad-row detection
-  float mx = -INFINITY;
-  int bad = 0;
-  visit_range<DT, false, 4>(row, nullptr, 0, V, [&](int, float v, float) {
-    mx = fmaxf(mx, v);
-    bad |= (isnan(v) || v == INFINITY) ? 1 : 0;
-  });
-  mx = wave_max_f32(mx);
-  if ((tid & 63) == 0) sh.red.f[tid >> 6] = mx;
-  const int any_bad = __syncthreads_or(bad);
-  float m = sh.red.f[0];
-  for (int w = 1; w < (int)(blockDim.x >> 6); ++w) m = fmaxf(m, sh.red.f[w]);
-  __syncthreads();
-  if (any_bad || m == -INFINITY) {
-    if (tid == 0) { cutoff[blockIdx.x] = __builtin_nanf(""); if (flags) flags[blockIdx.x] = SV_FLAG_BAD_ROW; }
-    return;
-  }
   const bool use_k = top_k > 0 && top_k < V, use_p = top_p < 1.0f;
-  if (!use_k && !use_p) {
-    if (tid == 0) { cutoff[blockIdx.x] = -INFINITY; if (flags) flags[blockIdx.x] = 0; }
-    return;
-  }
   const float c_ref = m * lt;
-  if (tid == 0) sh.near_tie = 0;
 
   // histogram sweep over the entries under `prefix` at `level`, optionally only z >= floor_v
   auto histogram = [&](int level, uint32_t prefix, float floor_v) {
@@ -191,6 +190,140 @@ __global__ __launch_bounds__(kWarpThreads) void warp_cutoffs_kernel(const void* 
     }
     const uint32_t key = (DT == DT_BF16) ? ((prefix << 10) | ((prefix >> 21) ? 0u : 0x3ffu)) : prefix;
     theta = fmaxf(from_okey(key), t_k);
+  }
+  return theta;
+}
+
+// Bitonic sort of c[0..n2) in descending order by the whole workgroup (n2 a power of two).
+__device__ __forceinline__ void sort_desc(float* c, int n2) {
+  const int tid = threadIdx.x, nt = blockDim.x;
+  for (int k2 = 2; k2 <= n2; k2 <<= 1) {
+    for (int j = k2 >> 1; j > 0; j >>= 1) {
+      for (int i = tid; i < n2; i += nt) {
+        const int o = i ^ j;
+        if (o > i) {
+          const float a = c[i], b = c[o];
+          const bool desc = (i & k2) == 0;
+          if (desc ? (a < b) : (a > b)) { c[i] = b; c[o] = a; }
+        }
+      }
+      __syncthreads();
+    }
+  }
+}
+
+template <int DT>
+__global__ __launch_bounds__(kWarpThreads) void warp_cutoffs_kernel(const void* z, int V, float lt, int top_k,
+                                                                    float top_p, float* cutoff, uint32_t* flags) {
+  __shared__ WarpShared sh;
+  const int tid = threadIdx.x;
+  const void* row = static_cast<const char*>(z) + (size_t)blockIdx.x * V * Elem<DT>::bytes;
+
+  // sweep 1: maximum, normaliser, bad-row detection (NaN poisons the sum, +inf the maximum)
+  Online acc[1];
+  acc[0].init();
+  sweep_online<DT, false, false>(row, V, 0, 1, acc[0], lt);
+  MS merged[1];
+  block_merge<1>(acc, sh.mg, merged, lt);
+  const float m = merged[0].m;
+  const double Z = merged[0].s;                        // sum 2^(z lt - c_ref)
+  if (!(Z > 0.0) || !isfinite(Z) || !isfinite(m)) {
+    if (tid == 0) { cutoff[blockIdx.x] = __builtin_nanf(""); if (flags) flags[blockIdx.x] = SV_FLAG_BAD_ROW; }
+    return;
+  }
+  const bool use_k = top_k > 0 && top_k < V, use_p = top_p < 1.0f;
+  if (!use_k && !use_p) {
+    if (tid == 0) { cutoff[blockIdx.x] = -INFINITY; if (flags) flags[blockIdx.x] = 0; }
+    return;
+  }
+  const float c_ref = ref_of(m, lt);
+
+  // ---- candidate threshold from the lane maxima -----------------------------
+  float tau = -INFINITY;                                // V <= kCand: every entry is a candidate
+  bool try_list = true;
+  if (V > kCand) {
+    const int rank = use_k ? top_k : kGuessRank;       // tau = rank-th largest lane maximum
+    if (rank > kWarpThreads) {
+      try_list = false;
+    } else {
+      sh.lane_max[tid] = acc[0].m;
+      if (tid == 0) sh.tau = -INFINITY;
+      __syncthreads();
+      const float mine = sh.lane_max[tid];
+      int gt = 0, ge = 0;
+      for (int j = 0; j < kWarpThreads; j += 4) {
+        const float4 q = *reinterpret_cast<const float4*>(&sh.lane_max[j]);   // same address in all lanes
+        gt += (q.x > mine) + (q.y > mine) + (q.z > mine) + (q.w > mine);
+        ge += (q.x >= mine) + (q.y >= mine) + (q.z >= mine) + (q.w >= mine);
+      }
+      if (gt < rank && rank <= ge) sh.tau = mine;      // every lane that writes holds the same value
+      __syncthreads();
+      tau = sh.tau;
+    }
+  }
+
+  float theta = 0.f;
+  bool settled = false;
+  if (tid == 0) { sh.n_cand = 0; sh.near_tie = 0; sh.settled = 0; }
+  __syncthreads();
+  if (try_list) {
+    // sweep 2: collect the candidates (a few per row: the shared counter is not a bottleneck)
+    visit_range<DT, false, 4>(row, nullptr, 0, V, [&](int, float v, float) {
+      if (v >= tau) {
+        const int at = atomicAdd(&sh.n_cand, 1);
+        if (at < kCand) sh.cand[at] = v;
+      }
+    });
+    __syncthreads();
+    const int n = sh.n_cand;
+    if (n <= kCand && (!use_k || n >= top_k)) {
+      int n2 = 64;
+      while (n2 < n) n2 <<= 1;
+      for (int i = n + tid; i < n2; i += blockDim.x) sh.cand[i] = -INFINITY;
+      __syncthreads();
+      sort_desc(sh.cand, n2);
+      for (int i = tid; i < n; i += blockDim.x) sh.w[i] = exp2_fast(__builtin_fmaf(sh.cand[i], lt, -c_ref));
+      __syncthreads();
+      if (tid == 0) {
+        float t_k = -INFINITY;
+        int ns = n;                                     // survivors of top-k: cand[0..ns)
+        double total = Z;
+        if (use_k) {
+          t_k = sh.cand[top_k - 1];
+          ns = top_k;
+          while (ns < n && sh.cand[ns] == t_k) ++ns;
+          total = 0.0;
+          for (int i = 0; i < ns; ++i) total += (double)sh.w[i];
+        }
+        float th = t_k;
+        bool ok = true;
+        if (use_p) {
+          ok = false;
+          double run = 0.0;
+          int i = 0;
+          while (i < ns) {
+            const float v = sh.cand[i];
+            do { run += (double)sh.w[i]; ++i; } while (i < ns && sh.cand[i] == v);
+            const double frac = run / total;
+            if (fabs(frac - (double)top_p) < kNearTie) sh.near_tie = 1;
+            if (frac >= (double)top_p) { th = v; ok = true; break; }
+          }
+          // top-k survivors always reach P (their own mass is the total); a list
+          // without top-k may end before the row's mass does
+          if (!ok && use_k) { th = sh.cand[ns - 1]; ok = true; }
+        }
+        sh.theta = th;
+        sh.settled = ok ? 1 : 0;
+      }
+      __syncthreads();
+      settled = sh.settled != 0;
+      theta = sh.theta;
+    }
+  }
+  if (!settled) {
+    __syncthreads();
+    if (tid == 0) sh.near_tie = 0;
+    theta = general_cutoff<DT>(row, V, lt, top_k, top_p, m, sh);
   }
   if (tid == 0) {
     cutoff[blockIdx.x] = theta;

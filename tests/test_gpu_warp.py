@@ -41,13 +41,17 @@ def _compare(z_torch, T, K, Pp):
             continue
         vals = O.upcast(rows[r])
         if (rflags | gflags[r]) & O.FLAG_NEAR_TIE:
-            # the two decisions may differ, but only by groups of negligible mass
+            # either decision is acceptable when the kept mass sits on P: the GPU's cutoff must
+            # reach P (within the band) and must not do so without its last group of equal values
             n_tie += 1
-            lo, hi = min(got[r], ref), max(got[r], ref)
-            y = vals / T
+            t_k = np.partition(vals, V - K)[V - K] if 0 < K < V else -np.inf
+            surv = vals[vals >= t_k]
+            y = surv / T
             w = np.exp(y - y.max())
-            between = w[(vals >= lo) & (vals < hi)].sum() / w.sum()
-            assert between <= 4e-6, (r, T, K, Pp, got[r], ref, between)
+            incl = w[surv >= got[r]].sum() / w.sum()
+            excl = w[surv > got[r]].sum() / w.sum()
+            assert got[r] >= t_k and (surv == got[r]).any(), (r, T, K, Pp, got[r], ref)
+            assert incl >= Pp - 5e-6 and excl < Pp + 5e-6, (r, T, K, Pp, got[r], ref, incl, excl)
             continue
         assert np.array_equal(vals >= got[r], vals >= ref), (r, T, K, Pp, got[r], ref)
     return n_tie
@@ -61,7 +65,7 @@ def test_cutoffs_on_config_rows(T, K, Pp):
         cfg = svgen.make_config(idx, B=B, k=k, V=V, dtype=dtype)
         ties += _compare(cfg["z_t"], T, K, Pp)
         ties += _compare(cfg["z_d"], T, K, Pp)
-    assert ties <= 8            # flat rows with groups lighter than the 1e-6 band trip the flag
+    assert ties <= 20           # flat rows with groups lighter than the flagged band trip the flag
 
 
 def test_ties_negative_rows_masked_and_bad_rows():
