@@ -60,13 +60,17 @@ enum {
   SV_FLAG_NEAR_TIE = 2,           /* |u - min(1, ratio)| < 1e-6 at an evaluated position      */
   SV_FLAG_RESIDUAL_FALLBACK = 4,  /* residual mass 0 / non-finite: token drawn from target    */
   SV_FLAG_NEAR_CDF_EDGE = 8,      /* sampling threshold within 1e-6 * W of a CDF edge         */
-  SV_FLAG_BAD_TOKEN = 16          /* drafted token id outside [0, V)                          */
+  SV_FLAG_BAD_TOKEN = 16,         /* drafted token id outside [0, V)                          */
+  SV_FLAG_NOT_COMPACT = 32        /* a needed row has no compact support (count < 0): the
+                                     result is not valid, use the dense warped entry points   */
 };
 
 /* Largest B*k accepted by sv_select_length (keys are sorted in one workgroup). */
 #define SV_SELECT_MAX_KEYS 4096
 /* Largest k accepted by sv_verify_sample. */
 #define SV_MAX_K 64
+/* Largest per-row capacity of a compacted support (sv_warp_compact). */
+#define SV_SUPPORT_MAX_CAP 1024
 
 /* Kernels of the library, for sv_set_timing_events. */
 enum {
@@ -295,6 +299,60 @@ int sv_verify_sample_warped(const void* z_t, const int32_t* t_offsets_or_null, i
                             uint64_t seed, uint32_t step,
                             int32_t* out_tokens, int32_t* n_accept, uint32_t* flags,
                             float* ratio_or_null, void* ws, size_t ws_bytes, sv_stream_t stream);
+
+/* ------------------------------------------------------------------------
+ * The step on compacted supports.  With the paper's sampling hyper-parameters
+ * (top-k 20, or top-p 0.6-0.9 at temperature 0.6-0.95) a warped distribution
+ * lives on a few dozen tokens, so one pass per logit tensor that writes each
+ * row's support replaces every later sweep over the vocabulary.
+ * ------------------------------------------------------------------------ */
+
+/*
+ * sv_warp_cutoffs plus the support of every warped row:
+ *   count  [rows] int32        out  number of kept tokens n_r; 0 for a bad row; -1 when the
+ *                                   support is wider than cap or could not be settled on the
+ *                                   kernel's candidate list (flat rows): use the dense path
+ *   token  [rows, cap] int32   out  kept token ids, ascending, entries 0..n_r-1
+ *   prob   [rows, cap] double  out  their probabilities under soft-max(z / T) restricted to
+ *                                   the kept set (entries of zero probability are not listed)
+ *   lse    [rows] float        out  log-sum-exp of z / T over the kept set (NaN: bad row / -1)
+ *   cutoff_or_null, flags_or_null   as in sv_warp_cutoffs
+ * 1 <= cap <= SV_SUPPORT_MAX_CAP.  Entries beyond n_r are left untouched.
+ */
+int sv_warp_compact(const void* z, int rows, int V, int dtype,
+                    float temperature, int top_k, float top_p, int cap,
+                    int32_t* count, int32_t* token, double* prob, float* lse,
+                    float* cutoff_or_null, uint32_t* flags_or_null, sv_stream_t stream);
+
+/*
+ * sv_row_stats on compacted supports (draft and companion, one support per
+ * (b, i) as written by sv_warp_compact with the same cap): S, A and the optional
+ * KL, entropy and P_d(x), in fp64 over the listed tokens.  Outputs and flags as in
+ * sv_row_stats; lse_d / lse_c are copied from the supports.  A pair with a count
+ * of -1 on either side gets NaN outputs and SV_FLAG_NOT_COMPACT.
+ *   V  vocabulary size, only to range-check the drafted tokens
+ */
+int sv_row_stats_sparse(const int32_t* count_d, const int32_t* token_d, const double* prob_d, const float* lse_d_in,
+                        const int32_t* count_c, const int32_t* token_c, const double* prob_c, const float* lse_c_in,
+                        int cap, const int32_t* x, int B, int k, int V,
+                        float* lse_d, float* lse_c, float* S, float* A,
+                        float* kl_or_null, float* entropy_d_or_null, float* pd_x_or_null,
+                        uint32_t* flags_or_null, sv_stream_t stream);
+
+/*
+ * sv_verify_sample on compacted supports: same rule, same Philox addressing,
+ * same outputs and flags.  The target supports are indexed like the rows of z_t
+ * (dense: b * (k+1) + i; packed: t_offsets[b] + i, with n_t_rows rows in all),
+ * the draft supports by b * k + i.  A sequence that needs a row with a count of
+ * -1 gets SV_FLAG_NOT_COMPACT | SV_FLAG_BAD_ROW and must be redone densely.
+ */
+int sv_verify_sample_sparse(const int32_t* count_t, const int32_t* token_t, const double* prob_t,
+                            const int32_t* t_offsets_or_null, int n_t_rows,
+                            const int32_t* count_d, const int32_t* token_d, const double* prob_d,
+                            int cap, const int32_t* x, const int32_t* gamma_or_null,
+                            int B, int k, int V, uint64_t seed, uint32_t step,
+                            int32_t* out_tokens, int32_t* n_accept, uint32_t* flags,
+                            float* ratio_or_null, sv_stream_t stream);
 
 /*
  * Timing taps for benchmarks (not part of the method): while a pair of

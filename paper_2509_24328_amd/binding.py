@@ -20,13 +20,16 @@ SV_OK = 0
 SV_ERR_INVALID_ARG, SV_ERR_NULL, SV_ERR_DTYPE, SV_ERR_ALIGN = -1, -2, -3, -4
 SV_ERR_WORKSPACE, SV_ERR_LAUNCH, SV_ERR_TOO_LARGE = -5, -6, -7
 FLAG_BAD_ROW, FLAG_NEAR_TIE, FLAG_RESIDUAL_FALLBACK, FLAG_NEAR_CDF_EDGE, FLAG_BAD_TOKEN = 1, 2, 4, 8, 16
+FLAG_NOT_COMPACT = 32
+SV_SUPPORT_MAX_CAP = 1024
 SV_SELECT_MAX_KEYS = 4096
 SV_MAX_K = 64
 
 EXPORTS = ("sv_strerror", "sv_workspace_bytes", "sv_row_stats", "sv_accept_estimate",
            "sv_select_length", "sv_verify_sample", "sv_set_timing_events", "sv_accept_ratio",
            "sv_quantile_edges", "sv_profile_accumulate", "sv_profile_finalize", "sv_warp_cutoffs",
-           "sv_row_stats_warped", "sv_verify_sample_warped")
+           "sv_row_stats_warped", "sv_verify_sample_warped",
+           "sv_warp_compact", "sv_row_stats_sparse", "sv_verify_sample_sparse")
 (SV_KERNEL_ROW_STATS, SV_KERNEL_ACCEPT_ESTIMATE, SV_KERNEL_SELECT_LENGTH, SV_KERNEL_VERIFY_ROWS,
  SV_KERNEL_VERIFY_ACCEPT, SV_KERNEL_VERIFY_MASS, SV_KERNEL_VERIFY_PICK, SV_KERNEL_COUNT) = range(8)
 
@@ -67,6 +70,14 @@ lib.sv_row_stats_warped.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _f, _vp, _f, 
 lib.sv_verify_sample_warped.restype = _i
 lib.sv_verify_sample_warped.argtypes = [_vp, _vp, _i, _vp, _vp, _vp, _i, _i, _i, _i, _f, _vp, _f, _vp,
                                         ctypes.c_uint64, ctypes.c_uint32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+lib.sv_warp_compact.restype = _i
+lib.sv_warp_compact.argtypes = [_vp, _i, _i, _i, _f, _i, _f, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+lib.sv_row_stats_sparse.restype = _i
+lib.sv_row_stats_sparse.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _vp, _i, _i, _i,
+                                    _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+lib.sv_verify_sample_sparse.restype = _i
+lib.sv_verify_sample_sparse.argtypes = [_vp, _vp, _vp, _vp, _i, _vp, _vp, _vp, _i, _vp, _vp, _i, _i, _i,
+                                        ctypes.c_uint64, ctypes.c_uint32, _vp, _vp, _vp, _vp, _vp]
 lib.sv_set_timing_events.restype = _i
 lib.sv_set_timing_events.argtypes = [_i, _vp, _vp]
 
@@ -197,3 +208,47 @@ def sv_verify_sample_warped(z_t, t_offsets, z_d, x, gamma, temperature_t, cutoff
                                        temperature_d, _ptr(cutoff_d), seed, step, _ptr(out_tokens),
                                        _ptr(n_accept), _ptr(flags), _ptr(ratio), _ptr(ws),
                                        0 if ws is None else ws.numel(), _stream(stream)))
+
+
+class Supports:
+    """Device buffers for the compacted supports of `rows` logit rows (sv_warp_compact)."""
+
+    def __init__(self, rows, cap, device="cuda"):
+        self.rows, self.cap = rows, cap
+        self.count = torch.empty(rows, dtype=torch.int32, device=device)
+        self.token = torch.empty((rows, cap), dtype=torch.int32, device=device)
+        self.prob = torch.empty((rows, cap), dtype=torch.float64, device=device)
+        self.lse = torch.empty(rows, dtype=torch.float32, device=device)
+
+
+def sv_warp_compact(z, temperature, top_k, top_p, sup, cutoff=None, flags=None, stream=None):
+    V = z.shape[-1]
+    rows = z.numel() // V
+    if rows != sup.rows:
+        raise SvError(SV_ERR_INVALID_ARG)
+    _check(lib.sv_warp_compact(_ptr(z), rows, V, _dtype_tag(z), temperature, top_k, top_p, sup.cap,
+                               _ptr(sup.count), _ptr(sup.token), _ptr(sup.prob), _ptr(sup.lse), _ptr(cutoff),
+                               _ptr(flags), _stream(stream)))
+
+
+def sv_row_stats_sparse(sup_d, sup_c, x, V, lse_d, lse_c, S, A, kl=None, flags=None, stream=None,
+                        entropy_d=None, pd_x=None):
+    B, k = x.shape
+    if sup_d.cap != sup_c.cap or sup_d.rows != B * k or sup_c.rows != B * k:
+        raise SvError(SV_ERR_INVALID_ARG)
+    _check(lib.sv_row_stats_sparse(_ptr(sup_d.count), _ptr(sup_d.token), _ptr(sup_d.prob), _ptr(sup_d.lse),
+                                   _ptr(sup_c.count), _ptr(sup_c.token), _ptr(sup_c.prob), _ptr(sup_c.lse),
+                                   sup_d.cap, _ptr(x), B, k, V, _ptr(lse_d), _ptr(lse_c), _ptr(S), _ptr(A),
+                                   _ptr(kl), _ptr(entropy_d), _ptr(pd_x), _ptr(flags), _stream(stream)))
+
+
+def sv_verify_sample_sparse(sup_t, t_offsets, sup_d, x, gamma, V, seed, step, out_tokens, n_accept, flags,
+                            ratio=None, stream=None):
+    B, k = x.shape
+    if sup_t.cap != sup_d.cap or sup_d.rows != B * k or (t_offsets is None and sup_t.rows != B * (k + 1)):
+        raise SvError(SV_ERR_INVALID_ARG)
+    n_t_rows = sup_t.rows if t_offsets is not None else 0
+    _check(lib.sv_verify_sample_sparse(_ptr(sup_t.count), _ptr(sup_t.token), _ptr(sup_t.prob), _ptr(t_offsets),
+                                       n_t_rows, _ptr(sup_d.count), _ptr(sup_d.token), _ptr(sup_d.prob),
+                                       sup_t.cap, _ptr(x), _ptr(gamma), B, k, V, seed, step, _ptr(out_tokens),
+                                       _ptr(n_accept), _ptr(flags), _ptr(ratio), _stream(stream)))

@@ -14,13 +14,18 @@
 //   settle   sort the list, read off the K-th largest value, walk the groups of equal
 //            value until their mass reaches P
 // The list is exact whenever it holds at least K entries and (top-p alone) at
-// least P of the row's mass.  Otherwise - flat rows, huge K, more than 4096
+// least P of the row's mass.  Otherwise - flat rows, huge K, more than 2048
 // candidates - the general path takes over: radix selection on an order-preserving
 // 32-bit key of the logit (11 + 11 + 10 bits; bfloat16 rows are resolved after two
 // levels), one histogram sweep of counts and masses per level.
-// Masses are fp32 exponentials summed in fp64 (candidate path) or with LDS float
-// atomics (general path); a top-p decision within 3e-6 of P is flagged
-// SV_FLAG_NEAR_TIE.
+// Masses are fp64 exponentials (candidate path; the row total of top-p alone comes
+// from the fp32 sweep) or fp32 ones summed with LDS float atomics (general path); a
+// top-p decision within 3e-6 of P is flagged SV_FLAG_NEAR_TIE.
+//
+// sv_warp_compact is the same kernel with one more step: the kept entries of a
+// settled list are the whole support of the warped distribution, so their token
+// ids (ascending) and fp64 probabilities are written out and everything
+// downstream can work on a few dozen entries per row instead of V.
 #include "sv_device.hpp"
 #include "sv_host.hpp"
 
@@ -28,7 +33,7 @@ namespace sv {
 
 constexpr int kWarpThreads = 512;
 constexpr int kBins = 2048;
-constexpr int kCand = 4096;          // capacity of the candidate list
+constexpr int kCand = 2048;          // capacity of the candidate list
 constexpr int kGuessRank = 384;      // top-p alone: tau = this rank among the lane maxima
 constexpr double kNearTie = 3e-6;    // flagged band of a top-p decision
 
@@ -61,13 +66,14 @@ struct alignas(16) WarpShared {
       float mass0[kBins];      // level-0 masses, kept for the top-p pass
     };
     struct {                   // candidate path
-      float cand[kCand];       // candidate values, then sorted descending
-      float w[kCand];          // their masses 2^(z lt - c_ref)
+      uint64_t key[kCand];     // (order key of the value, ~token id): sorted descending
+      double w[kCand];         // masses exp((z - m) / T) of the sorted candidates
       float lane_max[kWarpThreads];
     };
   };
   float tau, theta;
-  int n_cand, settled;
+  int n_cand, settled, n_keep;
+  double z_keep;               // mass of the kept entries
   int sel_digit;
   uint32_t sel_count_above;
   double sel_mass_above;
@@ -195,14 +201,14 @@ __device__ __noinline__ float general_cutoff(const void* row, int V, float lt, i
 }
 
 // Bitonic sort of c[0..n2) in descending order by the whole workgroup (n2 a power of two).
-__device__ __forceinline__ void sort_desc(float* c, int n2) {
+__device__ __forceinline__ void sort_desc(uint64_t* c, int n2) {
   const int tid = threadIdx.x, nt = blockDim.x;
   for (int k2 = 2; k2 <= n2; k2 <<= 1) {
     for (int j = k2 >> 1; j > 0; j >>= 1) {
       for (int i = tid; i < n2; i += nt) {
         const int o = i ^ j;
         if (o > i) {
-          const float a = c[i], b = c[o];
+          const uint64_t a = c[i], b = c[o];
           const bool desc = (i & k2) == 0;
           if (desc ? (a < b) : (a > b)) { c[i] = b; c[o] = a; }
         }
@@ -212,12 +218,27 @@ __device__ __forceinline__ void sort_desc(float* c, int n2) {
   }
 }
 
+__device__ __forceinline__ float key_value(uint64_t key) { return from_okey((uint32_t)(key >> 32)); }
+__device__ __forceinline__ uint32_t key_token(uint64_t key) { return 0xFFFFFFFFu - (uint32_t)key; }
+
+// Optional outputs of sv_warp_compact (all null for sv_warp_cutoffs).
+struct CompactOut {
+  int32_t* count;    // [rows]
+  int32_t* token;    // [rows, cap]
+  double* prob;      // [rows, cap]
+  float* lse;        // [rows]
+  int cap;
+};
+
 template <int DT>
-__global__ __launch_bounds__(kWarpThreads) void warp_cutoffs_kernel(const void* z, int V, float lt, int top_k,
-                                                                    float top_p, float* cutoff, uint32_t* flags) {
+__global__ __launch_bounds__(kWarpThreads) void warp_cutoffs_kernel(const void* z, int V, Scale sc, int top_k,
+                                                                    float top_p, float* cutoff, uint32_t* flags,
+                                                                    CompactOut out) {
   __shared__ WarpShared sh;
   const int tid = threadIdx.x;
-  const void* row = static_cast<const char*>(z) + (size_t)blockIdx.x * V * Elem<DT>::bytes;
+  const int r = blockIdx.x;
+  const void* row = static_cast<const char*>(z) + (size_t)r * V * Elem<DT>::bytes;
+  const float lt = sc.L;
 
   // sweep 1: maximum, normaliser, bad-row detection (NaN poisons the sum, +inf the maximum)
   Online acc[1];
@@ -226,17 +247,26 @@ __global__ __launch_bounds__(kWarpThreads) void warp_cutoffs_kernel(const void* 
   MS merged[1];
   block_merge<1>(acc, sh.mg, merged, lt);
   const float m = merged[0].m;
-  const double Z = merged[0].s;                        // sum 2^(z lt - c_ref)
-  if (!(Z > 0.0) || !isfinite(Z) || !isfinite(m)) {
-    if (tid == 0) { cutoff[blockIdx.x] = __builtin_nanf(""); if (flags) flags[blockIdx.x] = SV_FLAG_BAD_ROW; }
+  const double lse_row = lse_from_ms(merged[0], sc);   // of z / T over the whole row; NaN: bad row
+  if (isnan(lse_row)) {
+    if (tid == 0) {
+      if (cutoff) cutoff[r] = __builtin_nanf("");
+      if (flags) flags[r] = SV_FLAG_BAD_ROW;
+      if (out.count) { out.count[r] = 0; out.lse[r] = __builtin_nanf(""); }
+    }
     return;
   }
   const bool use_k = top_k > 0 && top_k < V, use_p = top_p < 1.0f;
-  if (!use_k && !use_p) {
-    if (tid == 0) { cutoff[blockIdx.x] = -INFINITY; if (flags) flags[blockIdx.x] = 0; }
+  if (!use_k && !use_p && (V > kCand || !out.count)) {  // nothing to cut, and no short support to write
+    if (tid == 0) {
+      if (cutoff) cutoff[r] = -INFINITY;
+      if (flags) flags[r] = 0;
+      if (out.count) { out.count[r] = -1; out.lse[r] = (float)lse_row; }
+    }
     return;
   }
-  const float c_ref = ref_of(m, lt);
+  const double m_t = (double)m * sc.inv_t;
+  const double Z = exp(lse_row - m_t);                  // sum_v exp((z_v - m) / T)
 
   // ---- candidate threshold from the lane maxima -----------------------------
   float tau = -INFINITY;                                // V <= kCand: every entry is a candidate
@@ -264,56 +294,69 @@ __global__ __launch_bounds__(kWarpThreads) void warp_cutoffs_kernel(const void* 
 
   float theta = 0.f;
   bool settled = false;
-  if (tid == 0) { sh.n_cand = 0; sh.near_tie = 0; sh.settled = 0; }
+  if (tid == 0) { sh.n_cand = 0; sh.near_tie = 0; sh.settled = 0; sh.n_keep = -1; }
   __syncthreads();
   if (try_list) {
     // sweep 2: collect the candidates (a few per row: the shared counter is not a bottleneck)
-    visit_range<DT, false, 4>(row, nullptr, 0, V, [&](int, float v, float) {
-      if (v >= tau) {
+    visit_range<DT, false, 4>(row, nullptr, 0, V, [&](int v, float zv, float) {
+      if (zv >= tau && zv > -INFINITY) {                // entries at -inf carry no mass and are never listed
         const int at = atomicAdd(&sh.n_cand, 1);
-        if (at < kCand) sh.cand[at] = v;
+        if (at < kCand) sh.key[at] = ((uint64_t)okey(zv) << 32) | (uint64_t)(0xFFFFFFFFu - (uint32_t)v);
       }
     });
     __syncthreads();
     const int n = sh.n_cand;
-    if (n <= kCand && (!use_k || n >= top_k)) {
+    // fewer than K candidates happens only when tau = -inf lists every finite entry
+    // of the row (masked vocabularies): top-k then keeps them all
+    if (n <= kCand && (!use_k || n >= top_k || tau == -INFINITY)) {
       int n2 = 64;
       while (n2 < n) n2 <<= 1;
-      for (int i = n + tid; i < n2; i += blockDim.x) sh.cand[i] = -INFINITY;
+      for (int i = n + tid; i < n2; i += blockDim.x) sh.key[i] = 0;      // below every real key
       __syncthreads();
-      sort_desc(sh.cand, n2);
-      for (int i = tid; i < n; i += blockDim.x) sh.w[i] = exp2_fast(__builtin_fmaf(sh.cand[i], lt, -c_ref));
+      sort_desc(sh.key, n2);
+      for (int i = tid; i < n; i += blockDim.x)
+        sh.w[i] = exp((double)key_value(sh.key[i]) * sc.inv_t - m_t);    // exp(-inf) = 0
       __syncthreads();
       if (tid == 0) {
         float t_k = -INFINITY;
-        int ns = n;                                     // survivors of top-k: cand[0..ns)
+        int ns = n;                                     // survivors of top-k: sorted entries 0..ns-1
         double total = Z;
         if (use_k) {
-          t_k = sh.cand[top_k - 1];
-          ns = top_k;
-          while (ns < n && sh.cand[ns] == t_k) ++ns;
+          if (n >= top_k) {
+            t_k = key_value(sh.key[top_k - 1]);
+            ns = top_k;
+            while (ns < n && key_value(sh.key[ns]) == t_k) ++ns;
+          }
           total = 0.0;
-          for (int i = 0; i < ns; ++i) total += (double)sh.w[i];
+          for (int i = 0; i < ns; ++i) total += sh.w[i];
         }
         float th = t_k;
+        int nk = ns;                                    // kept entries: sorted entries 0..nk-1
+        double kept = total;
         bool ok = true;
         if (use_p) {
           ok = false;
           double run = 0.0;
           int i = 0;
           while (i < ns) {
-            const float v = sh.cand[i];
-            do { run += (double)sh.w[i]; ++i; } while (i < ns && sh.cand[i] == v);
+            const float v = key_value(sh.key[i]);
+            do { run += sh.w[i]; ++i; } while (i < ns && key_value(sh.key[i]) == v);
             const double frac = run / total;
             if (fabs(frac - (double)top_p) < kNearTie) sh.near_tie = 1;
-            if (frac >= (double)top_p) { th = v; ok = true; break; }
+            if (frac >= (double)top_p) { th = v; nk = i; kept = run; ok = true; break; }
           }
           // top-k survivors always reach P (their own mass is the total); a list
           // without top-k may end before the row's mass does
-          if (!ok && use_k) { th = sh.cand[ns - 1]; ok = true; }
+          if (!ok && use_k) { th = key_value(sh.key[ns - 1]); nk = ns; kept = run; ok = true; }
+        } else if (!use_k) {
+          kept = 0.0;                                   // no warp at all (short rows): everything is kept
+          for (int i = 0; i < n; ++i) kept += sh.w[i];
         }
+        while (nk > 0 && sh.w[nk - 1] == 0.0) --nk;     // masses that underflow fp64 are not listed
         sh.theta = th;
         sh.settled = ok ? 1 : 0;
+        sh.n_keep = nk;
+        sh.z_keep = kept;
       }
       __syncthreads();
       settled = sh.settled != 0;
@@ -322,33 +365,87 @@ __global__ __launch_bounds__(kWarpThreads) void warp_cutoffs_kernel(const void* 
   }
   if (!settled) {
     __syncthreads();
-    if (tid == 0) sh.near_tie = 0;
+    if (tid == 0) { sh.near_tie = 0; sh.n_keep = -1; }
     theta = general_cutoff<DT>(row, V, lt, top_k, top_p, m, sh);
   }
   if (tid == 0) {
-    cutoff[blockIdx.x] = theta;
-    if (flags) flags[blockIdx.x] = sh.near_tie ? SV_FLAG_NEAR_TIE : 0u;
+    if (cutoff) cutoff[r] = theta;
+    if (flags) flags[r] = sh.near_tie ? SV_FLAG_NEAR_TIE : 0u;
+  }
+  if (!out.count) return;
+
+  // ---- support of the warped row: token ids ascending, fp64 probabilities ----
+  __syncthreads();
+  const int nk = sh.n_keep;
+  if (nk < 0 || nk > out.cap) {                         // not settled on the list, or too wide
+    if (tid == 0) { out.count[r] = -1; out.lse[r] = __builtin_nanf(""); }
+    return;
+  }
+  const double z_keep = sh.z_keep;
+  int n2 = 64;
+  while (n2 < nk) n2 <<= 1;
+  __syncthreads();
+  // re-key the kept entries by token id (ascending = descending complement); the position
+  // in the value order rides along.  Every slot is rewritten by the thread that read it.
+  for (int i = tid; i < n2; i += blockDim.x) {
+    uint64_t key = 0;
+    if (i < nk) key = ((uint64_t)(0xFFFFFFFFu - key_token(sh.key[i])) << 32) | (uint64_t)i;
+    sh.key[i] = key;
+  }
+  __syncthreads();
+  sort_desc(sh.key, n2);
+  for (int i = tid; i < nk; i += blockDim.x) {
+    const uint64_t key = sh.key[i];
+    const size_t at = (size_t)r * out.cap + i;
+    out.token[at] = (int32_t)(0xFFFFFFFFu - (uint32_t)(key >> 32));
+    out.prob[at] = sh.w[(uint32_t)key] / z_keep;
+  }
+  if (tid == 0) {
+    out.count[r] = nk;
+    out.lse[r] = (float)(m_t + log(z_keep));
   }
 }
 
 }  // namespace sv
 
-extern "C" int sv_warp_cutoffs(const void* z, int rows, int V, int dtype, float temperature, int top_k,
-                               float top_p, float* cutoff, uint32_t* flags_or_null, sv_stream_t stream) {
+namespace {
+
+int launch_warp(const void* z, int rows, int V, int dtype, float temperature, int top_k, float top_p,
+                float* cutoff, uint32_t* flags, const sv::CompactOut& out, sv_stream_t stream) {
   using namespace sv;
   SV_REQUIRE(dtype == SV_F32 || dtype == SV_BF16, SV_ERR_DTYPE);
-  SV_REQUIRE(rows >= 0 && V >= 1 && temperature > 0.f && top_p > 0.f, SV_ERR_INVALID_ARG);
+  SV_REQUIRE(rows >= 0 && V >= 1 && top_p > 0.f, SV_ERR_INVALID_ARG);
+  Scale sc;
+  SV_REQUIRE(scale_of(temperature, &sc), SV_ERR_INVALID_ARG);
   if (rows == 0) return SV_OK;
-  SV_REQUIRE(z && cutoff, SV_ERR_NULL);
-  SV_REQUIRE(is_aligned(z, elem_bytes(dtype)) && is_aligned(cutoff, 4) && is_aligned(flags_or_null, 4),
-             SV_ERR_ALIGN);
-  const float lt = (float)(1.4426950408889634 / (double)temperature);
+  SV_REQUIRE(z, SV_ERR_NULL);
+  SV_REQUIRE(is_aligned(z, elem_bytes(dtype)) && is_aligned(cutoff, 4) && is_aligned(flags, 4), SV_ERR_ALIGN);
   hipStream_t st = as_stream(stream);
   if (dtype == SV_F32)
-    hipLaunchKernelGGL(warp_cutoffs_kernel<DT_F32>, dim3(rows), dim3(kWarpThreads), 0, st, z, V, lt, top_k, top_p,
-                       cutoff, flags_or_null);
+    hipLaunchKernelGGL(warp_cutoffs_kernel<DT_F32>, dim3(rows), dim3(kWarpThreads), 0, st, z, V, sc, top_k, top_p,
+                       cutoff, flags, out);
   else
-    hipLaunchKernelGGL(warp_cutoffs_kernel<DT_BF16>, dim3(rows), dim3(kWarpThreads), 0, st, z, V, lt, top_k, top_p,
-                       cutoff, flags_or_null);
+    hipLaunchKernelGGL(warp_cutoffs_kernel<DT_BF16>, dim3(rows), dim3(kWarpThreads), 0, st, z, V, sc, top_k, top_p,
+                       cutoff, flags, out);
   return launch_status();
+}
+
+}  // namespace
+
+extern "C" int sv_warp_cutoffs(const void* z, int rows, int V, int dtype, float temperature, int top_k,
+                               float top_p, float* cutoff, uint32_t* flags_or_null, sv_stream_t stream) {
+  SV_REQUIRE(cutoff || rows <= 0, SV_ERR_NULL);
+  return launch_warp(z, rows, V, dtype, temperature, top_k, top_p, cutoff, flags_or_null, sv::CompactOut{}, stream);
+}
+
+extern "C" int sv_warp_compact(const void* z, int rows, int V, int dtype, float temperature, int top_k,
+                               float top_p, int cap, int32_t* count, int32_t* token, double* prob, float* lse,
+                               float* cutoff_or_null, uint32_t* flags_or_null, sv_stream_t stream) {
+  using namespace sv;
+  SV_REQUIRE(cap >= 1 && cap <= SV_SUPPORT_MAX_CAP, SV_ERR_INVALID_ARG);
+  SV_REQUIRE((count && token && prob && lse) || rows <= 0, SV_ERR_NULL);
+  SV_REQUIRE(is_aligned(count, 4) && is_aligned(token, 4) && is_aligned(prob, 8) && is_aligned(lse, 4),
+             SV_ERR_ALIGN);
+  return launch_warp(z, rows, V, dtype, temperature, top_k, top_p, cutoff_or_null, flags_or_null,
+                     CompactOut{count, token, prob, lse, cap}, stream);
 }

@@ -145,3 +145,34 @@ def test_warped_entry_points_reject_bad_temperatures():
                                  None, p, 1 << 20, None) == Bd.SV_ERR_ALIGN
     assert L.sv_verify_sample_warped(p, None, 0, p, p, None, 2, 2, 64, 1, f(1.0), None, f(1.0), bad, 1, 0, p, p,
                                      p, None, p, 1 << 20, None) == Bd.SV_ERR_ALIGN
+
+
+def test_compact_and_sparse_argument_errors():
+    L = Bd.lib
+    p = ctypes.c_void_p(256 * 1024)
+    odd = ctypes.c_void_p(256 * 1024 + 4)
+    f = ctypes.c_float
+    wc = lambda **kw: L.sv_warp_compact(kw.get("z", p), kw.get("rows", 4), 8, kw.get("dt", 1), f(kw.get("T", 0.7)), 20,
+                                        f(0.8), kw.get("cap", 64), kw.get("count", p), p, kw.get("prob", p), p,
+                                        None, None, None)
+    assert wc(cap=0) == Bd.SV_ERR_INVALID_ARG
+    assert wc(cap=Bd.SV_SUPPORT_MAX_CAP + 1) == Bd.SV_ERR_INVALID_ARG
+    assert wc(T=0.0) == Bd.SV_ERR_INVALID_ARG
+    assert wc(dt=3) == Bd.SV_ERR_DTYPE
+    assert wc(count=None) == Bd.SV_ERR_NULL
+    assert wc(prob=odd) == Bd.SV_ERR_ALIGN
+    assert wc(rows=0) == Bd.SV_OK
+    rs = lambda **kw: L.sv_row_stats_sparse(p, p, kw.get("prob", p), p, p, p, p, p, kw.get("cap", 64), kw.get("x", p),
+                                            kw.get("B", 2), 2, 100, p, p, p, p, None, None, None, None, None)
+    assert rs(cap=0) == Bd.SV_ERR_INVALID_ARG
+    assert rs(x=None) == Bd.SV_ERR_NULL
+    assert rs(prob=odd) == Bd.SV_ERR_ALIGN
+    assert rs(B=0) == Bd.SV_OK
+    vs = lambda **kw: L.sv_verify_sample_sparse(p, p, kw.get("prob", p), None, 0, p, p, p, kw.get("cap", 64), p, None,
+                                                kw.get("B", 2), kw.get("k", 2), 100, 1, 0, kw.get("out", p), p, p,
+                                                None, None)
+    assert vs(cap=2000) == Bd.SV_ERR_INVALID_ARG
+    assert vs(k=Bd.SV_MAX_K + 1) == Bd.SV_ERR_TOO_LARGE
+    assert vs(out=None) == Bd.SV_ERR_NULL
+    assert vs(prob=odd) == Bd.SV_ERR_ALIGN
+    assert vs(B=0) == Bd.SV_OK
