@@ -367,6 +367,46 @@ def main():
                        "ms_per_step": round((w1 - w0) * 1e3 / reps, 4),
                        "cutoff_pass_us": round(hip.elapsed_ms(ce0, ce1) * 1e3, 1),
                        "cutoff_rows": B * (3 * k + 1)}
+
+        # the same warped step on compacted supports: one compaction pass per tensor, then
+        # every later stage works on the few kept tokens of each row
+        cap = 64
+        sup_t, sup_d, sup_c = P.Supports(B * (k + 1), cap), P.Supports(B * k, cap), P.Supports(B * k, cap)
+        s_tokens, s_nacc, s_flags = i32(B, k + 1), i32(B), i32(B)
+        s_S, s_A = f32(B, k), f32(B, k)
+
+        def sparse_once(i):
+            P.sv_warp_compact(c0["z_t"], wT, wK, wP, sup_t, None, None, stream)
+            P.sv_warp_compact(c0["z_d"], wT, wK, wP, sup_d, None, None, stream)
+            P.sv_warp_compact(c0["z_c"], wT, wK, wP, sup_c, None, None, stream)
+            P.sv_row_stats_sparse(sup_d, sup_c, c0["x"], V, lse_d, lse_c, s_S, s_A, None, None, stream)
+            P.sv_accept_estimate(s_S, s_A, d_es, d_ea, d_tab, p_hat, None, stream)
+            P.sv_select_length(p_hat, d_lat, P.SV_BATCH_GREEDY, gamma, offs, total, stream)
+            P.sv_verify_sample_sparse(sup_t, None, sup_d, c0["x"], None, V, 0, i, s_tokens, s_nacc, s_flags,
+                                      None, stream)
+
+        for i in range(3):
+            sparse_once(i)
+        torch.cuda.synchronize()
+        q0 = time.perf_counter()
+        for i in range(reps):
+            sparse_once(i)
+        torch.cuda.synchronize()
+        q1 = time.perf_counter()
+        counts = torch.cat([sup_t.count, sup_d.count, sup_c.count]).cpu().numpy()
+        # both paths on the same step index: identical accept counts and tokens
+        warped_once(5)
+        sparse_once(5)
+        torch.cuda.synchronize()
+        same_n = bool(torch.equal(n_acc, s_nacc))
+        near = ((flags | s_flags) & (2 | 8)) != 0
+        same_tok = bool(torch.equal(tokens[~near], s_tokens[~near]))
+        warped_step["compacted"] = {"cap": cap, "ms_per_step": round((q1 - q0) * 1e3 / reps, 4),
+                                    "rows_not_compact": int((counts < 0).sum()),
+                                    "mean_support": round(float(counts[counts > 0].mean()), 2),
+                                    "n_accept_equal_dense_warped": same_n,
+                                    "tokens_equal_dense_warped_off_near_flags": same_tok}
+        assert same_n and same_tok, warped_step
         if not args.no_cpu_baseline:
             from oracle import warp_oracle as WO
             nq = min(B, 4)

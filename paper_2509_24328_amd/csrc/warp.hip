@@ -68,11 +68,12 @@ struct alignas(16) WarpShared {
     struct {                   // candidate path
       uint64_t key[kCand];     // (order key of the value, ~token id): sorted descending
       double w[kCand];         // masses exp((z - m) / T) of the sorted candidates
-      float lane_max[kWarpThreads];
+      uint32_t lane_key[kWarpThreads];   // upper 16 bits of the order key of each lane's maximum
     };
   };
-  float tau, theta;
-  int n_cand, settled, n_keep;
+  uint32_t tau_key;
+  float theta;
+  int n_cand, settled, n_keep, out_done;
   double z_keep;               // mass of the kept entries
   int sel_digit;
   uint32_t sel_count_above;
@@ -230,6 +231,81 @@ struct CompactOut {
   int cap;
 };
 
+// The four largest tagged keys a lane has seen (k1 >= k2 >= k3 >= k4, unsigned order).
+// Key of a 16-byte vector of the row: the upper 16 order-preserving bits of its
+// largest entry on top, below them the lane's vector step, from which the lane
+// recovers the vector's position.  For fp32 rows the 16 bits order the maxima
+// coarsely; that is enough, because the keys only decide which vectors are read
+// again and whether a lane may hide one.
+struct Top4 {
+  uint32_t k1 = 0, k2 = 0, k3 = 0, k4 = 0;
+  __device__ __forceinline__ void add(uint32_t key) {
+    uint32_t t = key;
+    const uint32_t n1 = max(k1, t); t = min(k1, t);
+    const uint32_t n2 = max(k2, t); t = min(k2, t);
+    const uint32_t n3 = max(k3, t); t = min(k3, t);
+    k1 = n1; k2 = n2; k3 = n3; k4 = max(k4, t);
+  }
+};
+
+constexpr int kTagSteps = 1 << 16;   // vector steps per lane that fit the 16-bit tag
+
+// Sweep 1 for rows made of whole, aligned vectors: the online (max, sum-exp) of
+// sweep_online plus the lane's four largest vector maxima with their positions.
+template <int DT>
+__device__ __forceinline__ void sweep_online_top4(const void* row, int V, Online& acc, Top4& top, const float L) {
+  constexpr int EPV = Elem<DT>::per_vec;
+  const int tid = threadIdx.x;
+  constexpr int nt = kWarpThreads;
+  const u32x4* p = reinterpret_cast<const u32x4*>(row);
+  const int nvec = V / EPV;
+  auto add_vec = [&](const u32x4& q, int i) {
+    float f[EPV];
+    unpack<DT>(q, f);
+    acc.add(f, L);
+    float vmax = f[0];
+#pragma unroll
+    for (int e = 1; e + 1 < EPV; e += 2) vmax = fmaxf(fmaxf(vmax, f[e]), f[e + 1]);
+    vmax = fmaxf(vmax, f[EPV - 1]);
+    top.add((okey(vmax) & 0xFFFF0000u) | (uint32_t)(i / nt));     // i = tid + step * nt
+  };
+  int i = tid;
+  for (; i + 3 * nt < nvec; i += 4 * nt) {
+    const u32x4 q0 = p[i], q1 = p[i + nt], q2 = p[i + 2 * nt], q3 = p[i + 3 * nt];
+    add_vec(q0, i); add_vec(q1, i + nt); add_vec(q2, i + 2 * nt); add_vec(q3, i + 3 * nt);
+  }
+  for (; i < nvec; i += nt) add_vec(p[i], i);
+}
+
+__device__ __forceinline__ uint64_t shfl_u64(uint64_t v, int src) {
+  const uint32_t lo = __shfl((uint32_t)v, src, kWave), hi = __shfl((uint32_t)(v >> 32), src, kWave);
+  return ((uint64_t)hi << 32) | lo;
+}
+__device__ __forceinline__ double shfl_f64(double v, int src) {
+  int lo = __double2loint(v), hi = __double2hiint(v);
+  lo = __shfl(lo, src, kWave);
+  hi = __shfl(hi, src, kWave);
+  return __hiloint2double(hi, lo);
+}
+
+// Descending bitonic sort of one 64-bit key per lane inside a wavefront.
+__device__ __forceinline__ uint64_t wave_sort_desc(uint64_t key) {
+  const int lane = threadIdx.x & 63;
+#pragma unroll
+  for (int k2 = 2; k2 <= kWave; k2 <<= 1) {
+#pragma unroll
+    for (int j = k2 >> 1; j > 0; j >>= 1) {
+      const uint64_t other = shfl_u64(key, lane ^ j);
+      const bool desc = (lane & k2) == 0, lower = (lane & j) == 0;
+      const uint64_t hi = key > other ? key : other, lo = key > other ? other : key;
+      key = (lower == desc) ? hi : lo;
+    }
+  }
+  return key;
+}
+
+constexpr int kNucleusRank = 64;     // top-p alone, first attempt: tau = this rank among the lane maxima
+
 template <int DT>
 __global__ __launch_bounds__(kWarpThreads) void warp_cutoffs_kernel(const void* z, int V, Scale sc, int top_k,
                                                                     float top_p, float* cutoff, uint32_t* flags,
@@ -243,7 +319,11 @@ __global__ __launch_bounds__(kWarpThreads) void warp_cutoffs_kernel(const void* 
   // sweep 1: maximum, normaliser, bad-row detection (NaN poisons the sum, +inf the maximum)
   Online acc[1];
   acc[0].init();
-  sweep_online<DT, false, false>(row, V, 0, 1, acc[0], lt);
+  Top4 top;
+  const bool tagged = aligned16(row) && V % Elem<DT>::per_vec == 0 &&
+                      V / Elem<DT>::per_vec <= kTagSteps * kWarpThreads;
+  if (tagged) sweep_online_top4<DT>(row, V, acc[0], top, lt);
+  else sweep_online<DT, false, false>(row, V, 0, 1, acc[0], lt);
   MS merged[1];
   block_merge<1>(acc, sh.mg, merged, lt);
   const float m = merged[0].m;
@@ -268,101 +348,228 @@ __global__ __launch_bounds__(kWarpThreads) void warp_cutoffs_kernel(const void* 
   const double m_t = (double)m * sc.inv_t;
   const double Z = exp(lse_row - m_t);                  // sum_v exp((z_v - m) / T)
 
-  // ---- candidate threshold from the lane maxima -----------------------------
-  float tau = -INFINITY;                                // V <= kCand: every entry is a candidate
-  bool try_list = true;
-  if (V > kCand) {
-    const int rank = use_k ? top_k : kGuessRank;       // tau = rank-th largest lane maximum
-    if (rank > kWarpThreads) {
-      try_list = false;
-    } else {
-      sh.lane_max[tid] = acc[0].m;
-      if (tid == 0) sh.tau = -INFINITY;
-      __syncthreads();
-      const float mine = sh.lane_max[tid];
-      int gt = 0, ge = 0;
-      for (int j = 0; j < kWarpThreads; j += 4) {
-        const float4 q = *reinterpret_cast<const float4*>(&sh.lane_max[j]);   // same address in all lanes
-        gt += (q.x > mine) + (q.y > mine) + (q.z > mine) + (q.w > mine);
-        ge += (q.x >= mine) + (q.y >= mine) + (q.z >= mine) + (q.w >= mine);
+  // The rank-th largest of the 512 lane maxima, to the 16 upper bits of its order key
+  // (exact for bfloat16, rounded down for fp32): a lower bound of the rank-th largest
+  // entry of the row.  Wavefront 0 holds eight maxima per lane and bisects the 16 bits
+  // with ballots.
+  sh.lane_key[tid] = okey(acc[0].m) >> 16;
+  __syncthreads();
+  auto lane_max_of_rank = [&](int rank) {
+    if (tid < kWave) {
+      uint32_t kk[kWarpThreads / kWave];
+#pragma unroll
+      for (int j = 0; j < kWarpThreads / kWave; ++j) kk[j] = sh.lane_key[tid + kWave * j];
+      uint32_t t = 0;
+      for (int bit = 15; bit >= 0; --bit) {
+        const uint32_t cand = t | (1u << bit);
+        int c = 0;
+#pragma unroll
+        for (int j = 0; j < kWarpThreads / kWave; ++j) c += __popcll(__ballot(kk[j] >= cand));
+        if (c >= rank) t = cand;
       }
-      if (gt < rank && rank <= ge) sh.tau = mine;      // every lane that writes holds the same value
+      if (tid == 0) sh.tau_key = t << 16;
+    }
+    __syncthreads();
+    const uint32_t tk = sh.tau_key;
+    // keys at or below that of -inf (lanes without a finite entry) mean: no bound
+    return tk <= (okey(-INFINITY) & 0xFFFF0000u) ? -INFINITY : from_okey(tk);
+  };
+
+  // The same decisions for a list of at most 64 entries, taken by wavefront 0 alone
+  // with shuffles (no barriers, no serial walk); it also writes the row's support.
+  auto settle_wave = [&](int n, float tau) {
+    const int lane = tid;                                // wavefront 0: tid = lane
+    uint64_t key = lane < n ? sh.key[lane] : 0;
+    key = wave_sort_desc(key);
+    const bool valid = lane < n;
+    const float v = valid ? key_value(key) : -INFINITY;
+    const double w = valid ? exp((double)v * sc.inv_t - m_t) : 0.0;
+    float t_k = -INFINITY;
+    int ns = n;
+    double total = Z;
+    if (use_k) {
+      if (n >= top_k) {
+        t_k = __shfl(v, top_k - 1, kWave);
+        ns = __popcll(__ballot(valid && v >= t_k));      // a prefix: the list is sorted
+      }
+      total = wave_sum_f64(lane < ns ? w : 0.0);
+    }
+    float th = t_k;
+    int nk = ns;
+    double kept = total;
+    bool ok = true;
+    int near = 0;
+    if (use_p) {
+      double incl = lane < ns ? w : 0.0;                 // inclusive prefix masses
+#pragma unroll
+      for (int off = 1; off < kWave; off <<= 1) {
+        const double o = shfl_f64(incl, max(lane - off, 0));
+        if (lane >= off) incl += o;
+      }
+      const float v_next = __shfl(v, min(lane + 1, kWave - 1), kWave);
+      const bool group_end = lane < ns && (lane == ns - 1 || v_next != v);
+      const double frac = incl / total;
+      const unsigned long long reach = __ballot(group_end && frac >= (double)top_p);
+      int d = reach ? (int)__builtin_ctzll(reach) : -1;
+      if (d < 0 && use_k) d = ns - 1;                    // survivors of top-k are their own total
+      ok = d >= 0;
+      if (ok) {
+        near = __ballot(group_end && lane <= d && fabs(frac - (double)top_p) < kNearTie) != 0;
+        th = __shfl(v, d, kWave);
+        nk = d + 1;
+        kept = shfl_f64(incl, d);
+      }
+    } else if (!use_k) {
+      kept = wave_sum_f64(w);                            // no warp at all (short rows)
+    }
+    nk = __popcll(__ballot(lane < nk && w > 0.0));       // masses that underflow fp64 are not listed
+    if (ok && out.count) {
+      if (nk <= out.cap) {
+        // order the kept entries by token id and write them out
+        uint64_t k2 = lane < nk ? (((uint64_t)(0xFFFFFFFFu - key_token(key)) << 32) | (uint64_t)lane) : 0;
+        k2 = wave_sort_desc(k2);
+        const double wj = shfl_f64(w, (int)(uint32_t)k2 & 63);
+        if (lane < nk) {
+          const size_t at = (size_t)r * out.cap + lane;
+          out.token[at] = (int32_t)(0xFFFFFFFFu - (uint32_t)(k2 >> 32));
+          out.prob[at] = wj / kept;
+        }
+      }
+      if (lane == 0) {
+        out.count[r] = nk <= out.cap ? nk : -1;
+        out.lse[r] = nk <= out.cap ? (float)(m_t + log(kept)) : __builtin_nanf("");
+      }
+    }
+    if (lane == 0) {
+      sh.theta = th;
+      sh.settled = ok ? 1 : 0;
+      sh.n_keep = ok ? nk : -1;
+      sh.z_keep = kept;
+      sh.near_tie = ok ? near : 0;
+      sh.out_done = ok ? 1 : 0;
+    }
+  };
+
+  // Settle top-k / top-p on the list sh.key[0 .. sh.n_cand) of all entries >= tau.
+  // Called by all threads; true when the list decides the row (then sh.theta,
+  // sh.n_keep, sh.z_keep are set and the kept entries are sh.key[0 .. n_keep)).
+  auto settle = [&](float tau) {
+    const int n = sh.n_cand;
+    if (n <= kWave && (!use_k || n >= top_k || tau == -INFINITY)) {
+      if (tid < kWave) settle_wave(n, tau);
       __syncthreads();
-      tau = sh.tau;
+      return sh.settled != 0;
+    }
+    // fewer than K candidates happens only when tau = -inf lists every finite entry
+    // of the row (masked vocabularies): top-k then keeps them all
+    if (!(n <= kCand && (!use_k || n >= top_k || tau == -INFINITY))) return false;
+    int n2 = 64;
+    while (n2 < n) n2 <<= 1;
+    for (int i = n + tid; i < n2; i += blockDim.x) sh.key[i] = 0;      // below every real key
+    __syncthreads();
+    sort_desc(sh.key, n2);
+    for (int i = tid; i < n; i += blockDim.x)
+      sh.w[i] = exp((double)key_value(sh.key[i]) * sc.inv_t - m_t);
+    __syncthreads();
+    if (tid == 0) {
+      float t_k = -INFINITY;
+      int ns = n;                                     // survivors of top-k: sorted entries 0..ns-1
+      double total = Z;
+      if (use_k) {
+        if (n >= top_k) {
+          t_k = key_value(sh.key[top_k - 1]);
+          ns = top_k;
+          while (ns < n && key_value(sh.key[ns]) == t_k) ++ns;
+        }
+        total = 0.0;
+        for (int i = 0; i < ns; ++i) total += sh.w[i];
+      }
+      float th = t_k;
+      int nk = ns;                                    // kept entries: sorted entries 0..nk-1
+      double kept = total;
+      bool ok = true;
+      int near = 0;
+      if (use_p) {
+        ok = false;
+        double run = 0.0;
+        int i = 0;
+        while (i < ns) {
+          const float v = key_value(sh.key[i]);
+          do { run += sh.w[i]; ++i; } while (i < ns && key_value(sh.key[i]) == v);
+          const double frac = run / total;
+          if (fabs(frac - (double)top_p) < kNearTie) near = 1;
+          if (frac >= (double)top_p) { th = v; nk = i; kept = run; ok = true; break; }
+        }
+        // top-k survivors always reach P (their own mass is the total); a list
+        // without top-k may end before the row's mass does
+        if (!ok && use_k) { th = key_value(sh.key[ns - 1]); nk = ns; kept = run; ok = true; }
+      } else if (!use_k) {
+        kept = 0.0;                                   // no warp at all (short rows): everything is kept
+        for (int i = 0; i < n; ++i) kept += sh.w[i];
+      }
+      while (nk > 0 && sh.w[nk - 1] == 0.0) --nk;     // masses that underflow fp64 are not listed
+      sh.theta = th;
+      sh.settled = ok ? 1 : 0;
+      sh.n_keep = ok ? nk : -1;
+      sh.z_keep = kept;
+      sh.near_tie = ok ? near : 0;
+    }
+    __syncthreads();
+    return sh.settled != 0;
+  };
+
+  bool settled = false;
+  if (tid == 0) { sh.n_cand = 0; sh.near_tie = 0; sh.settled = 0; sh.n_keep = -1; sh.out_done = 0; }
+  __syncthreads();
+
+  // ---- attempt 1 (tagged rows): only the lanes' largest vectors are read again
+  if (tagged && V > kCand && (!use_k || top_k <= kWarpThreads)) {
+    const float tau = lane_max_of_rank(use_k ? top_k : kNucleusRank);
+    const uint32_t tau_key = sh.tau_key;
+    // a lane whose fourth-largest vector may reach tau may hide a fifth one that does
+    const int hidden = __syncthreads_or(top.k4 >= tau_key);
+    if (!hidden && tau > -INFINITY) {
+      constexpr int EPV = Elem<DT>::per_vec;
+      const u32x4* p = reinterpret_cast<const u32x4*>(row);
+      const uint32_t keys[3] = {top.k1, top.k2, top.k3};
+#pragma unroll
+      for (int q = 0; q < 3; ++q) {
+        if (keys[q] >= tau_key) {
+          const uint32_t vec = (keys[q] & 0xFFFFu) * kWarpThreads + (uint32_t)tid;
+          float f[EPV];
+          unpack<DT>(p[vec], f);
+#pragma unroll
+          for (int e = 0; e < EPV; ++e) {
+            if (f[e] >= tau && f[e] > -INFINITY) {
+              const int at = atomicAdd(&sh.n_cand, 1);
+              if (at < kCand)
+                sh.key[at] = ((uint64_t)okey(f[e]) << 32) | (uint64_t)(0xFFFFFFFFu - (vec * EPV + (uint32_t)e));
+            }
+          }
+        }
+      }
+      __syncthreads();
+      settled = settle(tau);
     }
   }
 
-  float theta = 0.f;
-  bool settled = false;
-  if (tid == 0) { sh.n_cand = 0; sh.near_tie = 0; sh.settled = 0; sh.n_keep = -1; }
-  __syncthreads();
-  if (try_list) {
-    // sweep 2: collect the candidates (a few per row: the shared counter is not a bottleneck)
+  // ---- attempt 2: a second sweep (from cache) lists every entry >= tau -------
+  if (!settled && (V <= kCand || !use_k || top_k <= kWarpThreads)) {
+    float tau = -INFINITY;                              // V <= kCand: every entry is a candidate
+    if (V > kCand) tau = lane_max_of_rank(use_k ? top_k : kGuessRank);
+    __syncthreads();
+    if (tid == 0) sh.n_cand = 0;
+    __syncthreads();
     visit_range<DT, false, 4>(row, nullptr, 0, V, [&](int v, float zv, float) {
       if (zv >= tau && zv > -INFINITY) {                // entries at -inf carry no mass and are never listed
-        const int at = atomicAdd(&sh.n_cand, 1);
+        const int at = atomicAdd(&sh.n_cand, 1);        // a few per row: the shared counter is not a bottleneck
         if (at < kCand) sh.key[at] = ((uint64_t)okey(zv) << 32) | (uint64_t)(0xFFFFFFFFu - (uint32_t)v);
       }
     });
     __syncthreads();
-    const int n = sh.n_cand;
-    // fewer than K candidates happens only when tau = -inf lists every finite entry
-    // of the row (masked vocabularies): top-k then keeps them all
-    if (n <= kCand && (!use_k || n >= top_k || tau == -INFINITY)) {
-      int n2 = 64;
-      while (n2 < n) n2 <<= 1;
-      for (int i = n + tid; i < n2; i += blockDim.x) sh.key[i] = 0;      // below every real key
-      __syncthreads();
-      sort_desc(sh.key, n2);
-      for (int i = tid; i < n; i += blockDim.x)
-        sh.w[i] = exp((double)key_value(sh.key[i]) * sc.inv_t - m_t);    // exp(-inf) = 0
-      __syncthreads();
-      if (tid == 0) {
-        float t_k = -INFINITY;
-        int ns = n;                                     // survivors of top-k: sorted entries 0..ns-1
-        double total = Z;
-        if (use_k) {
-          if (n >= top_k) {
-            t_k = key_value(sh.key[top_k - 1]);
-            ns = top_k;
-            while (ns < n && key_value(sh.key[ns]) == t_k) ++ns;
-          }
-          total = 0.0;
-          for (int i = 0; i < ns; ++i) total += sh.w[i];
-        }
-        float th = t_k;
-        int nk = ns;                                    // kept entries: sorted entries 0..nk-1
-        double kept = total;
-        bool ok = true;
-        if (use_p) {
-          ok = false;
-          double run = 0.0;
-          int i = 0;
-          while (i < ns) {
-            const float v = key_value(sh.key[i]);
-            do { run += sh.w[i]; ++i; } while (i < ns && key_value(sh.key[i]) == v);
-            const double frac = run / total;
-            if (fabs(frac - (double)top_p) < kNearTie) sh.near_tie = 1;
-            if (frac >= (double)top_p) { th = v; nk = i; kept = run; ok = true; break; }
-          }
-          // top-k survivors always reach P (their own mass is the total); a list
-          // without top-k may end before the row's mass does
-          if (!ok && use_k) { th = key_value(sh.key[ns - 1]); nk = ns; kept = run; ok = true; }
-        } else if (!use_k) {
-          kept = 0.0;                                   // no warp at all (short rows): everything is kept
-          for (int i = 0; i < n; ++i) kept += sh.w[i];
-        }
-        while (nk > 0 && sh.w[nk - 1] == 0.0) --nk;     // masses that underflow fp64 are not listed
-        sh.theta = th;
-        sh.settled = ok ? 1 : 0;
-        sh.n_keep = nk;
-        sh.z_keep = kept;
-      }
-      __syncthreads();
-      settled = sh.settled != 0;
-      theta = sh.theta;
-    }
+    settled = settle(tau);
   }
+  float theta = sh.theta;
   if (!settled) {
     __syncthreads();
     if (tid == 0) { sh.near_tie = 0; sh.n_keep = -1; }
@@ -372,7 +579,7 @@ __global__ __launch_bounds__(kWarpThreads) void warp_cutoffs_kernel(const void* 
     if (cutoff) cutoff[r] = theta;
     if (flags) flags[r] = sh.near_tie ? SV_FLAG_NEAR_TIE : 0u;
   }
-  if (!out.count) return;
+  if (!out.count || (settled && sh.out_done)) return;    // (the wavefront path has written the support already)
 
   // ---- support of the warped row: token ids ascending, fp64 probabilities ----
   __syncthreads();
