@@ -45,3 +45,95 @@ def test_random_problems(block):
             gg, go, gm = H.gpu_select_length(p, l, mode)
             assert gm == rm and np.array_equal(gg, rg) and np.array_equal(go, ro)
     print(f"\n  block {block}: {n_seq} sequences, near-tie {n_tie}, near-cdf-edge {n_edge}", flush=True)
+
+
+@pytest.mark.parametrize("block", range(4))
+def test_random_warped_problems(block):
+    """Random shapes and sampling hyper-parameters through the dense warped entry
+    points (GPU cutoffs) and through the compacted ones, both against the oracle
+    on warped rows.  Sequences touching a near-tie top-p decision are skipped."""
+    from oracle import warp_oracle as W
+    P = H.sv()
+    rng = np.random.default_rng(7700 + block)
+    n_seq = n_tie = n_sparse = 0
+    for case in range(8):
+        idx = int(rng.integers(0, 4))
+        B = int(rng.integers(1, 6))
+        k = int(rng.integers(1, 7))
+        V = int(rng.choice([int(rng.integers(2, 300)), int(rng.integers(300, 9000)),
+                            8 * int(rng.integers(1000, 5000)), 8192 * int(rng.integers(1, 4)) + int(rng.integers(0, 9))]))
+        dtype = "bf16" if rng.random() < 0.7 else "f32"
+        cfg = svgen.make_config(idx, B=B, k=k, V=V, dtype=dtype, seed=int(rng.integers(0, 2 ** 31)))
+        d = {n: cfg[n].cuda() for n in ("z_t", "z_d", "z_c", "x")}
+        oi = H.oracle_inputs(cfg)
+        par = {}
+        for name in ("t", "d", "c"):
+            T = float(np.float32(rng.choice([0.6, 0.7, 0.95, 1.0, 1.3])))
+            K = int(rng.choice([0, 1, 5, 20, 50]))
+            Pp = float(rng.choice([1.0, 0.9, 0.8, 0.6]))
+            par[name] = (T, K, Pp)
+        y, cut, fl, gcut, gfl, sup = {}, {}, {}, {}, {}, {}
+        for name, z in (("t", "z_t"), ("d", "z_d"), ("c", "z_c")):
+            T, K, Pp = par[name]
+            y[name], cut[name], fl[name] = W.warp_rows(oi[z], T, K, Pp)
+            rows = d[z].shape[0] * d[z].shape[1]
+            gcut[name] = torch.empty(rows, dtype=torch.float32, device="cuda")
+            gf = torch.empty(rows, dtype=torch.int32, device="cuda")
+            sup[name] = P.Supports(rows, 128)
+            P.sv_warp_compact(d[z], T, K, Pp, sup[name], gcut[name], gf)
+            torch.cuda.synchronize()
+            gfl[name] = gf.cpu().numpy().astype(np.uint32).reshape(fl[name].shape)
+        tie = lambda n: ((fl[n] | gfl[n]) & O.FLAG_NEAR_TIE) != 0
+        pair_tie = tie("d") | tie("c")
+        seq_tie = tie("t").any(1) | tie("d").any(1)
+        # drafted tokens from the warped draft distribution
+        x = np.zeros((B, k), dtype=np.int32)
+        for b in range(B):
+            for i in range(k):
+                p = np.exp(y["d"][b, i] - y["d"][b, i].max())
+                x[b, i] = rng.choice(V, p=p / p.sum())
+        xg = H.dev(x, torch.int32)
+        ref = O.row_stats(y["d"], y["c"], x)
+        f32 = lambda *s: torch.full(s, -7.0, dtype=torch.float32, device="cuda")
+        i32 = lambda *s: torch.full(s, -5, dtype=torch.int32, device="cuda")
+        ws = P.alloc_workspace(B, k, V, P.binding._dtype_tag(d["z_d"]))
+        keep = ~pair_tie
+        pick = lambda dct, m: {n: np.asarray(v)[m] for n, v in dct.items()}
+        # dense warped indicators
+        o = dict(lse_d=f32(B, k), lse_c=f32(B, k), S=f32(B, k), A=f32(B, k), KL=f32(B, k), H_d=f32(B, k),
+                 pd_x=f32(B, k), flags=i32(B, k))
+        P.sv_row_stats_warped(d["z_d"], d["z_c"], xg, par["d"][0], gcut["d"], par["c"][0], gcut["c"], o["lse_d"],
+                              o["lse_c"], o["S"], o["A"], o["KL"], o["flags"], ws, entropy_d=o["H_d"], pd_x=o["pd_x"])
+        torch.cuda.synchronize()
+        H.assert_row_stats(pick({n: t.cpu().numpy() for n, t in o.items()}, keep), pick(ref, keep))
+        # compacted indicators
+        P.sv_row_stats_sparse(sup["d"], sup["c"], xg, V, o["lse_d"], o["lse_c"], o["S"], o["A"], o["KL"], o["flags"],
+                              entropy_d=o["H_d"], pd_x=o["pd_x"])
+        torch.cuda.synchronize()
+        got = {n: t.cpu().numpy() for n, t in o.items()}
+        ks = keep & ((got["flags"].astype(np.uint32) & 32) == 0)
+        n_sparse += int(ks.sum())
+        H.assert_row_stats(pick(got, ks), pick(ref, ks))
+        # verification, dense warped and compacted
+        gamma = rng.integers(0, k + 1, size=B).astype(np.int32) if rng.random() < 0.6 else None
+        gg = None if gamma is None else H.dev(gamma, torch.int32)
+        pseed, step = int(rng.integers(0, 2 ** 62)), int(rng.integers(0, 2 ** 31))
+        vref = O.verify_sample(y["t"], y["d"], x, gamma=gamma, seed=pseed, step=step)
+        sub = lambda dct, m: {n: ([v[i] for i in np.flatnonzero(m)] if isinstance(v, list) else np.asarray(v)[m])
+                              for n, v in dct.items()}
+        for mode in ("dense", "sparse"):
+            tokens, n_acc, flags, ratio = i32(B, k + 1), i32(B), i32(B), f32(B, k)
+            if mode == "dense":
+                P.sv_verify_sample_warped(d["z_t"], None, d["z_d"], xg, gg, par["t"][0], gcut["t"], par["d"][0],
+                                          gcut["d"], pseed, step, tokens, n_acc, flags, ratio, ws)
+            else:
+                P.sv_verify_sample_sparse(sup["t"], None, sup["d"], xg, gg, V, pseed, step, tokens, n_acc, flags, ratio)
+            torch.cuda.synchronize()
+            vgot = dict(tokens=tokens.cpu().numpy(), n_accept=n_acc.cpu().numpy(),
+                        flags=flags.cpu().numpy().astype(np.uint32), ratio=ratio.cpu().numpy())
+            m = ~seq_tie & ((vgot["flags"] & 32) == 0)
+            t, _ = H.assert_verify(sub(vgot, m), sub(vref, m), k)
+            n_tie += t
+            n_seq += int(m.sum())
+    print(f"\n  warped block {block}: {n_seq} sequence checks, {n_sparse} compacted pairs, near-tie {n_tie}", flush=True)
+    assert n_seq >= 20 and n_sparse >= 20
