@@ -271,10 +271,11 @@ __device__ __forceinline__ void sweep_online_top4(const void* row, int V, Online
   };
   int i = tid;
   for (; i + 3 * nt < nvec; i += 4 * nt) {
-    const u32x4 q0 = p[i], q1 = p[i + nt], q2 = p[i + 2 * nt], q3 = p[i + 3 * nt];
+    const u32x4 q0 = __builtin_nontemporal_load(p + i), q1 = __builtin_nontemporal_load(p + i + nt),
+                q2 = __builtin_nontemporal_load(p + i + 2 * nt), q3 = __builtin_nontemporal_load(p + i + 3 * nt);
     add_vec(q0, i); add_vec(q1, i + nt); add_vec(q2, i + 2 * nt); add_vec(q3, i + 3 * nt);
   }
-  for (; i < nvec; i += nt) add_vec(p[i], i);
+  for (; i < nvec; i += nt) add_vec(__builtin_nontemporal_load(p + i), i);
 }
 
 __device__ __forceinline__ uint64_t shfl_u64(uint64_t v, int src) {
