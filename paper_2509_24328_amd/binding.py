@@ -94,7 +94,15 @@ def _check(status):
 
 
 def _ptr(t):
-    return None if t is None else ctypes.c_void_p(t.data_ptr())
+    """Device address of a tensor (None -> NULL).  The C ABI takes plain pointers to
+    dense row-major device memory, so anything else is refused here instead of being
+    read as if it were."""
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("sv: tensors must be contiguous device tensors "
+                         f"(got device={t.device}, contiguous={t.is_contiguous()})")
+    return ctypes.c_void_p(t.data_ptr())
 
 
 def _stream(stream):

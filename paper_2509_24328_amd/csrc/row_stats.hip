@@ -441,13 +441,16 @@ static int launch_stats(const StatsArgs& a, bool rows_aligned, hipStream_t st) {
     return launch_status();
   }
   if (rows_aligned) {
-    // more than 64 KB of dynamic LDS has to be allowed once per kernel
-    static bool allowed = false;
-    if (!allowed) {
+    // more than 64 KB of dynamic LDS has to be allowed once per kernel and device
+    constexpr int kMaxDevices = 64;
+    static bool allowed[kMaxDevices] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return SV_ERR_LAUNCH;
+    if (dev < 0 || dev >= kMaxDevices || !allowed[dev]) {
       if (hipFuncSetAttribute(reinterpret_cast<const void*>(&row_stats_stash_kernel<DT, WITH_KL>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kStashLdsBytes) != hipSuccess)
         return SV_ERR_LAUNCH;
-      allowed = true;
+      if (dev >= 0 && dev < kMaxDevices) allowed[dev] = true;
     }
     TapScope tap(SV_KERNEL_ROW_STATS, st);
     hipLaunchKernelGGL((row_stats_stash_kernel<DT, WITH_KL>), grid, dim3(kStashThreads), kStashLdsBytes, st, a);

@@ -176,3 +176,11 @@ def test_compact_and_sparse_argument_errors():
     assert vs(out=None) == Bd.SV_ERR_NULL
     assert vs(prob=odd) == Bd.SV_ERR_ALIGN
     assert vs(B=0) == Bd.SV_OK
+
+
+def test_binding_refuses_host_and_strided_tensors():
+    import pytest
+    import torch
+    with pytest.raises(ValueError):
+        Bd._ptr(torch.zeros(4))                    # host memory
+    assert Bd._ptr(None) is None
