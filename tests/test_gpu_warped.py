@@ -236,3 +236,46 @@ def test_decode_step_with_gpu_cutoffs_end_to_end():
     sub = lambda d: {n: ([v[i] for i in np.flatnonzero(keep)] if isinstance(v, list) else np.asarray(v)[keep])
                      for n, v in d.items()}
     H.assert_verify(sub(got), sub(ref), k)
+
+
+@pytest.mark.parametrize("T", [0.01, 0.05, 20.0, 100.0])
+def test_extreme_temperatures(T):
+    """Very sharp and very flat warped distributions, dense and compacted."""
+    P = H.sv()
+    T = _t32(T)
+    K, Pp = (0, 1.0) if T > 1 else (50, 0.99)
+    for idx, B, k, V, dtype in ((1, 2, 3, 32000, "bf16"), (0, 2, 2, 4099, "f32")):
+        cfg = svgen.make_config(idx, seed=600 + idx, B=B, k=k, V=V, dtype=dtype, device="cuda")
+        inp = H.oracle_inputs(cfg)
+        y_t, cut_t, f_t = W.warp_rows(inp["z_t"], T, K, Pp)
+        y_d, cut_d, f_d = W.warp_rows(inp["z_d"], T, K, Pp)
+        y_c, cut_c, f_c = W.warp_rows(inp["z_c"], T, K, Pp)
+        x = _redraw_tokens(y_d, 9)
+        xg = H.dev(x, torch.int32)
+        pair_ok = ((f_d | f_c) & O.FLAG_NEAR_TIE) == 0
+        ref = O.row_stats(y_d, y_c, x)
+        got = _gpu_row_stats_warped(cfg["z_d"], cfg["z_c"], xg, T, _cut32(cut_d), T, _cut32(cut_c))
+        H.assert_row_stats({n: v[pair_ok] for n, v in got.items()}, {n: np.asarray(v)[pair_ok] for n, v in ref.items()})
+        vref = O.verify_sample(y_t, y_d, x, seed=3, step=8)
+        vgot = _gpu_verify_warped(cfg["z_t"], cfg["z_d"], xg, T, _cut32(cut_t), T, _cut32(cut_d), seed=3, step=8)
+        seq_ok = ~(((f_t & O.FLAG_NEAR_TIE) != 0).any(1) | ((f_d & O.FLAG_NEAR_TIE) != 0).any(1))
+        sub = lambda d: {n: ([v[i] for i in np.flatnonzero(seq_ok)] if isinstance(v, list) else np.asarray(v)[seq_ok])
+                         for n, v in d.items()}
+        H.assert_verify(sub(vgot), sub(vref), k)
+        if T < 1:                                        # sharp rows compact to a handful of tokens
+            sup_d = P.Supports(B * k, 64)
+            gf = torch.zeros(B * k, dtype=torch.int32, device="cuda")
+            P.sv_warp_compact(cfg["z_d"], T, K, Pp, sup_d, None, gf)
+            torch.cuda.synchronize()
+            count = sup_d.count.cpu().numpy().reshape(B, k)
+            tok = sup_d.token.cpu().numpy().reshape(B, k, -1)
+            prob = sup_d.prob.cpu().numpy().reshape(B, k, -1)
+            gfn = gf.cpu().numpy().reshape(B, k).astype(np.uint32)
+            for b in range(B):
+                for i in range(k):
+                    if (gfn[b, i] | f_d[b, i]) & O.FLAG_NEAR_TIE or count[b, i] < 0:
+                        continue
+                    keep = np.flatnonzero(np.isfinite(y_d[b, i]) & (np.exp(y_d[b, i] - y_d[b, i].max()) > 0))
+                    assert np.array_equal(tok[b, i, :count[b, i]], keep)
+                    e = np.exp(y_d[b, i][keep] - y_d[b, i].max())
+                    assert np.allclose(prob[b, i, :count[b, i]], e / e.sum(), rtol=1e-12, atol=0)
