@@ -193,7 +193,8 @@ def main():
     for kid in names:
         P.sv_set_timing_events(kid, None, None)
     torch.cuda.synchronize()
-    us = {names[kid]: float(np.mean([hip.elapsed_ms(a, b) for a, b in ev[kid]]) * 1e3) for kid in names}
+    samples = {names[kid]: np.array([hip.elapsed_ms(a, b) for a, b in ev[kid]]) * 1e3 for kid in names}
+    us = {n: float(np.mean(v)) for n, v in samples.items()}
     for kid in names:
         for a, b in ev[kid]:
             hip.lib.hipEventDestroy(a)
@@ -208,7 +209,8 @@ def main():
            "select_batch_kernel": 0}
     kernels = {}
     for n, t_us in us.items():
-        kernels[n] = {"avg_us": round(t_us, 2)}
+        kernels[n] = {"avg_us": round(t_us, 2), "median_us": round(float(np.median(samples[n])), 2),
+                      "min_us": round(float(np.min(samples[n])), 2)}
         if alg[n]:
             gbs = alg[n] / t_us * 1e-3
             kernels[n].update({"algorithmic_bytes": alg[n], "achieved_GBps": round(gbs, 1),

@@ -355,6 +355,16 @@ int sv_verify_sample_sparse(const int32_t* count_t, const int32_t* token_t, cons
                             float* ratio_or_null, sv_stream_t stream);
 
 /*
+ * The uniforms sv_verify_sample draws (for tests and for callers that want to
+ * replay a step): Philox-4x32-10 with counter (i, b, 0, step) and key (seed low,
+ * seed high); output word 0 -> accept uniform of drafted position i, word 1 ->
+ * sampling uniform of position i; value ((w >> 8) + 0.5) * 2^-24.
+ *   u_accept, u_sample  [B, n_pos] double  out
+ */
+int sv_uniforms(uint64_t seed, uint32_t step, int B, int n_pos, double* u_accept, double* u_sample,
+                sv_stream_t stream);
+
+/*
  * Timing taps for benchmarks (not part of the method): while a pair of
  * hipEvent_t handles is set for `kernel`, every launch of that kernel records
  * `start_event` immediately before and `stop_event` immediately after it on the

@@ -29,7 +29,7 @@ EXPORTS = ("sv_strerror", "sv_workspace_bytes", "sv_row_stats", "sv_accept_estim
            "sv_select_length", "sv_verify_sample", "sv_set_timing_events", "sv_accept_ratio",
            "sv_quantile_edges", "sv_profile_accumulate", "sv_profile_finalize", "sv_warp_cutoffs",
            "sv_row_stats_warped", "sv_verify_sample_warped",
-           "sv_warp_compact", "sv_row_stats_sparse", "sv_verify_sample_sparse")
+           "sv_warp_compact", "sv_row_stats_sparse", "sv_verify_sample_sparse", "sv_uniforms")
 (SV_KERNEL_ROW_STATS, SV_KERNEL_ACCEPT_ESTIMATE, SV_KERNEL_SELECT_LENGTH, SV_KERNEL_VERIFY_ROWS,
  SV_KERNEL_VERIFY_ACCEPT, SV_KERNEL_VERIFY_MASS, SV_KERNEL_VERIFY_PICK, SV_KERNEL_COUNT) = range(8)
 
@@ -78,6 +78,8 @@ lib.sv_row_stats_sparse.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, 
 lib.sv_verify_sample_sparse.restype = _i
 lib.sv_verify_sample_sparse.argtypes = [_vp, _vp, _vp, _vp, _i, _vp, _vp, _vp, _i, _vp, _vp, _i, _i, _i,
                                         ctypes.c_uint64, ctypes.c_uint32, _vp, _vp, _vp, _vp, _vp]
+lib.sv_uniforms.restype = _i
+lib.sv_uniforms.argtypes = [ctypes.c_uint64, ctypes.c_uint32, _i, _i, _vp, _vp, _vp]
 lib.sv_set_timing_events.restype = _i
 lib.sv_set_timing_events.argtypes = [_i, _vp, _vp]
 
@@ -260,3 +262,8 @@ def sv_verify_sample_sparse(sup_t, t_offsets, sup_d, x, gamma, V, seed, step, ou
                                        n_t_rows, _ptr(sup_d.count), _ptr(sup_d.token), _ptr(sup_d.prob),
                                        sup_t.cap, _ptr(x), _ptr(gamma), B, k, V, seed, step, _ptr(out_tokens),
                                        _ptr(n_accept), _ptr(flags), _ptr(ratio), _stream(stream)))
+
+
+def sv_uniforms(seed, step, u_accept, u_sample, stream=None):
+    B, n_pos = u_accept.shape
+    _check(lib.sv_uniforms(seed, step, B, n_pos, _ptr(u_accept), _ptr(u_sample), _stream(stream)))

@@ -1,4 +1,5 @@
 // Shape-independent parts of the C ABI: status strings and workspace sizing.
+#include "sv_device.hpp"
 #include "sv_host.hpp"
 
 extern "C" const char* sv_strerror(int status) {
@@ -31,4 +32,31 @@ extern "C" int sv_set_timing_events(int kernel, void* start_event, void* stop_ev
   sv::g_taps[kernel].start = reinterpret_cast<hipEvent_t>(start_event);
   sv::g_taps[kernel].stop = reinterpret_cast<hipEvent_t>(stop_event);
   return SV_OK;
+}
+
+namespace sv {
+// one lane per (sequence, position): both uniforms of its counter
+__global__ void uniforms_kernel(uint32_t seed_lo, uint32_t seed_hi, uint32_t step, int B, int n_pos,
+                                double* u_accept, double* u_sample) {
+  const long j = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= (long)B * n_pos) return;
+  const uint32_t b = (uint32_t)(j / n_pos), i = (uint32_t)(j % n_pos);
+  const U4 r = philox4x32_10(i, b, 0u, step, seed_lo, seed_hi);
+  u_accept[j] = unit_from_word(r.w[0]);
+  u_sample[j] = unit_from_word(r.w[1]);
+}
+}  // namespace sv
+
+extern "C" int sv_uniforms(uint64_t seed, uint32_t step, int B, int n_pos, double* u_accept, double* u_sample,
+                           sv_stream_t stream) {
+  using namespace sv;
+  SV_REQUIRE(B >= 0 && n_pos >= 1, SV_ERR_INVALID_ARG);
+  SV_REQUIRE((long long)B * n_pos <= 0x7fffffffLL, SV_ERR_TOO_LARGE);
+  if (B == 0) return SV_OK;
+  SV_REQUIRE(u_accept && u_sample, SV_ERR_NULL);
+  SV_REQUIRE(is_aligned(u_accept, 8) && is_aligned(u_sample, 8), SV_ERR_ALIGN);
+  const long n = (long)B * n_pos;
+  hipLaunchKernelGGL(uniforms_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, as_stream(stream),
+                     (uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32), step, B, n_pos, u_accept, u_sample);
+  return launch_status();
 }

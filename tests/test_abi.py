@@ -184,3 +184,12 @@ def test_binding_refuses_host_and_strided_tensors():
     with pytest.raises(ValueError):
         Bd._ptr(torch.zeros(4))                    # host memory
     assert Bd._ptr(None) is None
+
+
+def test_uniforms_argument_errors():
+    L = Bd.lib
+    p = ctypes.c_void_p(256 * 1024)
+    assert L.sv_uniforms(1, 0, 4, 0, p, p, None) == Bd.SV_ERR_INVALID_ARG
+    assert L.sv_uniforms(1, 0, 4, 4, None, p, None) == Bd.SV_ERR_NULL
+    assert L.sv_uniforms(1, 0, 4, 4, ctypes.c_void_p(256 * 1024 + 4), p, None) == Bd.SV_ERR_ALIGN
+    assert L.sv_uniforms(1, 0, 0, 4, None, None, None) == Bd.SV_OK

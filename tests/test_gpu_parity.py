@@ -158,3 +158,20 @@ def test_chained_step_config2():
     got = dict(tokens=tokens.cpu().numpy(), n_accept=n_acc.cpu().numpy(),
                flags=flags.cpu().numpy().astype(np.uint32), ratio=ratio.cpu().numpy())
     H.assert_verify(got, ref, k)
+
+
+def test_philox_uniforms_agree_on_a_million_counters():
+    """The two independently written Philox generators (oracle/philox.py and the
+    device one) on 2 * 10^6 uniforms: bit-identical doubles."""
+    from oracle import philox as OP
+    P = H.sv()
+    B, n_pos = 1000, 1000
+    for seed, step in ((0, 0), (0x0123456789ABCDEF, 7), ((1 << 64) - 1, (1 << 32) - 1)):
+        ua = torch.empty((B, n_pos), dtype=torch.float64, device="cuda")
+        us = torch.empty((B, n_pos), dtype=torch.float64, device="cuda")
+        P.sv_uniforms(seed, step, ua, us)
+        torch.cuda.synchronize()
+        b = np.arange(B)[:, None]
+        i = np.arange(n_pos)[None, :]
+        ra, rs = OP.sv_uniforms(seed, step, b, i)
+        assert np.array_equal(ua.cpu().numpy(), ra) and np.array_equal(us.cpu().numpy(), rs)
