@@ -269,6 +269,26 @@ def main():
                   "gamma_equal": bool(np.array_equal(got["gamma"], rg)) if nseq == B else None}
         assert bad == 0 and s_err < 1e-5 and a_err < 1e-5, parity
 
+    # ---- sv_row_stats with the optional outputs (KL, draft entropy, P_d(x): the signals of
+    # the baseline predictors), same rotation of inputs; bracketed by the same timing tap
+    kl_out, ent_out, pdx_out = f32(B, k), f32(B, k), f32(B, k)
+    for i in range(3):
+        c = copies[i % len(copies)]
+        P.sv_row_stats(c["z_d"], c["z_c"], c["x"], lse_d, lse_c, S, A, kl_out, None, ws, stream,
+                       entropy_d=ent_out, pd_x=pdx_out)
+    torch.cuda.synchronize()
+    xe = [(hip.event(), hip.event()) for _ in range(40)]
+    for i, (e0, e1) in enumerate(xe):
+        c = copies[i % len(copies)]
+        P.sv_set_timing_events(Bd.SV_KERNEL_ROW_STATS, e0, e1)
+        P.sv_row_stats(c["z_d"], c["z_c"], c["x"], lse_d, lse_c, S, A, kl_out, None, ws, stream,
+                       entropy_d=ent_out, pd_x=pdx_out)
+    P.sv_set_timing_events(Bd.SV_KERNEL_ROW_STATS, None, None)
+    torch.cuda.synchronize()
+    ext_us = float(np.mean([hip.elapsed_ms(a, b) for a, b in xe]) * 1e3)
+    row_stats_extended = {"outputs": "S, A, KL, H(P_d), P_d(x)", "avg_us": round(ext_us, 2),
+                          "achieved_GBps": round(alg["row_stats_stash_kernel"] / ext_us * 1e-3, 1)}
+
     # ---- profile-construction pass (the offline step before the hot path), timed
     # on a held-out batch of the same recipe: S, A from sv_row_stats, X from
     # sv_accept_ratio, 10x10 uniform grid, histogram, table + information gain
@@ -460,6 +480,7 @@ def main():
         "graph_replay": None if graph_ms is None else {
             "ms_per_step": round(graph_ms, 5), "rows_per_s": round(rows_per_step / (graph_ms * 1e-3), 1)},
         "parity": parity,
+        "row_stats_extended": row_stats_extended,
         "profile_pass": profile_pass,
         "warped_step": warped_step,
         "mean_gamma_selected": float(np.mean(got["gamma"])),
