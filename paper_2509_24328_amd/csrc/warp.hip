@@ -73,7 +73,7 @@ struct alignas(16) WarpShared {
   };
   uint32_t tau_key;
   float theta;
-  int n_cand, settled, n_keep, out_done;
+  int n_cand, settled, n_keep, out_done, first_reach, near_any;
   double z_keep;               // mass of the kept entries
   int sel_digit;
   uint32_t sel_count_above;
@@ -305,7 +305,12 @@ __device__ __forceinline__ uint64_t wave_sort_desc(uint64_t key) {
   return key;
 }
 
-constexpr int kNucleusRank = 64;     // top-p alone, first attempt: tau = this rank among the lane maxima
+// top-p alone has no K and guesses the depth of the nucleus from the lane maxima: a
+// list of about rank + rank^2 / 1024 entries, short enough for the one-wavefront
+// settle when the largest 48 lane maxima already carry P of the row's mass, a deeper
+// one otherwise
+constexpr int kNucleusRank = 48;
+constexpr int kNucleusRank2 = 256;
 
 template <int DT>
 __global__ __launch_bounds__(kWarpThreads) void warp_cutoffs_kernel(const void* z, int V, Scale sc, int top_k,
@@ -472,48 +477,92 @@ __global__ __launch_bounds__(kWarpThreads) void warp_cutoffs_kernel(const void* 
     for (int i = tid; i < n; i += blockDim.x)
       sh.w[i] = exp((double)key_value(sh.key[i]) * sc.inv_t - m_t);
     __syncthreads();
+    // Every lane owns a run of consecutive sorted entries; the masses of the
+    // survivors are prefix-summed over the workgroup (fp64), then every lane looks
+    // at the ends of groups of equal value inside its run.
+    float t_k = -INFINITY;
+    int ns = n;                                       // survivors of top-k: sorted entries 0..ns-1
+    if (use_k && n >= top_k) {
+      t_k = key_value(sh.key[top_k - 1]);
+      int lo = top_k, hi = n;                         // first entry below t_k
+      while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (key_value(sh.key[mid]) >= t_k) lo = mid + 1; else hi = mid;
+      }
+      ns = lo;
+    }
+    constexpr int kRun = kCand / kWarpThreads;
+    const int i0 = tid * kRun;
+    double wv[kRun];
+    float vv[kRun + 1];
+    double mine = 0.0;
+#pragma unroll
+    for (int j = 0; j < kRun; ++j) {
+      const int i = i0 + j;
+      wv[j] = i < ns ? sh.w[i] : 0.0;
+      vv[j] = i < n ? key_value(sh.key[i]) : -INFINITY;
+      mine += wv[j];
+    }
+    vv[kRun] = i0 + kRun < n ? key_value(sh.key[i0 + kRun]) : -INFINITY;
+    double incl = mine;                               // inclusive scan of the lanes' sums
+    const int lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+      const double o = shfl_f64(incl, max(lane - off, 0));
+      if (lane >= off) incl += o;
+    }
+    if (lane == kWave - 1) sh.red.d[wave] = incl;
+    if (tid == 0) { sh.first_reach = 0x7fffffff; sh.near_any = 0; }
+    __syncthreads();
+    double base = incl - mine, surv_total = 0.0;
+    for (int w = 0; w < (int)(blockDim.x >> 6); ++w) {
+      const double tw = sh.red.d[w];
+      if (w < wave) base += tw;
+      surv_total += tw;
+    }
+    const double total = use_k ? surv_total : Z;
+    double run[kRun], fr[kRun];
+    bool gend[kRun];
+    {
+      double acc = base;
+#pragma unroll
+      for (int j = 0; j < kRun; ++j) {
+        const int i = i0 + j;
+        acc += wv[j];
+        run[j] = acc;
+        fr[j] = acc / total;
+        gend[j] = i < ns && (i == ns - 1 || vv[j + 1] != vv[j]);
+        if (use_p && gend[j] && fr[j] >= (double)top_p) atomicMin(&sh.first_reach, i);
+      }
+    }
+    __syncthreads();
+    int d = sh.first_reach;
+    bool ok = true;
+    if (use_p) {
+      // top-k survivors always reach P (their own mass is the total); a list
+      // without top-k may end before the row's mass does
+      if (d == 0x7fffffff) { d = ns - 1; ok = use_k; }
+    } else {
+      d = ns - 1;                                     // nothing to walk: all survivors are kept
+    }
+    if (ok) {
+#pragma unroll
+      for (int j = 0; j < kRun; ++j) {
+        const int i = i0 + j;
+        if (use_p && gend[j] && i <= d && fabs(fr[j] - (double)top_p) < kNearTie) atomicOr(&sh.near_any, 1);
+        if (i == d) {
+          sh.theta = use_p ? vv[j] : t_k;
+          sh.z_keep = run[j];
+        }
+      }
+    }
+    __syncthreads();
     if (tid == 0) {
-      float t_k = -INFINITY;
-      int ns = n;                                     // survivors of top-k: sorted entries 0..ns-1
-      double total = Z;
-      if (use_k) {
-        if (n >= top_k) {
-          t_k = key_value(sh.key[top_k - 1]);
-          ns = top_k;
-          while (ns < n && key_value(sh.key[ns]) == t_k) ++ns;
-        }
-        total = 0.0;
-        for (int i = 0; i < ns; ++i) total += sh.w[i];
-      }
-      float th = t_k;
-      int nk = ns;                                    // kept entries: sorted entries 0..nk-1
-      double kept = total;
-      bool ok = true;
-      int near = 0;
-      if (use_p) {
-        ok = false;
-        double run = 0.0;
-        int i = 0;
-        while (i < ns) {
-          const float v = key_value(sh.key[i]);
-          do { run += sh.w[i]; ++i; } while (i < ns && key_value(sh.key[i]) == v);
-          const double frac = run / total;
-          if (fabs(frac - (double)top_p) < kNearTie) near = 1;
-          if (frac >= (double)top_p) { th = v; nk = i; kept = run; ok = true; break; }
-        }
-        // top-k survivors always reach P (their own mass is the total); a list
-        // without top-k may end before the row's mass does
-        if (!ok && use_k) { th = key_value(sh.key[ns - 1]); nk = ns; kept = run; ok = true; }
-      } else if (!use_k) {
-        kept = 0.0;                                   // no warp at all (short rows): everything is kept
-        for (int i = 0; i < n; ++i) kept += sh.w[i];
-      }
-      while (nk > 0 && sh.w[nk - 1] == 0.0) --nk;     // masses that underflow fp64 are not listed
-      sh.theta = th;
+      int nk = d + 1;
+      while (ok && nk > 0 && sh.w[nk - 1] == 0.0) --nk;   // masses that underflow fp64 are not listed
       sh.settled = ok ? 1 : 0;
       sh.n_keep = ok ? nk : -1;
-      sh.z_keep = kept;
-      sh.near_tie = ok ? near : 0;
+      sh.near_tie = ok ? sh.near_any : 0;
     }
     __syncthreads();
     return sh.settled != 0;
@@ -523,31 +572,54 @@ __global__ __launch_bounds__(kWarpThreads) void warp_cutoffs_kernel(const void* 
   if (tid == 0) { sh.n_cand = 0; sh.near_tie = 0; sh.settled = 0; sh.n_keep = -1; sh.out_done = 0; }
   __syncthreads();
 
-  // ---- attempt 1 (tagged rows): only the lanes' largest vectors are read again
+  // ---- attempt 1 (tagged rows): only the lanes' largest vectors are read again.
+  // A lane whose fourth-largest vector may reach tau may hide a fifth one that
+  // does: such a lane (rare) walks all of its vectors again instead.
   if (tagged && V > kCand && (!use_k || top_k <= kWarpThreads)) {
-    const float tau = lane_max_of_rank(use_k ? top_k : kNucleusRank);
+    float tau = lane_max_of_rank(use_k ? top_k : kNucleusRank);
+    if (!use_k) {
+      // top-p alone: does the mass of the lane maxima above tau already reach P?  Then the
+      // list above tau certainly does; otherwise ask for a deeper list straight away.
+      if (tid < kWave) {
+        const uint32_t t16 = sh.tau_key >> 16;
+        double above = 0.0;
+#pragma unroll
+        for (int j = 0; j < kWarpThreads / kWave; ++j) {
+          const uint32_t k16 = sh.lane_key[tid + kWave * j];
+          // (the 16-bit key rounds an fp32 maximum down: the sum is a lower bound)
+          if (k16 >= t16 && k16 > (okey(-INFINITY) >> 16)) above += exp((double)from_okey(k16 << 16) * sc.inv_t - m_t);
+        }
+        above = wave_sum_f64(above);
+        if (tid == 0) sh.z_keep = above;
+      }
+      __syncthreads();
+      const bool deep = sh.z_keep < (double)top_p * Z * (1.0 + 1e-6);
+      __syncthreads();
+      if (deep) tau = lane_max_of_rank(kNucleusRank2);
+    }
     const uint32_t tau_key = sh.tau_key;
-    // a lane whose fourth-largest vector may reach tau may hide a fifth one that does
-    const int hidden = __syncthreads_or(top.k4 >= tau_key);
-    if (!hidden && tau > -INFINITY) {
+    if (tau > -INFINITY) {
       constexpr int EPV = Elem<DT>::per_vec;
       const u32x4* p = reinterpret_cast<const u32x4*>(row);
-      const uint32_t keys[3] = {top.k1, top.k2, top.k3};
+      auto list_vector = [&](uint32_t vec) {
+        float f[EPV];
+        unpack<DT>(p[vec], f);
 #pragma unroll
-      for (int q = 0; q < 3; ++q) {
-        if (keys[q] >= tau_key) {
-          const uint32_t vec = (keys[q] & 0xFFFFu) * kWarpThreads + (uint32_t)tid;
-          float f[EPV];
-          unpack<DT>(p[vec], f);
-#pragma unroll
-          for (int e = 0; e < EPV; ++e) {
-            if (f[e] >= tau && f[e] > -INFINITY) {
-              const int at = atomicAdd(&sh.n_cand, 1);
-              if (at < kCand)
-                sh.key[at] = ((uint64_t)okey(f[e]) << 32) | (uint64_t)(0xFFFFFFFFu - (vec * EPV + (uint32_t)e));
-            }
+        for (int e = 0; e < EPV; ++e) {
+          if (f[e] >= tau && f[e] > -INFINITY) {
+            const int at = atomicAdd(&sh.n_cand, 1);
+            if (at < kCand)
+              sh.key[at] = ((uint64_t)okey(f[e]) << 32) | (uint64_t)(0xFFFFFFFFu - (vec * EPV + (uint32_t)e));
           }
         }
+      };
+      if (top.k4 >= tau_key) {
+        for (uint32_t vec = (uint32_t)tid; vec < (uint32_t)(V / EPV); vec += kWarpThreads) list_vector(vec);
+      } else {
+        const uint32_t keys[3] = {top.k1, top.k2, top.k3};
+#pragma unroll
+        for (int q = 0; q < 3; ++q)
+          if (keys[q] >= tau_key) list_vector((keys[q] & 0xFFFFu) * kWarpThreads + (uint32_t)tid);
       }
       __syncthreads();
       settled = settle(tau);
