@@ -355,6 +355,18 @@ int sv_verify_sample_sparse(const int32_t* count_t, const int32_t* token_t, cons
                             float* ratio_or_null, sv_stream_t stream);
 
 /*
+ * sv_accept_ratio on compacted supports: X = P_t(x) / P_d(x) of every drafted
+ * position under the warped distributions (profile construction with the sampling
+ * hyper-parameters in force).  Target supports: t_rows_per_seq (k or k+1) rows per
+ * sequence.  NaN with SV_FLAG_BAD_ROW / SV_FLAG_BAD_TOKEN / SV_FLAG_NOT_COMPACT where
+ * the ratio is not available; +inf where the draft gives the token no mass.
+ */
+int sv_accept_ratio_sparse(const int32_t* count_t, const int32_t* token_t, const double* prob_t,
+                           int t_rows_per_seq, const int32_t* count_d, const int32_t* token_d,
+                           const double* prob_d, int cap, const int32_t* x, int B, int k, int V,
+                           float* ratio, uint32_t* flags_or_null, sv_stream_t stream);
+
+/*
  * The uniforms sv_verify_sample draws (for tests and for callers that want to
  * replay a step): Philox-4x32-10 with counter (i, b, 0, step) and key (seed low,
  * seed high); output word 0 -> accept uniform of drafted position i, word 1 ->

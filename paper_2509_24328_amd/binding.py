@@ -29,7 +29,8 @@ EXPORTS = ("sv_strerror", "sv_workspace_bytes", "sv_row_stats", "sv_accept_estim
            "sv_select_length", "sv_verify_sample", "sv_set_timing_events", "sv_accept_ratio",
            "sv_quantile_edges", "sv_profile_accumulate", "sv_profile_finalize", "sv_warp_cutoffs",
            "sv_row_stats_warped", "sv_verify_sample_warped",
-           "sv_warp_compact", "sv_row_stats_sparse", "sv_verify_sample_sparse", "sv_uniforms")
+           "sv_warp_compact", "sv_row_stats_sparse", "sv_verify_sample_sparse", "sv_uniforms",
+           "sv_accept_ratio_sparse")
 (SV_KERNEL_ROW_STATS, SV_KERNEL_ACCEPT_ESTIMATE, SV_KERNEL_SELECT_LENGTH, SV_KERNEL_VERIFY_ROWS,
  SV_KERNEL_VERIFY_ACCEPT, SV_KERNEL_VERIFY_MASS, SV_KERNEL_VERIFY_PICK, SV_KERNEL_COUNT) = range(8)
 
@@ -78,6 +79,8 @@ lib.sv_row_stats_sparse.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, 
 lib.sv_verify_sample_sparse.restype = _i
 lib.sv_verify_sample_sparse.argtypes = [_vp, _vp, _vp, _vp, _i, _vp, _vp, _vp, _i, _vp, _vp, _i, _i, _i,
                                         ctypes.c_uint64, ctypes.c_uint32, _vp, _vp, _vp, _vp, _vp]
+lib.sv_accept_ratio_sparse.restype = _i
+lib.sv_accept_ratio_sparse.argtypes = [_vp, _vp, _vp, _i, _vp, _vp, _vp, _i, _vp, _i, _i, _i, _vp, _vp, _vp]
 lib.sv_uniforms.restype = _i
 lib.sv_uniforms.argtypes = [ctypes.c_uint64, ctypes.c_uint32, _i, _i, _vp, _vp, _vp]
 lib.sv_set_timing_events.restype = _i
@@ -267,3 +270,12 @@ def sv_verify_sample_sparse(sup_t, t_offsets, sup_d, x, gamma, V, seed, step, ou
 def sv_uniforms(seed, step, u_accept, u_sample, stream=None):
     B, n_pos = u_accept.shape
     _check(lib.sv_uniforms(seed, step, B, n_pos, _ptr(u_accept), _ptr(u_sample), _stream(stream)))
+
+
+def sv_accept_ratio_sparse(sup_t, sup_d, x, V, ratio, flags=None, stream=None):
+    B, k = x.shape
+    if sup_t.cap != sup_d.cap or sup_d.rows != B * k or sup_t.rows % B != 0 or sup_t.rows // B not in (k, k + 1):
+        raise SvError(SV_ERR_INVALID_ARG)
+    _check(lib.sv_accept_ratio_sparse(_ptr(sup_t.count), _ptr(sup_t.token), _ptr(sup_t.prob), sup_t.rows // B,
+                                      _ptr(sup_d.count), _ptr(sup_d.token), _ptr(sup_d.prob), sup_t.cap, _ptr(x),
+                                      B, k, V, _ptr(ratio), _ptr(flags), _stream(stream)))

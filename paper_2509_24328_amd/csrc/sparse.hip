@@ -238,6 +238,25 @@ __global__ __launch_bounds__(kWave) void verify_sample_sparse_kernel(SparseVerif
   }
 }
 
+// one lane per (sequence, position): p_t(x) / p_d(x) of every drafted position (profile
+// construction: no early stop, no sampling)
+__global__ void accept_ratio_sparse_kernel(Supports t, Supports d, int t_rows_per_seq, const int32_t* x, int B,
+                                           int k, int V, float* ratio, uint32_t* flags) {
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= B * k) return;
+  const int b = j / k, i = j - b * k;
+  const long trow = (long)b * t_rows_per_seq + i, drow = j;
+  const int tok = x[j], nt = t.count[trow], nd = d.count[drow];
+  uint32_t fl = 0;
+  double rho = __builtin_nan("");
+  if (tok < 0 || tok >= V) fl |= SV_FLAG_BAD_TOKEN;
+  else if (nt < 0 || nd < 0) fl |= SV_FLAG_NOT_COMPACT;
+  else if (nt == 0 || nd == 0) fl |= SV_FLAG_BAD_ROW;
+  else rho = support_prob(t, trow, nt, tok) / support_prob(d, drow, nd, tok);
+  ratio[j] = (float)rho;
+  if (flags) flags[j] = fl;
+}
+
 }  // namespace sv
 
 extern "C" int sv_row_stats_sparse(const int32_t* count_d, const int32_t* token_d, const double* prob_d,
@@ -297,5 +316,26 @@ extern "C" int sv_verify_sample_sparse(const int32_t* count_t, const int32_t* to
   a.seed_lo = (uint32_t)(seed & 0xffffffffu); a.seed_hi = (uint32_t)(seed >> 32); a.step = step;
   a.out_tokens = out_tokens; a.n_accept = n_accept; a.flags = flags; a.ratio = ratio_or_null;
   hipLaunchKernelGGL(verify_sample_sparse_kernel, dim3(B), dim3(kWave), 0, as_stream(stream), a);
+  return launch_status();
+}
+
+extern "C" int sv_accept_ratio_sparse(const int32_t* count_t, const int32_t* token_t, const double* prob_t,
+                                      int t_rows_per_seq, const int32_t* count_d, const int32_t* token_d,
+                                      const double* prob_d, int cap, const int32_t* x, int B, int k, int V,
+                                      float* ratio, uint32_t* flags_or_null, sv_stream_t stream) {
+  using namespace sv;
+  SV_REQUIRE(B >= 0 && k >= 1 && V >= 1 && cap >= 1 && cap <= SV_SUPPORT_MAX_CAP, SV_ERR_INVALID_ARG);
+  SV_REQUIRE(t_rows_per_seq == k || t_rows_per_seq == k + 1, SV_ERR_INVALID_ARG);
+  SV_REQUIRE((long long)B * (k + 1) <= 0x7fffffffLL, SV_ERR_TOO_LARGE);
+  if (B == 0) return SV_OK;
+  SV_REQUIRE(count_t && token_t && prob_t && count_d && token_d && prob_d && x && ratio, SV_ERR_NULL);
+  SV_REQUIRE(is_aligned(count_t, 4) && is_aligned(token_t, 4) && is_aligned(prob_t, 8) && is_aligned(count_d, 4) &&
+                 is_aligned(token_d, 4) && is_aligned(prob_d, 8) && is_aligned(x, 4) && is_aligned(ratio, 4) &&
+                 is_aligned(flags_or_null, 4),
+             SV_ERR_ALIGN);
+  const int n = B * k, threads = 256;
+  hipLaunchKernelGGL(accept_ratio_sparse_kernel, dim3((n + threads - 1) / threads), dim3(threads), 0,
+                     as_stream(stream), Supports{count_t, token_t, prob_t, cap}, Supports{count_d, token_d, prob_d, cap},
+                     t_rows_per_seq, x, B, k, V, ratio, flags_or_null);
   return launch_status();
 }

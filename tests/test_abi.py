@@ -193,3 +193,15 @@ def test_uniforms_argument_errors():
     assert L.sv_uniforms(1, 0, 4, 4, None, p, None) == Bd.SV_ERR_NULL
     assert L.sv_uniforms(1, 0, 4, 4, ctypes.c_void_p(256 * 1024 + 4), p, None) == Bd.SV_ERR_ALIGN
     assert L.sv_uniforms(1, 0, 0, 4, None, None, None) == Bd.SV_OK
+
+
+def test_accept_ratio_sparse_argument_errors():
+    L = Bd.lib
+    p = ctypes.c_void_p(256 * 1024)
+    call = lambda **kw: L.sv_accept_ratio_sparse(p, p, p, kw.get("tr", 3), p, p, p, kw.get("cap", 64), kw.get("x", p),
+                                                 kw.get("B", 2), 2, 100, kw.get("ratio", p), None, None)
+    assert call(tr=5) == Bd.SV_ERR_INVALID_ARG
+    assert call(cap=0) == Bd.SV_ERR_INVALID_ARG
+    assert call(x=None) == Bd.SV_ERR_NULL
+    assert call(ratio=ctypes.c_void_p(256 * 1024 + 2)) == Bd.SV_ERR_ALIGN
+    assert call(B=0) == Bd.SV_OK

@@ -305,3 +305,30 @@ def test_sparse_step_end_to_end_against_dense_warped_path():
         assert np.array_equal(d["tokens"][ok], s["tokens"][ok])
     else:
         pytest.skip("estimates fell on different sides of a bin edge")
+
+
+def test_accept_ratio_sparse_matches_oracle():
+    """X = P_t(x) / P_d(x) of every drafted position under the warped distributions
+    (profile construction), against the oracle's ratio on warped rows."""
+    from oracle import profile_oracle as PO
+    P = H.sv()
+    for (idx, B, k, V, dtype), (T, K, Pp) in zip(CASES, SERIES + [(1.3, 50, 0.95)]):
+        T = _t32(T)
+        cfg = svgen.make_config(idx, seed=270 + idx, B=B, k=k, V=V, dtype=dtype, device="cuda")
+        inp = H.oracle_inputs(cfg)
+        y_t, _, f_t = W.warp_rows(inp["z_t"], T, K, Pp)
+        y_d, _, f_d = W.warp_rows(inp["z_d"], T, K, Pp)
+        sup_t, gf_t = _supports_for(cfg["z_t"], T, K, Pp, 256)
+        sup_d, gf_d = _supports_for(cfg["z_d"], T, K, Pp, 256)
+        for redraw in (False, True):
+            x = _redraw_tokens(y_d, 11) if redraw else inp["x"]
+            ref, _ = PO.accept_probability_ratio(y_t, y_d, x)
+            ratio = torch.full((B, k), -5.0, dtype=torch.float32, device="cuda")
+            flags = torch.full((B, k), 77, dtype=torch.int32, device="cuda")
+            P.sv_accept_ratio_sparse(sup_t, sup_d, H.dev(x, torch.int32), V, ratio, flags)
+            torch.cuda.synchronize()
+            got, fl = ratio.cpu().numpy(), flags.cpu().numpy().astype(np.uint32)
+            tie = ((f_t[:, :k] | f_d | gf_t.reshape(B, k + 1)[:, :k] | gf_d.reshape(B, k)) & O.FLAG_NEAR_TIE) != 0
+            ok = ~tie & (fl == 0)
+            assert ok.sum() >= B * k // 2
+            assert H.close(got[ok], np.asarray(ref)[ok], H.REL, 1e-30).all(), (got[ok], np.asarray(ref)[ok])
