@@ -29,6 +29,12 @@
 #include "sv_device.hpp"
 #include "sv_host.hpp"
 
+// Phase marks: empty in the library; a profiling build may define
+// SV_PHASE_MARK(n) to record a clock at the boundaries of the kernel's phases.
+#ifndef SV_PHASE_MARK
+#define SV_PHASE_MARK(n)
+#endif
+
 namespace sv {
 
 constexpr int kWarpThreads = 512;
@@ -305,6 +311,39 @@ __device__ __forceinline__ uint64_t wave_sort_desc(uint64_t key) {
   return key;
 }
 
+// Descending sort of keys[0..n), n <= 512 distinct non-zero keys, by a 512-lane
+// workgroup: every wavefront sorts 64 keys with shuffles, then every key finds its
+// rank by counting the larger keys of the other seven runs (binary searches in
+// lock-step, so that their LDS reads overlap).  tmp: n further slots.  keys[n..512)
+// end up zero.  Far fewer barriers than a bitonic network in LDS.
+__device__ __forceinline__ void sort_desc_runs(uint64_t* keys, uint64_t* tmp, int n) {
+  constexpr int kRuns = kWarpThreads / kWave;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  uint64_t key = tid < n ? keys[tid] : 0;
+  key = wave_sort_desc(key);
+  __syncthreads();                                     // all keys read before any is overwritten
+  keys[tid] = key;
+  __syncthreads();
+  int pos[kRuns];
+#pragma unroll
+  for (int r = 0; r < kRuns; ++r) pos[r] = 0;
+  for (int step = kWave; step > 0; step >>= 1) {
+#pragma unroll
+    for (int r = 0; r < kRuns; ++r) {
+      const int probe = pos[r] + step;
+      if (r != wave && probe <= kWave && keys[r * kWave + probe - 1] > key) pos[r] = probe;
+    }
+  }
+  int rank = lane;
+#pragma unroll
+  for (int r = 0; r < kRuns; ++r) rank += (r != wave) ? pos[r] : 0;
+  if (key != 0) tmp[rank] = key;
+  __syncthreads();
+  keys[tid] = tid < n ? tmp[tid] : 0;
+  __syncthreads();
+}
+
+
 // top-p alone has no K and guesses the depth of the nucleus from the lane maxima: a
 // list of about rank + rank^2 / 1024 entries, short enough for the one-wavefront
 // settle when the largest 48 lane maxima already carry P of the row's mass, a deeper
@@ -323,6 +362,7 @@ __global__ __launch_bounds__(kWarpThreads) void warp_cutoffs_kernel(const void* 
   const float lt = sc.L;
 
   // sweep 1: maximum, normaliser, bad-row detection (NaN poisons the sum, +inf the maximum)
+  SV_PHASE_MARK(0)
   Online acc[1];
   acc[0].init();
   Top4 top;
@@ -333,6 +373,7 @@ __global__ __launch_bounds__(kWarpThreads) void warp_cutoffs_kernel(const void* 
   MS merged[1];
   block_merge<1>(acc, sh.mg, merged, lt);
   const float m = merged[0].m;
+  SV_PHASE_MARK(1)
   const double lse_row = lse_from_ms(merged[0], sc);   // of z / T over the whole row; NaN: bad row
   if (isnan(lse_row)) {
     if (tid == 0) {
@@ -469,14 +510,20 @@ __global__ __launch_bounds__(kWarpThreads) void warp_cutoffs_kernel(const void* 
     // fewer than K candidates happens only when tau = -inf lists every finite entry
     // of the row (masked vocabularies): top-k then keeps them all
     if (!(n <= kCand && (!use_k || n >= top_k || tau == -INFINITY))) return false;
-    int n2 = 64;
-    while (n2 < n) n2 <<= 1;
-    for (int i = n + tid; i < n2; i += blockDim.x) sh.key[i] = 0;      // below every real key
-    __syncthreads();
-    sort_desc(sh.key, n2);
+    if (n <= kWarpThreads) {
+      sort_desc_runs(sh.key, reinterpret_cast<uint64_t*>(sh.w), n);    // (the masses are not there yet)
+    } else {
+      int n2 = kWarpThreads;
+      while (n2 < n) n2 <<= 1;
+      for (int i = n + tid; i < n2; i += blockDim.x) sh.key[i] = 0;    // below every real key
+      __syncthreads();
+      sort_desc(sh.key, n2);
+    }
+    SV_PHASE_MARK(4)
     for (int i = tid; i < n; i += blockDim.x)
       sh.w[i] = exp((double)key_value(sh.key[i]) * sc.inv_t - m_t);
     __syncthreads();
+    SV_PHASE_MARK(5)
     // Every lane owns a run of consecutive sorted entries; the masses of the
     // survivors are prefix-summed over the workgroup (fp64), then every lane looks
     // at the ends of groups of equal value inside its run.
@@ -597,6 +644,7 @@ __global__ __launch_bounds__(kWarpThreads) void warp_cutoffs_kernel(const void* 
       __syncthreads();
       if (deep) tau = lane_max_of_rank(kNucleusRank2);
     }
+    SV_PHASE_MARK(2)
     const uint32_t tau_key = sh.tau_key;
     if (tau > -INFINITY) {
       constexpr int EPV = Elem<DT>::per_vec;
@@ -622,7 +670,9 @@ __global__ __launch_bounds__(kWarpThreads) void warp_cutoffs_kernel(const void* 
           if (keys[q] >= tau_key) list_vector((keys[q] & 0xFFFFu) * kWarpThreads + (uint32_t)tid);
       }
       __syncthreads();
+      SV_PHASE_MARK(3)
       settled = settle(tau);
+      SV_PHASE_MARK(6)
     }
   }
 
@@ -662,18 +712,19 @@ __global__ __launch_bounds__(kWarpThreads) void warp_cutoffs_kernel(const void* 
     return;
   }
   const double z_keep = sh.z_keep;
-  int n2 = 64;
-  while (n2 < nk) n2 <<= 1;
   __syncthreads();
   // re-key the kept entries by token id (ascending = descending complement); the position
   // in the value order rides along.  Every slot is rewritten by the thread that read it.
+  int n2 = kWarpThreads;
+  while (n2 < nk) n2 <<= 1;
   for (int i = tid; i < n2; i += blockDim.x) {
     uint64_t key = 0;
     if (i < nk) key = ((uint64_t)(0xFFFFFFFFu - key_token(sh.key[i])) << 32) | (uint64_t)i;
     sh.key[i] = key;
   }
   __syncthreads();
-  sort_desc(sh.key, n2);
+  if (nk <= kWarpThreads) sort_desc_runs(sh.key, sh.key + kCand / 2, nk);   // (the list beyond nk is dead)
+  else sort_desc(sh.key, n2);
   for (int i = tid; i < nk; i += blockDim.x) {
     const uint64_t key = sh.key[i];
     const size_t at = (size_t)r * out.cap + i;
@@ -684,6 +735,7 @@ __global__ __launch_bounds__(kWarpThreads) void warp_cutoffs_kernel(const void* 
     out.count[r] = nk;
     out.lse[r] = (float)(m_t + log(z_keep));
   }
+  SV_PHASE_MARK(7)
 }
 
 }  // namespace sv
