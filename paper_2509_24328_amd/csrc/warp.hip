@@ -295,12 +295,12 @@ __device__ __forceinline__ double shfl_f64(double v, int src) {
   return __hiloint2double(hi, lo);
 }
 
-// Descending bitonic sort of one 64-bit key per lane inside a wavefront.
-__device__ __forceinline__ uint64_t wave_sort_desc(uint64_t key) {
+// Descending bitonic sort of one 64-bit key per lane inside a wavefront: the first n2
+// lanes (a power of two) are sorted among themselves, which is all that is needed
+// when the other lanes hold zeros.
+__device__ __forceinline__ uint64_t wave_sort_desc(uint64_t key, int n2 = kWave) {
   const int lane = threadIdx.x & 63;
-#pragma unroll
-  for (int k2 = 2; k2 <= kWave; k2 <<= 1) {
-#pragma unroll
+  for (int k2 = 2; k2 <= n2; k2 <<= 1) {
     for (int j = k2 >> 1; j > 0; j >>= 1) {
       const uint64_t other = shfl_u64(key, lane ^ j);
       const bool desc = (lane & k2) == 0, lower = (lane & j) == 0;
@@ -427,7 +427,9 @@ __global__ __launch_bounds__(kWarpThreads) void warp_cutoffs_kernel(const void* 
   auto settle_wave = [&](int n, float tau) {
     const int lane = tid;                                // wavefront 0: tid = lane
     uint64_t key = lane < n ? sh.key[lane] : 0;
-    key = wave_sort_desc(key);
+    int n2 = 2;
+    while (n2 < n) n2 <<= 1;
+    key = wave_sort_desc(key, n2);
     const bool valid = lane < n;
     const float v = valid ? key_value(key) : -INFINITY;
     const double w = valid ? exp((double)v * sc.inv_t - m_t) : 0.0;
@@ -474,7 +476,9 @@ __global__ __launch_bounds__(kWarpThreads) void warp_cutoffs_kernel(const void* 
       if (nk <= out.cap) {
         // order the kept entries by token id and write them out
         uint64_t k2 = lane < nk ? (((uint64_t)(0xFFFFFFFFu - key_token(key)) << 32) | (uint64_t)lane) : 0;
-        k2 = wave_sort_desc(k2);
+        int m2 = 2;
+        while (m2 < nk) m2 <<= 1;
+        k2 = wave_sort_desc(k2, m2);
         const double wj = shfl_f64(w, (int)(uint32_t)k2 & 63);
         if (lane < nk) {
           const size_t at = (size_t)r * out.cap + lane;
