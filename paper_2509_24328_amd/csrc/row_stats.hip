@@ -255,7 +255,7 @@ __global__ __launch_bounds__(kStashThreads) void row_stats_stash_kernel(StatsArg
     const int i = tid + j * nt;
     sd[j] = neg;
     sc[j] = neg;
-    if (i < nvec) { sd[j] = pd[i]; sc[j] = pc[i]; }
+    if (i < nvec) { sd[j] = __builtin_nontemporal_load(pd + i); sc[j] = __builtin_nontemporal_load(pc + i); }
   }
   // the LDS share goes straight from memory into LDS (no registers in between)
   // and lands while the register share is being accumulated
@@ -330,7 +330,8 @@ __global__ __launch_bounds__(kStashThreads) void row_stats_stash_kernel(StatsArg
       int r = tid;
       for (; r + nt < n_rest; r += 2 * nt) {
         const int i0 = nvec - 1 - r, i1 = nvec - 1 - (r + nt);
-        const u32x4 d0 = pd[i0], c0 = pc[i0], d1 = pd[i1], c1 = pc[i1];
+        const u32x4 d0 = __builtin_nontemporal_load(pd + i0), c0 = __builtin_nontemporal_load(pc + i0),
+                    d1 = __builtin_nontemporal_load(pd + i1), c1 = __builtin_nontemporal_load(pc + i1);
         acc.template add_vec<DT>(d0, c0);
         __builtin_amdgcn_sched_barrier(0);
         acc.template add_vec<DT>(d1, c1);
