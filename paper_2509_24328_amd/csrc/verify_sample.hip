@@ -486,11 +486,12 @@ __global__ __launch_bounds__(kSampleThreads) void verify_pick_kernel(VerifyArgs 
 }
 
 // Workgroups per row: enough of them to spread the rows evenly over the CUs
-// (1088 rows on 256 CUs leave some CUs a fifth more work than others), but
-// never parts shorter than 8192 entries.
+// (1088 rows on 256 CUs leave some CUs a fifth more work than others) and to keep
+// small batches from leaving CUs idle, but never parts shorter than 4096 entries.
+// Measured at the five workloads: flat within 2 % from 3 to 8 workgroups per row.
 static int rows_split(int rows, int V) {
-  int s = (4096 + rows - 1) / rows;
-  s = std::min(s, std::max(1, V / 8192));
+  int s = (8192 + rows - 1) / rows;
+  s = std::min(s, std::max(1, V / 4096));
   return std::max(1, std::min(s, kMaxSplit));
 }
 
