@@ -31,6 +31,12 @@
 #include "sv_device.hpp"
 #include "sv_host.hpp"
 
+// Phase marks: empty in the library; a profiling build may define
+// SV_PHASE_MARK(n) to record a clock at the boundaries of a kernel's phases.
+#ifndef SV_PHASE_MARK
+#define SV_PHASE_MARK(n)
+#endif
+
 namespace sv {
 
 constexpr int kRowsThreads = 256;
@@ -347,6 +353,7 @@ static_assert(sizeof(double) * 2 * kMaxChunks <= sizeof(float) * (kChunk + kChun
 template <int DT, bool CUT>
 __global__ __launch_bounds__(kSampleThreads) void verify_pick_kernel(VerifyArgs a, int C) {
   __shared__ PickShared sh;
+  SV_PHASE_MARK(0)
   const int b = blockIdx.x;
   const int tid = threadIdx.x;
   const int k = a.k, V = a.V;
@@ -367,6 +374,7 @@ __global__ __launch_bounds__(kSampleThreads) void verify_pick_kernel(VerifyArgs 
     sh.mass[C + j] = a.ws.mass_t[(size_t)b * C + j];
   }
   __syncthreads();
+  SV_PHASE_MARK(1)
   if (tid == 0) {
     uint32_t flags = pl.flags;
     const double* mr = sh.mass;
@@ -403,6 +411,7 @@ __global__ __launch_bounds__(kSampleThreads) void verify_pick_kernel(VerifyArgs 
     sh.found_thread = kSampleThreads;
   }
   __syncthreads();
+  SV_PHASE_MARK(2)
   const int chunk = sh.chunk;
   const int use_resid = sh.use_resid;
   int32_t* out = a.out_tokens + (size_t)b * (k + 1);
@@ -427,6 +436,7 @@ __global__ __launch_bounds__(kSampleThreads) void verify_pick_kernel(VerifyArgs 
     });
   }
   __syncthreads();
+  SV_PHASE_MARK(3)
 
   // block prefix scan over contiguous per-thread segments (fp64)
   static_assert(kSeg == 32, "skew() pads once per 32-entry segment");
@@ -456,6 +466,7 @@ __global__ __launch_bounds__(kSampleThreads) void verify_pick_kernel(VerifyArgs 
   // between the two passes put the threshold at or beyond the chunk total
   if (incl > tau_local) atomicMin(&sh.found_thread, tid);
   __syncthreads();
+  SV_PHASE_MARK(4)
   int owner = sh.found_thread;
   const bool beyond = owner >= kSampleThreads;
   if (beyond) owner = kSampleThreads - 1;
@@ -483,6 +494,7 @@ __global__ __launch_bounds__(kSampleThreads) void verify_pick_kernel(VerifyArgs 
   }
   if (y >= 0) out[n] = w0 + y; else fl |= SV_FLAG_BAD_ROW;   // y < 0: the chunk holds no mass at all
   a.flags[b] = fl;
+  SV_PHASE_MARK(5)
 }
 
 // Workgroups per row: enough of them to spread the rows evenly over the CUs
