@@ -87,3 +87,80 @@ def test_full_config5_ragged_chain():
     got_dense = H.gpu_verify(d["z_t"], d["z_d"], d["x"], gamma=rg, seed=5, step=2)
     assert np.array_equal(got_dense["tokens"], got["tokens"])
     assert np.array_equal(got_dense["n_accept"], got["n_accept"])
+
+
+def test_full_config_warped_compacted_ragged():
+    """Config 5 at full size with sampling warps on compacted supports: lengths from
+    sv_select_length, target supports compacted from the packed target rows.  Every
+    sequence is compared with the dense warped entry points (checked against the
+    oracle elsewhere), and a sample of sequences with the oracle itself."""
+    from oracle import warp_oracle as W
+    P = H.sv()
+    cfg = svgen.make_config(4, device="cuda")
+    B, k, V = cfg["B"], cfg["k"], cfg["V"]
+    T, K, Pp, cap = float(np.float32(0.7)), 20, 0.8, 64
+    f32 = lambda *s: torch.empty(s, dtype=torch.float32, device="cuda")
+    i32 = lambda *s: torch.empty(s, dtype=torch.int32, device="cuda")
+    sup_d, sup_c = P.Supports(B * k, cap), P.Supports(B * k, cap)
+    cut_d, cut_c = f32(B * k), f32(B * k)
+    wf_d, wf_c = i32(B * k), i32(B * k)
+    P.sv_warp_compact(cfg["z_d"], T, K, Pp, sup_d, cut_d, wf_d)
+    P.sv_warp_compact(cfg["z_c"], T, K, Pp, sup_c, cut_c, wf_c)
+    lse_d, lse_c, S, A, p_hat = (f32(B, k) for _ in range(5))
+    P.sv_row_stats_sparse(sup_d, sup_c, cfg["x"], V, lse_d, lse_c, S, A)
+    edges_s, edges_a, table = svgen.profile_table(10, 10)
+    lat = H.dev(svgen.latency_table(B * k), torch.float32)
+    gamma, offs, total = i32(B), i32(B + 1), i32(1)
+    P.sv_accept_estimate(S, A, H.dev(edges_s), H.dev(edges_a), H.dev(table), p_hat, None)
+    P.sv_select_length(p_hat, lat, P.SV_BATCH_GREEDY, gamma, offs, total)
+    torch.cuda.synchronize()
+    g = gamma.cpu().numpy()
+    o = offs.cpu().numpy()
+    assert (sup_d.count.cpu().numpy() > 0).all() and int(total.item()) == int(g.sum())
+    # pack the target rows of the selected positions plus the bonus row
+    z_tp = torch.cat([cfg["z_t"][b, :g[b] + 1] for b in range(B)], dim=0).contiguous()
+    rows_t = z_tp.shape[0]
+    assert rows_t == o[-1]
+    sup_t, cut_t, wf_t = P.Supports(rows_t, cap), f32(rows_t), i32(rows_t)
+    P.sv_warp_compact(z_tp, T, K, Pp, sup_t, cut_t, wf_t)
+    res = {}
+    ws = P.alloc_workspace(B, k, V, P.SV_BF16)
+    for mode in ("sparse", "dense"):
+        tokens, n_acc, flags, ratio = i32(B, k + 1), i32(B), i32(B), f32(B, k)
+        if mode == "sparse":
+            P.sv_verify_sample_sparse(sup_t, offs, sup_d, cfg["x"], gamma, V, 9, 2, tokens, n_acc, flags, ratio)
+        else:
+            P.sv_verify_sample_warped(z_tp, offs, cfg["z_d"], cfg["x"], gamma, T, cut_t, T, cut_d, 9, 2, tokens, n_acc,
+                                      flags, ratio, ws)
+        torch.cuda.synchronize()
+        res[mode] = dict(tokens=tokens.cpu().numpy(), n_accept=n_acc.cpu().numpy(),
+                         flags=flags.cpu().numpy().astype(np.uint32), ratio=ratio.cpu().numpy())
+    s, d = res["sparse"], res["dense"]
+    assert not (s["flags"] & 32).any()
+    near = ((s["flags"] | d["flags"]) & (O.FLAG_NEAR_TIE | O.FLAG_NEAR_CDF_EDGE)) != 0
+    ok = ~near
+    assert np.array_equal(s["n_accept"][ok], d["n_accept"][ok]) and np.array_equal(s["tokens"][ok], d["tokens"][ok])
+    assert near.sum() <= 3
+    # the oracle on a sample of sequences (their own rows only)
+    zt_bits, zd_bits = svgen.to_numpy_bits(z_tp), svgen.to_numpy_bits(cfg["z_d"])
+    x = cfg["x"].cpu().numpy()
+    wt, wd = wf_t.cpu().numpy().astype(np.uint32), wf_d.cpu().numpy().astype(np.uint32).reshape(B, k)
+    checked = 0
+    for b in (0, 7, 21, 40, 63):
+        rows = slice(o[b], o[b + 1])
+        y_t, _, f_t = W.warp_rows(zt_bits[rows], T, K, Pp)
+        y_d, _, f_d = W.warp_rows(zd_bits[b:b + 1], T, K, Pp)
+        if ((f_t | wt[rows]) & O.FLAG_NEAR_TIE).any() or ((f_d[0] | wd[b]) & O.FLAG_NEAR_TIE).any():
+            continue
+        # the oracle addresses its uniforms by the sequence index: hand it those of sequence b
+        from oracle import philox as OP
+        ua, _ = OP.sv_uniforms(9, 2, np.full((1, k), b), np.arange(k)[None, :])
+        _, us_full = OP.sv_uniforms(9, 2, np.full((1, k + 1), b), np.arange(k + 1)[None, :])
+        ref = O.verify_sample(y_t, y_d, x[b:b + 1], gamma=g[b:b + 1], t_offsets=np.array([0, g[b] + 1], np.int32),
+                              uniforms=(ua, us_full))
+        got = {n: v[b:b + 1] for n, v in s.items()}
+        H.assert_verify(got, ref, k)
+        checked += 1
+    assert checked >= 3
+    print(f"\n  cfg5 warped, compacted: mean gamma {g.mean():.2f}, near flags {int(near.sum())}, "
+          f"oracle-checked sequences {checked}", flush=True)
