@@ -251,7 +251,7 @@ int sv_profile_finalize(const uint32_t* counts, const double* sum_x, int n_s, in
  *   cutoff  [rows] float       out  a value of the row, -inf, or NaN for a bad row
  *   flags_or_null [rows] uint32 out SV_FLAG_BAD_ROW; SV_FLAG_NEAR_TIE when the top-p
  *                                   decision lies within 3e-6 of top_p
- * temperature > 0, top_p > 0.
+ * temperature in [1e-3, 1e3], top_p > 0; otherwise SV_ERR_INVALID_ARG.
  */
 int sv_warp_cutoffs(const void* z, int rows, int V, int dtype,
                     float temperature, int top_k, float top_p,
