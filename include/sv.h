@@ -66,7 +66,7 @@ enum {
 };
 
 /* Largest B*k accepted by sv_select_length (keys are sorted in one workgroup). */
-#define SV_SELECT_MAX_KEYS 4096
+#define SV_SELECT_MAX_KEYS 8192
 /* Largest k accepted by sv_verify_sample. */
 #define SV_MAX_K 64
 /* Largest per-row capacity of a compacted support (sv_warp_compact). */

@@ -22,7 +22,7 @@ SV_ERR_WORKSPACE, SV_ERR_LAUNCH, SV_ERR_TOO_LARGE = -5, -6, -7
 FLAG_BAD_ROW, FLAG_NEAR_TIE, FLAG_RESIDUAL_FALLBACK, FLAG_NEAR_CDF_EDGE, FLAG_BAD_TOKEN = 1, 2, 4, 8, 16
 FLAG_NOT_COMPACT = 32
 SV_SUPPORT_MAX_CAP = 1024
-SV_SELECT_MAX_KEYS = 4096
+SV_SELECT_MAX_KEYS = 8192
 SV_MAX_K = 64
 
 EXPORTS = ("sv_strerror", "sv_workspace_bytes", "sv_row_stats", "sv_accept_estimate",

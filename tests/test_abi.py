@@ -72,7 +72,7 @@ def test_argument_errors_are_reported_before_any_launch():
                                          kw.get("nl", 17), kw.get("mode", 0), p, p, p, None)
     assert sl(mode=2) == Bd.SV_ERR_INVALID_ARG
     assert sl(nl=16) == Bd.SV_ERR_INVALID_ARG
-    assert sl(B=4097, k=1, nl=5000) == Bd.SV_ERR_TOO_LARGE
+    assert sl(B=Bd.SV_SELECT_MAX_KEYS + 1, k=1, nl=10000) == Bd.SV_ERR_TOO_LARGE
     assert sl(p=None) == Bd.SV_ERR_NULL
 
 

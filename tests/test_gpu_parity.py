@@ -92,7 +92,8 @@ def test_accept_estimate_exact():
         assert np.array_equal(got_f, ref_f)
 
 
-@pytest.mark.parametrize("B,k", [(1, 4), (8, 8), (64, 8), (64, 16), (3, 5), (4096, 1), (1, 64), (37, 11)])
+@pytest.mark.parametrize("B,k", [(1, 4), (8, 8), (64, 8), (64, 16), (3, 5), (4096, 1), (1, 64), (37, 11), (512, 16), (300, 20),
+                                 (8192, 1)])
 def test_select_length_exact(B, k):
     rng = np.random.default_rng(B * 100 + k)
     for trial in range(3):
