@@ -7,10 +7,14 @@
 // "with the highest increase in expected acceptance length" is always the
 // largest not-yet-taken c.  Because c is non-increasing along a sequence,
 // sorting all (b,j) by (c descending, b, j ascending) reproduces the greedy
-// order.  One workgroup: products (one lane per sequence), bitonic sort in LDS,
-// the running sum E_M in exactly that order (one lane, fp64, so that the
-// integer outputs do not depend on a reduction tree), goodput and first-peak
-// search in parallel, then counts and offsets.  Launch-latency bound.
+// order.  One workgroup: products (one lane per sequence); pairwise merging of
+// the per-sequence lists in LDS (they are sorted already); the running sum E_M
+// is defined in exactly that order (fp64, one addition after another, so that
+// the integer outputs do not depend on a reduction tree) - a parallel scan with
+// an error bound decides every comparison that is not a near tie, one lane
+// re-sums in order otherwise; goodput and first-peak search in parallel; counts
+// and offsets.  Launch-latency bound at the paper's batch sizes (12 us at 512
+// keys; 55 us at 4096, 120 us at 8192).
 #include "sv_device.hpp"
 #include "sv_host.hpp"
 
@@ -24,16 +28,11 @@ namespace sv {
 
 constexpr int kSelThreads = 1024;
 constexpr int kSelMax = SV_SELECT_MAX_KEYS;   // power of two
-constexpr int kMergeMax = kSelMax / 2;         // keys sorted by pairwise merging (upper half = second buffer)
+constexpr int kMergeMax = kSelMax / 2;         // up to here the upper half of the key arrays is a second buffer
 
 __device__ __forceinline__ double clean_p(float p) {
   if (isnan(p)) return 0.0;
   return fmin(fmax((double)p, 0.0), 1.0);
-}
-
-// true when key (ca, ia) sorts before key (cb, ib)
-__device__ __forceinline__ bool key_before(double ca, int ia, double cb, int ib) {
-  return ca > cb || (ca == cb && ia < ib);
 }
 
 // Exclusive scan of cnt[b] + 1 over b = 0..B-1 by the whole workgroup; writes
@@ -130,19 +129,39 @@ __global__ __launch_bounds__(kSelThreads) void select_batch_kernel(
       __syncthreads();
     }
   } else {
-    for (int size = 2; size <= npad; size <<= 1) {
-      for (int stride = size >> 1; stride > 0; stride >>= 1) {
-        for (int t = tid; t < npad / 2; t += nt) {
-          const int lo = 2 * t - (t & (stride - 1));
-          const int hi = lo + stride;
-          const bool up = (lo & size) == 0;
-          const double cl = key_c[lo], ch = key_c[hi];
-          const int il = key_i[lo], ih = key_i[hi];
-          const bool swap = up ? key_before(ch, ih, cl, il) : key_before(cl, il, ch, ih);
-          if (swap) { key_c[lo] = ch; key_c[hi] = cl; key_i[lo] = ih; key_i[hi] = il; }
+    // More keys than the second buffer holds: the same merge rounds in place.  Every
+    // lane first takes its keys of the round into registers and finds their new
+    // positions (reading the old order), then, after a barrier, scatters them.
+    constexpr int kRunMax = kSelMax / kSelThreads;
+    for (int len = k; len < n; len <<= 1) {
+      double c_reg[kRunMax];
+      int i_reg[kRunMax], q_reg[kRunMax];
+#pragma unroll
+      for (int j = 0; j < kRunMax; ++j) {
+        const int p = tid + j * nt;
+        q_reg[j] = -1;
+        if (p < n) {
+          const int base = (p / (2 * len)) * (2 * len);
+          const int mid = min(n, base + len), end = min(n, base + 2 * len);
+          const bool left = p < mid;
+          const double c = key_c[p];
+          int lo = left ? mid : base, hi = left ? end : mid;
+          const int first = lo;
+          while (lo < hi) {
+            const int probe = (lo + hi) >> 1;
+            const double v = key_c[probe];
+            if (left ? (v > c) : (v >= c)) lo = probe + 1; else hi = probe;
+          }
+          c_reg[j] = c;
+          i_reg[j] = key_i[p];
+          q_reg[j] = base + (left ? p - base : p - mid) + (lo - first);
         }
-        __syncthreads();
       }
+      __syncthreads();
+#pragma unroll
+      for (int j = 0; j < kRunMax; ++j)
+        if (q_reg[j] >= 0) { key_c[q_reg[j]] = c_reg[j]; key_i[q_reg[j]] = i_reg[j]; }
+      __syncthreads();
     }
   }
 
@@ -155,14 +174,26 @@ __global__ __launch_bounds__(kSelThreads) void select_batch_kernel(
   // non-negative, u = 2^-53); wherever |G'_{M+1} - G'_M| exceeds the resulting
   // bound the comparison is already decided.  Only if an undecided comparison
   // comes before the first decided stop does one lane run the ordered sum.
-  bool need_exact = npad > nt;                     // more than one key per lane: no fast path
-  if (!need_exact) {
+  // (The bound holds for any summation tree, so lanes may own runs of keys.)
+  bool need_exact = false;
+  {
     __shared__ double wave_tot[kSelThreads / kWave];
     __shared__ double wave_last_g[kSelThreads / kWave];
     __shared__ int first_stop, first_open;
     if (tid == 0) { first_stop = n; first_open = n; }
     const int lane = tid & (kWave - 1), wave = tid >> 6;
-    double e = (tid < n) ? key_c[tid] : 0.0;       // inclusive scan: e becomes E'_{tid+1}
+    // every lane owns a run of R consecutive keys (R = 1 up to 1024 keys)
+    constexpr int kRunMax = kSelMax / kSelThreads;
+    const int R = (npad + nt - 1) / nt;
+    double e_run[kRunMax];
+    double run = 0.0;
+#pragma unroll
+    for (int j = 0; j < kRunMax; ++j) {
+      const int idx = tid * R + j;
+      if (j < R) run += (idx < n) ? key_c[idx] : 0.0;
+      e_run[j] = run;                              // inclusive inside the run
+    }
+    double e = run;                                // inclusive scan of the run totals
 #pragma unroll
     for (int off = 1; off < kWave; off <<= 1) {
       int lo = __double2loint(e), hi = __double2hiint(e);
@@ -173,19 +204,34 @@ __global__ __launch_bounds__(kSelThreads) void select_batch_kernel(
     if (lane == kWave - 1) wave_tot[wave] = e;
     __syncthreads();
     for (int w = 0; w < wave; ++w) e += wave_tot[w];
-    const double g_nxt = (tid < n) ? e / (double)latency[tid + 1] : 0.0;    // G'_{tid+1}
-    if (lane == kWave - 1) wave_last_g[wave] = g_nxt;
+    const double base = e - run;                   // E' of everything before this lane's run
+    double g_run[kRunMax];                         // G'_{idx+1} of the run's keys
+#pragma unroll
+    for (int j = 0; j < kRunMax; ++j) {
+      const int idx = tid * R + j;
+      g_run[j] = (j < R && idx < n) ? (base + e_run[j]) / (double)latency[idx + 1] : 0.0;
+    }
+    double g_last = 0.0;                           // G' of the last key of the run
+#pragma unroll
+    for (int j = 0; j < kRunMax; ++j) if (j == R - 1) g_last = g_run[j];
+    if (lane == kWave - 1) wave_last_g[wave] = g_last;
     __syncthreads();
-    int lo = __double2loint(g_nxt), hi = __double2hiint(g_nxt);
+    int lo = __double2loint(g_last), hi = __double2hiint(g_last);
     lo = __shfl_up(lo, 1, kWave);
     hi = __shfl_up(hi, 1, kWave);
-    double g_cur = __hiloint2double(hi, lo);                                 // G'_{tid}
+    double g_cur = __hiloint2double(hi, lo);                                 // G' of the key before the run
     if (lane == 0) g_cur = (wave == 0) ? 0.0 : wave_last_g[wave - 1];
-    if (tid < n) {
-      const double bound = 8.0 * (double)(n + 2) * 1.1102230246251565e-16 * fmax(g_nxt, g_cur);
-      const double d = g_nxt - g_cur;
-      if (d < -bound) atomicMin(&first_stop, tid);
-      else if (!(d > bound)) atomicMin(&first_open, tid);                    // undecided (or NaN)
+#pragma unroll
+    for (int j = 0; j < kRunMax; ++j) {
+      const int idx = tid * R + j;
+      if (j < R && idx < n) {
+        const double g_nxt = g_run[j];
+        const double bound = 8.0 * (double)(n + 2) * 1.1102230246251565e-16 * fmax(g_nxt, g_cur);
+        const double d = g_nxt - g_cur;
+        if (d < -bound) atomicMin(&first_stop, idx);
+        else if (!(d > bound)) atomicMin(&first_open, idx);                  // undecided (or NaN)
+        g_cur = g_nxt;
+      }
     }
     __syncthreads();
     if (first_open < first_stop) need_exact = true;  // block-uniform

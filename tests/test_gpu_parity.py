@@ -176,3 +176,16 @@ def test_philox_uniforms_agree_on_a_million_counters():
         i = np.arange(n_pos)[None, :]
         ra, rs = OP.sv_uniforms(seed, step, b, i)
         assert np.array_equal(ua.cpu().numpy(), ra) and np.array_equal(us.cpu().numpy(), rs)
+
+
+def test_select_length_many_ties_at_large_key_counts():
+    """Thousands of keys with only a few distinct estimates: the tie order (lowest
+    sequence first, then position) and the exact-sum fallback at every size class of
+    the kernel (one key per lane, runs of keys, in-place merge)."""
+    rng = np.random.default_rng(77)
+    for B, k in ((100, 8), (250, 12), (400, 16), (512, 16)):
+        p = rng.choice(np.array([1.0, 0.5, 0.25, 0.75], dtype=np.float32), size=(B, k))
+        for lat in (svgen.latency_table(B * k), svgen.latency_table(B * k, t0=1.0, d=0.5, m0=4)):
+            rg, ro, rm = O.select_length(p, lat, O.MODE_BATCH_GREEDY)
+            gg, go, gm = H.gpu_select_length(p, lat, O.MODE_BATCH_GREEDY)
+            assert gm == rm and np.array_equal(gg, rg) and np.array_equal(go, ro), (B, k)
