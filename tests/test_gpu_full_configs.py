@@ -164,3 +164,44 @@ def test_full_config_warped_compacted_ragged():
     assert checked >= 3
     print(f"\n  cfg5 warped, compacted: mean gamma {g.mean():.2f}, near flags {int(near.sum())}, "
           f"oracle-checked sequences {checked}", flush=True)
+
+
+def test_large_batch_chain():
+    """B = 512, k = 16 (8192 keys: the largest batch sv_select_length takes) through
+    the whole chain.  The estimate and the lengths are checked on the whole batch
+    (oracle rule on the GPU's own float32 S, A), the indicators and the verification
+    on a sample of sequences."""
+    from oracle import philox as OP
+    P = H.sv()
+    B, k, V = 512, 16, 32000
+    cfg = svgen.make_config(1, seed=31337, B=B, k=k, V=V, dtype="bf16", device="cuda")
+    f32 = lambda *s: torch.empty(s, dtype=torch.float32, device="cuda")
+    i32 = lambda *s: torch.empty(s, dtype=torch.int32, device="cuda")
+    lse_d, lse_c, S, A, p_hat, ratio = (f32(B, k) for _ in range(6))
+    gamma, offs, total = i32(B), i32(B + 1), i32(1)
+    tokens, n_acc, flags = i32(B, k + 1), i32(B), i32(B)
+    ws = P.alloc_workspace(B, k, V, P.SV_BF16)
+    edges_s, edges_a, table = svgen.profile_table(10, 10)
+    lat = svgen.latency_table(B * k)
+    P.sv_row_stats(cfg["z_d"], cfg["z_c"], cfg["x"], lse_d, lse_c, S, A, None, None, ws)
+    P.sv_accept_estimate(S, A, H.dev(edges_s), H.dev(edges_a), H.dev(table), p_hat, None)
+    P.sv_select_length(p_hat, H.dev(lat, torch.float32), P.SV_BATCH_GREEDY, gamma, offs, total)
+    P.sv_verify_sample(cfg["z_t"], None, cfg["z_d"], cfg["x"], gamma, 5, 6, tokens, n_acc, flags, ratio, ws)
+    torch.cuda.synchronize()
+    p_ref, _ = O.accept_estimate(S.cpu().numpy(), A.cpu().numpy(), edges_s, edges_a, table)
+    assert np.array_equal(p_hat.cpu().numpy(), p_ref)
+    rg, ro, rm = O.select_length(p_ref, lat, O.MODE_BATCH_GREEDY)
+    assert int(total.item()) == rm and np.array_equal(gamma.cpu().numpy(), rg) and np.array_equal(offs.cpu().numpy(), ro)
+    got_all = dict(tokens=tokens.cpu().numpy(), n_accept=n_acc.cpu().numpy(),
+                   flags=flags.cpu().numpy().astype(np.uint32), ratio=ratio.cpu().numpy())
+    x = cfg["x"].cpu().numpy()
+    for b in (0, 1, 255, 256, 511):
+        zt = svgen.to_numpy_bits(cfg["z_t"][b:b + 1])
+        zd = svgen.to_numpy_bits(cfg["z_d"][b:b + 1])
+        zc = svgen.to_numpy_bits(cfg["z_c"][b:b + 1])
+        r = O.row_stats(zd, zc, x[b:b + 1])
+        assert H.close(S.cpu().numpy()[b], r["S"][0], H.REL).all() and H.close(A.cpu().numpy()[b], r["A"][0], H.REL, 1e-30).all()
+        ua, _ = OP.sv_uniforms(5, 6, np.full((1, k), b), np.arange(k)[None, :])
+        _, us = OP.sv_uniforms(5, 6, np.full((1, k + 1), b), np.arange(k + 1)[None, :])
+        ref = O.verify_sample(zt, zd, x[b:b + 1], gamma=rg[b:b + 1], uniforms=(ua, us))
+        H.assert_verify({n: v[b:b + 1] for n, v in got_all.items()}, ref, k)
