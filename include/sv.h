@@ -23,6 +23,11 @@
  *     on the host (nothing is enqueued then).  Data-dependent conditions (NaN
  *     rows, token ids out of range, near-ties) are never errors: they set
  *     SV_FLAG_* bits in the flags outputs.
+ *   - Range of the logits: with y = z * log2(e) / T (T = 1 unless an entry
+ *     point takes a temperature), an entry with y < -2^30 - a finite stand-in
+ *     for -inf such as -1e30 or the lowest finite number of the type - carries
+ *     no probability mass, exactly like -inf; a row whose largest entry is below
+ *     that, or has y > 2^30, is reported as a bad row.
  *   - `ws` is caller-provided device scratch of at least
  *     sv_workspace_bytes(B, k, V, dtype) bytes, 256-byte aligned, which may be
  *     reused by the next call on the same stream.  Calls that share a
@@ -56,7 +61,7 @@ enum {
 
 /* Condition bits written to flags outputs. */
 enum {
-  SV_FLAG_BAD_ROW = 1,            /* a needed row holds NaN/+inf or no finite entry           */
+  SV_FLAG_BAD_ROW = 1,            /* a needed row holds NaN/+inf or no entry in range         */
   SV_FLAG_NEAR_TIE = 2,           /* |u - min(1, ratio)| < 1e-6 at an evaluated position      */
   SV_FLAG_RESIDUAL_FALLBACK = 4,  /* residual mass 0 / non-finite: token drawn from target    */
   SV_FLAG_NEAR_CDF_EDGE = 8,      /* sampling threshold within 1e-6 * W of a CDF edge         */

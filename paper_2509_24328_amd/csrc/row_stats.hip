@@ -15,11 +15,12 @@
 // A = min(1, P_c(x) / P_d(x)) is a scalar epilogue in fp64.
 //
 // Two kernels:
-//  * row_stats_stash_kernel (rows on 16-byte boundaries): 1024 lanes, one
-//    workgroup per CU.  Sweep 1 parks what it reads on chip - the first 10
-//    vector pairs of every lane stay in registers, the next 4800 pairs go to
-//    LDS (150 KB) - and only the rest of the pair (about a fifth at V = 152064,
-//    bf16) is read again, most recent bytes first so that they are still in L2.
+//  * row_stats_stash_kernel (rows on 16-byte boundaries): 512 lanes, two
+//    workgroups per CU, so that one's arithmetic overlaps the other's loads.
+//    Sweep 1 parks what it reads on chip - the first 10 vector pairs of every
+//    lane stay in registers, the next 2432 pairs go to LDS (76 KB) - and only
+//    the rest of the pair (about three fifths at V = 152064, bf16) is read
+//    again, most recent bytes first so that they are still in L2.
 //  * row_stats_kernel: plain two-sweep version for rows of any alignment.
 // Algorithmic HBM traffic: 2 * V * elem_size bytes per workgroup.
 #include "sv_device.hpp"
@@ -218,7 +219,7 @@ __device__ __forceinline__ void load_to_lds(const u32x4* src, u32x4* lds_wave_ba
 }
 
 // vector pairs per lane parked in registers: what fits beside the sweep-2
-// arithmetic within the 128 VGPRs a 1024-lane workgroup leaves each lane
+// arithmetic within the 128 VGPRs that two 512-lane workgroups per CU leave each lane
 template <bool WITH_KL>
 constexpr int reg_iters() { return WITH_KL ? 8 : 10; }
 

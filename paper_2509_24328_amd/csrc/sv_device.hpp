@@ -6,13 +6,21 @@
 //  * Philox-4x32-10 for the speculative-sampling uniforms
 //
 // A row's normaliser is carried as the pair (m, s): m = the row maximum in raw
-// logit units and s = sum_v 2^(z_v * L - c(m)), c(m) = max(fl32(m * L), -1e38),
+// logit units and s = sum_v 2^(z_v * L - c(m)), c(m) = max(fl32(m * L), -2^30),
 // where L is log2(e) / T rounded to fp32 (T = sampling temperature of the
 // tensor, 1 unless a warped entry point says otherwise; L32 is the T = 1 value).
 // Because L T / log2(e) = 1 + tau1 with |tau1| < 6e-8 (1.33e-8 for L32) the sum
 // is the soft-max normaliser at a temperature off by that factor; the fp64
 // epilogue removes the first-order effect around the row maximum
 // (lse_from_ms), leaving an error below |tau1| * (H - H_inf) of the row.
+//
+// Range of the logits.  2^(z L - c) is formed with one fused multiply-add, so it
+// is right for any z as long as the part of m * L that fp32 drops from c stays a
+// small exponent: |c| <= 2^30 keeps it within +-32.  Hence the floor of c: an
+// entry with z L < -2^30 (a finite stand-in for -inf such as -1e30, or the
+// lowest finite number of the storage type) carries no mass, exactly like
+// -inf, and a row without any entry above the floor is a bad row.  A row whose
+// maximum has m * L > 2^30 is a bad row as well.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -25,7 +33,8 @@ constexpr float kL32 = 1.44269502162933349609375f;          // fl32(log2 e)
 constexpr double kLog2e = 1.4426950408889634073599246810019;  // log2 e
 constexpr double kLn2 = 0.69314718055994530941723212145818;
 constexpr double kTauMinus1 = (double)kL32 / kLog2e - 1.0;   // ~ +1.33e-8
-constexpr float kRefFloor = -1.0e38f;                         // keeps c(m) finite
+constexpr float kRefFloor = -1073741824.f;                    // -2^30: lowest reference c(m)
+constexpr float kRefCeil = 1073741824.f;                      // 2^30: highest usable reference
 
 // Exponent scale of one logit tensor: 2^(z L) = e^((z / T) (1 + tau1)).
 struct Scale {
@@ -236,7 +245,7 @@ __device__ __forceinline__ void block_merge(const Online (&o)[NR], MergeScratch<
 // removing the temperature offset around the maximum.  Bad rows (NaN, +inf, no
 // finite entry) give NaN.
 __device__ __forceinline__ double lse_from_ms(const MS& r, const Scale sc = unit_scale()) {
-  if (!(r.s > 0.0) || !isfinite(r.s) || !isfinite(r.m)) return __builtin_nan("");
+  if (!(r.s > 0.0) || !isfinite(r.s) || !isfinite(r.m) || ref_of(r.m, sc.L) > kRefCeil) return __builtin_nan("");
   const double kappa = (double)ref_of(r.m, sc.L) + log2(r.s);
   return kappa * kLn2 - sc.tau1 * ((double)r.m * sc.inv_t);
 }

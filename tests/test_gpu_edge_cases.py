@@ -123,3 +123,66 @@ def test_results_are_reproducible_run_to_run():
         assert np.array_equal(a["ratio"], b["ratio"], equal_nan=True)
         for n in ("lse_d", "S", "A", "KL"):
             assert np.array_equal(s1[n], s2[n], equal_nan=True)
+
+
+@pytest.mark.parametrize("V,dtype", [(70000, torch.bfloat16), (40000, torch.float32), (152064, torch.bfloat16)])
+def test_row_stats_when_the_running_reference_has_to_move(V, dtype):
+    """The online sum-exp of sv_row_stats rescales its per-lane sums whenever the running
+    maximum moves.  Rows that force that at every stage of the aligned-row kernel (sizes
+    whose pairs span its register, LDS and re-read shares): steep ramps (up: a move every
+    vector; down: none, later terms underflow), a row whose first half is masked, a row of
+    -1e30 with a few ordinary entries, isolated spikes, and bad entries met late."""
+    rng = np.random.default_rng(V)
+    B, k = 2, 4
+    base = (2 * rng.standard_normal((B, k, V))).astype(np.float32)
+    ramp = np.linspace(-300.0, 300.0, V, dtype=np.float32)
+    z_d = base.copy()
+    z_c = (base + rng.standard_normal((B, k, V))).astype(np.float32)
+    z_d[0, 0] += ramp                      # rising: the reference keeps moving
+    z_c[0, 0] += 0.5 * ramp
+    z_d[0, 1] += ramp[::-1]                # falling: no move, later terms underflow
+    z_c[0, 1] += 0.9 * ramp[::-1]
+    z_d[0, 2, : V // 2] = -np.inf          # nothing finite for the first half of the row
+    z_c[0, 3, :] = -1e30                   # a reference far below the few ordinary entries
+    z_c[0, 3, V // 3 :: 997] = base[0, 3, V // 3 :: 997]
+    z_d[1, 0, V - 5] = np.nan              # bad entries met after the references are set
+    z_c[1, 1, V - 9] = np.inf
+    z_d[1, 2, 17::4096] += 200.0           # isolated spikes
+    z_c[1, 3, 5::8192] += 90.0
+    x = rng.integers(V // 2, V, size=(B, k)).astype(np.int32)
+    if dtype == torch.bfloat16:            # the oracle sees exactly the stored values
+        z_d = torch.from_numpy(z_d).to(torch.bfloat16).float().numpy()
+        z_c = torch.from_numpy(z_c).to(torch.bfloat16).float().numpy()
+    ref = O.row_stats(z_d, z_c, x)
+    got = H.gpu_row_stats(H.dev(z_d, dtype), H.dev(z_c, dtype), H.dev(x))
+    H.assert_row_stats(got, ref)
+    assert np.isnan(got["lse_d"][1, 0]) and np.isnan(got["lse_c"][1, 1])
+    assert np.isfinite(got["S"][0]).all()
+
+
+@pytest.mark.parametrize("V,dtype,mask", [(301, torch.float32, -1e30), (4096, torch.bfloat16, -1e30),
+                                          (300, torch.float32, float(np.finfo(np.float32).min)),
+                                          (4096, torch.bfloat16, -3.3895313892515355e38), (2048, torch.float32, -1e10)])
+def test_finite_stand_ins_for_minus_inf(V, dtype, mask):
+    """Vocabulary masks written as a huge negative finite number instead of -inf carry no
+    mass in any call (the library documents this range rule; in fp64 the oracle gets the
+    same numbers because exp(mask - lse) underflows to zero)."""
+    z_t, z_d, z_c, x = _case(B=3, k=3, V=V, seed=V)
+    rng = np.random.default_rng(V + 1)
+    for z in (z_t, z_d, z_c):
+        z[rng.random(z.shape) < 0.7] = mask
+    z_d[0, 0, :64] = mask                  # whole leading vectors masked
+    z_t[1, 1, : V // 2] = mask
+    z_d[2, 2, :] = mask                    # nothing in range: a bad row on the GPU ...
+    z_d[2, 2, 0] = 1.0                     # ... unless one entry is
+    x[0, 0] = 100
+    if dtype == torch.bfloat16:
+        z_t, z_d, z_c = (torch.from_numpy(z).to(torch.bfloat16).float().numpy() for z in (z_t, z_d, z_c))
+    with np.errstate(over="ignore"):       # exp(-mask) overflows to +inf inside the oracle's min(1, .)
+        ref = O.row_stats(z_d, z_c, x)
+    # (KL is left out: draft mass on a masked companion entry makes it about -mask)
+    got = H.gpu_row_stats(H.dev(z_d, dtype), H.dev(z_c, dtype), H.dev(x), with_kl=False)
+    H.assert_row_stats(got, ref, with_kl=False)
+    gotv, refv = _run_verify(z_t, z_d, x, seed=11, step=2) if dtype == torch.float32 else (None, None)
+    if gotv is not None:
+        H.assert_verify(gotv, refv, 3)
