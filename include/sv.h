@@ -63,7 +63,7 @@ enum {
 enum {
   SV_FLAG_BAD_ROW = 1,            /* a needed row holds NaN/+inf or no entry in range         */
   SV_FLAG_NEAR_TIE = 2,           /* |u - min(1, ratio)| < 1e-6 at an evaluated position      */
-  SV_FLAG_RESIDUAL_FALLBACK = 4,  /* residual mass 0 / non-finite: token drawn from target    */
+  SV_FLAG_RESIDUAL_FALLBACK = 4,  /* residual mass <= 1e-6 / non-finite: drawn from target    */
   SV_FLAG_NEAR_CDF_EDGE = 8,      /* sampling threshold within 1e-6 * W of a CDF edge         */
   SV_FLAG_BAD_TOKEN = 16,         /* drafted token id outside [0, V)                          */
   SV_FLAG_NOT_COMPACT = 32        /* a needed row has no compact support (count < 0): the

@@ -49,7 +49,8 @@ from . import philox
 # Per-sequence / per-row condition bits (data-dependent, never errors).
 FLAG_BAD_ROW = 1            # a row with a NaN or no finite entry was needed
 FLAG_NEAR_TIE = 2           # |u - min(1, rho)| < NEAR_TIE_EPS at an evaluated position
-FLAG_RESIDUAL_FALLBACK = 4  # residual mass was 0 / non-finite; target row used instead
+RESIDUAL_FLOOR = 1e-6       # residual mass at or below this counts as none
+FLAG_RESIDUAL_FALLBACK = 4  # residual mass <= RESIDUAL_FLOOR / non-finite; target row used instead
 FLAG_NEAR_CDF_EDGE = 8      # sampling threshold within CDF_EDGE_EPS * W of a CDF edge
 FLAG_BAD_TOKEN = 16         # drafted token id outside [0, V)
 
@@ -338,8 +339,11 @@ def sampling_weights(z_t_row, z_d_row=None):
     """Unnormalised sampling weights w over the vocabulary and their mass W.
 
     With a draft row: the residual max(0, P_t - P_d).  Without: P_t itself
-    (bonus token / position the target generates on its own).  A residual of
-    zero or non-finite mass falls back to P_t.  Returns (w, W, flag_bits); a
+    (bonus token / position the target generates on its own).  A residual whose
+    mass is not above RESIDUAL_FLOOR (P_t and P_d agree to within what fp32
+    probabilities can resolve; a rejection can still happen there when the
+    drafted token has no mass under either model), or is non-finite, falls back
+    to P_t.  Returns (w, W, flag_bits); a
     bad target row gives (None, nan, FLAG_BAD_ROW).
     """
     lse_t, lp_t = log_softmax_row(upcast(z_t_row))
@@ -352,7 +356,7 @@ def sampling_weights(z_t_row, z_d_row=None):
         if not np.isnan(lse_d):
             w = np.maximum(0.0, p_t - np.exp(lp_d))
             W = float(np.sum(w))
-            if np.isfinite(W) and W > 0.0:
+            if np.isfinite(W) and W > RESIDUAL_FLOOR:
                 return w, W, flags
         else:
             flags |= FLAG_BAD_ROW

@@ -15,6 +15,7 @@ struct Plan;
 constexpr int kChunk = 8192;          // vocabulary entries per sampling chunk
 constexpr size_t kWsAlign = 256;
 constexpr int kMaxSplit = 8;          // a row may be swept by up to 8 workgroups
+constexpr double kResidualFloor = 1e-6;   // residual mass (relative to the target's) at or below this: none
 
 inline hipStream_t as_stream(sv_stream_t s) { return reinterpret_cast<hipStream_t>(s); }
 

@@ -166,23 +166,31 @@ __global__ __launch_bounds__(kRowsThreads) void verify_rows_kernel(VerifyArgs a)
 // Probability of one vocabulary entry: 2^(z l - kappa) with l = log2(e) / T
 // carried as L + l_lo and kappa = k_hi + k_lo, so that neither the rounding of
 // the scale nor that of the row normaliser biases every entry of a row the
-// same way: p = e * (1 + ln2 * (z l_lo - k_lo)), e = 2^(z L - k_hi).
+// same way.  The exponent is head + tail, head = z L - k_hi (one fused
+// multiply-add: exact up to its own rounding whatever the size of z) and
+// tail = z l_lo - k_lo (|tail| grows with |z|: 1e-6 for ordinary logits, 1e-2
+// at |z| = 1e6).  2^(head + tail) is formed as 2^a (1 + ln2 r) with
+// a = fl(head + tail) and r = what that addition dropped, so the error does
+// not grow with the size of the logits.
 struct ProbRow {
   float L;         // fl32(log2(e) / T)
   float k_hi;      // fl32(kappa)
-  float lo_mul;    // ln2 * (log2(e) / T - L)
-  float lo_add;    // -ln2 * (kappa - k_hi)
+  float l_lo;      // log2(e) / T - L
+  float k_lo;      // kappa - k_hi
   __device__ __forceinline__ void set(double lse, const Scale& sc) {
     const double kappa = lse * kLog2e;
     L = sc.L;
     k_hi = (float)kappa;
-    lo_mul = (float)(kLn2 * sc.l_lo);
-    lo_add = (float)(-kLn2 * (kappa - (double)k_hi));
+    l_lo = (float)sc.l_lo;
+    k_lo = (float)(kappa - (double)k_hi);
   }
   __device__ __forceinline__ float p(float z) const {
-    const float e = exp2_fast(__builtin_fmaf(z, L, -k_hi));
-    const float corr = __builtin_fmaf(z, lo_mul, lo_add);
-    return e > 0.f ? __builtin_fmaf(e, corr, e) : 0.f;   // z = -inf: corr is inf, mass is 0
+    const float head = __builtin_fmaf(z, L, -k_hi);
+    const float tail = __builtin_fmaf(z, l_lo, -k_lo);
+    const float a = head + tail;
+    const float r = (head - a) + tail;
+    const float e = exp2_fast(a);
+    return e > 0.f ? __builtin_fmaf(e, (float)kLn2 * r, e) : 0.f;   // z = -inf: a is -inf or NaN, mass is 0
   }
 };
 
@@ -382,7 +390,8 @@ __global__ __launch_bounds__(kSampleThreads) void verify_pick_kernel(VerifyArgs 
     double Wr = 0.0, Wt = 0.0;
     for (int j = 0; j < C; ++j) { Wr += mr[j]; Wt += mt[j]; }
     int use_resid = resid;
-    if (target_ok && resid && !(isfinite(Wr) && Wr > 0.0)) { use_resid = 0; flags |= SV_FLAG_RESIDUAL_FALLBACK; }
+    // a residual within what fp32 probabilities can resolve of zero counts as none
+    if (target_ok && resid && !(isfinite(Wr) && Wr > kResidualFloor * Wt)) { use_resid = 0; flags |= SV_FLAG_RESIDUAL_FALLBACK; }
     const double W = use_resid ? Wr : Wt;
     int chunk = -1;
     double tau_local = 0.0;

@@ -80,6 +80,13 @@ def gpu_verify(z_t, z_d, x, gamma=None, t_offsets=None, seed=0, step=0):
 
 # ------------------------------------------------------------------ compare
 def close(got, ref, rel=REL, abs_floor=0.0):
+    """|got - ref| <= rel |ref| + abs_floor, NaN = NaN, inf = inf.  A float32
+    result is compared with what float32 can hold of the reference: beyond its
+    range the reference counts as inf, below its normal range as zero."""
+    if np.asarray(got).dtype == np.float32:
+        with np.errstate(over="ignore", under="ignore"):
+            ref = np.asarray(ref, dtype=np.float64).astype(np.float32)
+        abs_floor = max(abs_floor, float(np.finfo(np.float32).tiny))
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
     both_nan = np.isnan(got) & np.isnan(ref)

@@ -137,3 +137,61 @@ def test_random_warped_problems(block):
             n_seq += int(m.sum())
     print(f"\n  warped block {block}: {n_seq} sequence checks, {n_sparse} compacted pairs, near-tie {n_tie}", flush=True)
     assert n_seq >= 20 and n_sparse >= 20
+
+
+def _adversarial_rows(rng, B, k, V, bf16):
+    """Gaussian logits with, row by row, one of: a huge or tiny scale, a huge common
+    offset, a mask (-inf or one of its finite stand-ins) over 10-99 % of the entries,
+    integer values (ties), a constant row, a one-hot row."""
+    z_t = (2 * rng.standard_normal((B, k + 1, V))).astype(np.float32)
+    z_d = (z_t[:, :k] + rng.standard_normal((B, k, V)) * rng.choice([0.0, 0.3, 1.0, 3.0])).astype(np.float32)
+    z_c = (z_t[:, :k] + rng.standard_normal((B, k, V)) * rng.choice([0.0, 0.3, 1.0, 3.0])).astype(np.float32)
+    for z in (z_t, z_d, z_c):
+        for row in z.reshape(-1, V):
+            r = rng.random()
+            if r < 0.15:
+                row *= rng.choice([1e-3, 30.0, 1e3, 1e5])
+            elif r < 0.30:
+                row += rng.choice([-1e6, -1e4, -100.0, 100.0, 1e4, 1e6])
+            elif r < 0.50:
+                keep = rng.random(V) >= rng.choice([0.1, 0.5, 0.9, 0.99])
+                keep[rng.integers(V)] = True
+                row[~keep] = rng.choice([-np.inf, -1e30, float(np.finfo(np.float32).min), -1e9, -65504.0])
+            elif r < 0.58:
+                row[:] = np.round(row)
+            elif r < 0.62:
+                row[:] = row[0]
+            elif r < 0.66:
+                j = rng.integers(V)
+                row[:] = -np.inf
+                row[j] = rng.choice([0.0, 50.0, -50.0])
+    x = rng.integers(0, V, size=(B, k)).astype(np.int32)
+    if bf16:
+        z_t, z_d, z_c = (torch.from_numpy(z).to(torch.bfloat16).float().numpy() for z in (z_t, z_d, z_c))
+    return z_t, z_d, z_c, x
+
+
+@pytest.mark.parametrize("block", range(4))
+def test_random_adversarial_values(block):
+    """sv_row_stats and sv_verify_sample against the oracle on rows far from the recipe of
+    the configurations: logits of size 1e6, one-hot and constant rows, vocabularies of 1-17
+    entries, masks written as -1e30 / the lowest finite number / -65504.  Drafted tokens
+    are arbitrary, so tokens without mass under either model occur."""
+    n_seq = n_tie = 0
+    for case in range(40):
+        rng = np.random.default_rng(31000 + 100 * block + case)
+        bf16 = bool(case % 2)
+        dtype = torch.bfloat16 if bf16 else torch.float32
+        V = int(rng.choice([1, 2, 3, 7, 8, 17, 64, 300, 1000, 4096, 5001, 20000, 33000]))
+        B, k = int(rng.integers(1, 4)), int(rng.integers(1, 5))
+        z_t, z_d, z_c, x = _adversarial_rows(rng, B, k, V, bf16)
+        with np.errstate(all="ignore"):         # exp of +-1e6 inside the oracle's min(1, .) and ratios
+            ref = O.row_stats(z_d, z_c, x)
+            vref = O.verify_sample(z_t, z_d, x, seed=case, step=block)
+        # KL is left out: draft mass on a masked companion entry makes it about -mask
+        got = H.gpu_row_stats(H.dev(z_d, dtype), H.dev(z_c, dtype), H.dev(x), with_kl=False)
+        H.assert_row_stats(got, ref, with_kl=False)
+        vgot = H.gpu_verify(H.dev(z_t, dtype), H.dev(z_d, dtype), H.dev(x), seed=case, step=block)
+        t, _ = H.assert_verify(vgot, vref, k)
+        n_seq, n_tie = n_seq + B, n_tie + t
+    print(f"\n  block {block}: {n_seq} sequences, near-tie {n_tie}", flush=True)

@@ -230,3 +230,19 @@ def test_flags_near_tie_residual_fallback_bad_inputs():
     # token id out of range: rejected there, flagged, residual still drawn
     out = O.verify_sample(z, z[:, :1], np.array([[7]]), seed=1)
     assert out["flags"][0] & O.FLAG_BAD_TOKEN and out["n_accept"][0] == 0 and out["tokens"][0, 0] >= 0
+
+
+def test_residual_mass_floor():
+    """A residual mass at or below RESIDUAL_FLOOR counts as none (target row drawn, flagged);
+    above it the residual is used.  Two-token rows: P_t = (a, 1-a), P_d = (a-d, 1-a+d) give
+    the residual (d, 0) exactly, mass d."""
+    a = 0.4
+    for d, fallback in ((2e-7, True), (0.9 * O.RESIDUAL_FLOOR, True), (3 * O.RESIDUAL_FLOOR, False), (1e-3, False)):
+        zt = np.log(np.array([a, 1 - a]))
+        zd = np.log(np.array([a - d, 1 - a + d]))
+        w, W, fl = O.sampling_weights(zt, zd)
+        assert bool(fl & O.FLAG_RESIDUAL_FALLBACK) == fallback, d
+        if fallback:
+            assert np.allclose(w, [a, 1 - a], rtol=1e-12) and abs(W - 1) < 1e-12
+        else:
+            assert abs(W - d) < 1e-12 and w[1] == 0.0 and abs(w[0] - d) < 1e-12
