@@ -47,13 +47,91 @@ def test_random_problems(block):
     print(f"\n  block {block}: {n_seq} sequences, near-tie {n_tie}, near-cdf-edge {n_edge}", flush=True)
 
 
-@pytest.mark.parametrize("block", range(4))
-def test_random_warped_problems(block):
-    """Random shapes and sampling hyper-parameters through the dense warped entry
-    points (GPU cutoffs) and through the compacted ones, both against the oracle
-    on warped rows.  Sequences touching a near-tie top-p decision are skipped."""
+def _warped_case(rng, zs, dtype, par, with_kl=True):
+    """One problem through the dense warped entry points (GPU cutoffs) and through the
+    compacted ones, both against the oracle on warped rows.  zs: float32 arrays z_t, z_d,
+    z_c holding exactly the stored values; par: (T, K, P) per tensor.  Drafted tokens are
+    drawn from the warped draft distribution.  Pairs / sequences touching a near-tie top-p
+    decision are skipped.  Returns (sequence checks, compacted pairs, near-ties)."""
     from oracle import warp_oracle as W
     P = H.sv()
+    B, k, V = zs["d"].shape
+    d = {n: H.dev(z, dtype) for n, z in zs.items()}
+    y, cut, fl, gcut, gfl, sup = {}, {}, {}, {}, {}, {}
+    for name in ("t", "d", "c"):
+        T, K, Pp = par[name]
+        with np.errstate(all="ignore"):
+            y[name], cut[name], fl[name] = W.warp_rows(zs[name], T, K, Pp)
+        rows = zs[name].shape[0] * zs[name].shape[1]
+        gcut[name] = torch.empty(rows, dtype=torch.float32, device="cuda")
+        gf = torch.empty(rows, dtype=torch.int32, device="cuda")
+        sup[name] = P.Supports(rows, 128)
+        P.sv_warp_compact(d[name], T, K, Pp, sup[name], gcut[name], gf)
+        torch.cuda.synchronize()
+        gfl[name] = gf.cpu().numpy().astype(np.uint32).reshape(fl[name].shape)
+    tie = lambda n: ((fl[n] | gfl[n]) & O.FLAG_NEAR_TIE) != 0
+    pair_tie = tie("d") | tie("c")
+    seq_tie = tie("t").any(1) | tie("d").any(1)
+    x = rng.integers(0, V, size=(B, k)).astype(np.int32)
+    for b in range(B):
+        for i in range(k):
+            r = y["d"][b, i]
+            if np.isfinite(r).any() and not np.isnan(r).any() and not np.isposinf(r).any():
+                p = np.exp(r - r[np.isfinite(r)].max())
+                p[~np.isfinite(r)] = 0.0
+                if p.sum() > 0:
+                    x[b, i] = rng.choice(V, p=p / p.sum())
+    xg = H.dev(x, torch.int32)
+    with np.errstate(all="ignore"):
+        ref = O.row_stats(y["d"], y["c"], x)
+    f32 = lambda *s: torch.full(s, -7.0, dtype=torch.float32, device="cuda")
+    i32 = lambda *s: torch.full(s, -5, dtype=torch.int32, device="cuda")
+    ws = P.alloc_workspace(B, k, V, P.binding._dtype_tag(d["d"]))
+    keep = ~pair_tie
+    pick = lambda dct, m: {n: np.asarray(v)[m] for n, v in dct.items() if v is not None}
+    # dense warped indicators
+    o = dict(lse_d=f32(B, k), lse_c=f32(B, k), S=f32(B, k), A=f32(B, k), KL=f32(B, k) if with_kl else None,
+             H_d=f32(B, k) if with_kl else None, pd_x=f32(B, k), flags=i32(B, k))
+    P.sv_row_stats_warped(d["d"], d["c"], xg, par["d"][0], gcut["d"], par["c"][0], gcut["c"], o["lse_d"],
+                          o["lse_c"], o["S"], o["A"], o["KL"], o["flags"], ws, entropy_d=o["H_d"], pd_x=o["pd_x"])
+    torch.cuda.synchronize()
+    H.assert_row_stats(pick({n: None if t is None else t.cpu().numpy() for n, t in o.items()}, keep), pick(ref, keep), with_kl)
+    # compacted indicators
+    P.sv_row_stats_sparse(sup["d"], sup["c"], xg, V, o["lse_d"], o["lse_c"], o["S"], o["A"], o["KL"], o["flags"],
+                          entropy_d=o["H_d"], pd_x=o["pd_x"])
+    torch.cuda.synchronize()
+    got = {n: None if t is None else t.cpu().numpy() for n, t in o.items()}
+    ks = keep & ((got["flags"].astype(np.uint32) & 32) == 0)
+    H.assert_row_stats(pick(got, ks), pick(ref, ks), with_kl)
+    # verification, dense warped and compacted
+    gamma = rng.integers(0, k + 1, size=B).astype(np.int32) if rng.random() < 0.6 else None
+    gg = None if gamma is None else H.dev(gamma, torch.int32)
+    pseed, step = int(rng.integers(0, 2 ** 62)), int(rng.integers(0, 2 ** 31))
+    with np.errstate(all="ignore"):
+        vref = O.verify_sample(y["t"], y["d"], x, gamma=gamma, seed=pseed, step=step)
+    sub = lambda dct, m: {n: ([v[i] for i in np.flatnonzero(m)] if isinstance(v, list) else np.asarray(v)[m])
+                          for n, v in dct.items()}
+    n_seq = n_tie = 0
+    for mode in ("dense", "sparse"):
+        tokens, n_acc, flags, ratio = i32(B, k + 1), i32(B), i32(B), f32(B, k)
+        if mode == "dense":
+            P.sv_verify_sample_warped(d["t"], None, d["d"], xg, gg, par["t"][0], gcut["t"], par["d"][0],
+                                      gcut["d"], pseed, step, tokens, n_acc, flags, ratio, ws)
+        else:
+            P.sv_verify_sample_sparse(sup["t"], None, sup["d"], xg, gg, V, pseed, step, tokens, n_acc, flags, ratio)
+        torch.cuda.synchronize()
+        vgot = dict(tokens=tokens.cpu().numpy(), n_accept=n_acc.cpu().numpy(),
+                    flags=flags.cpu().numpy().astype(np.uint32), ratio=ratio.cpu().numpy())
+        m = ~seq_tie & ((vgot["flags"] & 32) == 0)
+        t, _ = H.assert_verify(sub(vgot, m), sub(vref, m), k)
+        n_tie += t
+        n_seq += int(m.sum())
+    return n_seq, int(ks.sum()), n_tie
+
+
+@pytest.mark.parametrize("block", range(4))
+def test_random_warped_problems(block):
+    """Random shapes and sampling hyper-parameters on the configurations' input recipes."""
     rng = np.random.default_rng(7700 + block)
     n_seq = n_tie = n_sparse = 0
     for case in range(8):
@@ -64,7 +142,6 @@ def test_random_warped_problems(block):
                             8 * int(rng.integers(1000, 5000)), 8192 * int(rng.integers(1, 4)) + int(rng.integers(0, 9))]))
         dtype = "bf16" if rng.random() < 0.7 else "f32"
         cfg = svgen.make_config(idx, B=B, k=k, V=V, dtype=dtype, seed=int(rng.integers(0, 2 ** 31)))
-        d = {n: cfg[n].cuda() for n in ("z_t", "z_d", "z_c", "x")}
         oi = H.oracle_inputs(cfg)
         par = {}
         for name in ("t", "d", "c"):
@@ -72,69 +149,9 @@ def test_random_warped_problems(block):
             K = int(rng.choice([0, 1, 5, 20, 50]))
             Pp = float(rng.choice([1.0, 0.9, 0.8, 0.6]))
             par[name] = (T, K, Pp)
-        y, cut, fl, gcut, gfl, sup = {}, {}, {}, {}, {}, {}
-        for name, z in (("t", "z_t"), ("d", "z_d"), ("c", "z_c")):
-            T, K, Pp = par[name]
-            y[name], cut[name], fl[name] = W.warp_rows(oi[z], T, K, Pp)
-            rows = d[z].shape[0] * d[z].shape[1]
-            gcut[name] = torch.empty(rows, dtype=torch.float32, device="cuda")
-            gf = torch.empty(rows, dtype=torch.int32, device="cuda")
-            sup[name] = P.Supports(rows, 128)
-            P.sv_warp_compact(d[z], T, K, Pp, sup[name], gcut[name], gf)
-            torch.cuda.synchronize()
-            gfl[name] = gf.cpu().numpy().astype(np.uint32).reshape(fl[name].shape)
-        tie = lambda n: ((fl[n] | gfl[n]) & O.FLAG_NEAR_TIE) != 0
-        pair_tie = tie("d") | tie("c")
-        seq_tie = tie("t").any(1) | tie("d").any(1)
-        # drafted tokens from the warped draft distribution
-        x = np.zeros((B, k), dtype=np.int32)
-        for b in range(B):
-            for i in range(k):
-                p = np.exp(y["d"][b, i] - y["d"][b, i].max())
-                x[b, i] = rng.choice(V, p=p / p.sum())
-        xg = H.dev(x, torch.int32)
-        ref = O.row_stats(y["d"], y["c"], x)
-        f32 = lambda *s: torch.full(s, -7.0, dtype=torch.float32, device="cuda")
-        i32 = lambda *s: torch.full(s, -5, dtype=torch.int32, device="cuda")
-        ws = P.alloc_workspace(B, k, V, P.binding._dtype_tag(d["z_d"]))
-        keep = ~pair_tie
-        pick = lambda dct, m: {n: np.asarray(v)[m] for n, v in dct.items()}
-        # dense warped indicators
-        o = dict(lse_d=f32(B, k), lse_c=f32(B, k), S=f32(B, k), A=f32(B, k), KL=f32(B, k), H_d=f32(B, k),
-                 pd_x=f32(B, k), flags=i32(B, k))
-        P.sv_row_stats_warped(d["z_d"], d["z_c"], xg, par["d"][0], gcut["d"], par["c"][0], gcut["c"], o["lse_d"],
-                              o["lse_c"], o["S"], o["A"], o["KL"], o["flags"], ws, entropy_d=o["H_d"], pd_x=o["pd_x"])
-        torch.cuda.synchronize()
-        H.assert_row_stats(pick({n: t.cpu().numpy() for n, t in o.items()}, keep), pick(ref, keep))
-        # compacted indicators
-        P.sv_row_stats_sparse(sup["d"], sup["c"], xg, V, o["lse_d"], o["lse_c"], o["S"], o["A"], o["KL"], o["flags"],
-                              entropy_d=o["H_d"], pd_x=o["pd_x"])
-        torch.cuda.synchronize()
-        got = {n: t.cpu().numpy() for n, t in o.items()}
-        ks = keep & ((got["flags"].astype(np.uint32) & 32) == 0)
-        n_sparse += int(ks.sum())
-        H.assert_row_stats(pick(got, ks), pick(ref, ks))
-        # verification, dense warped and compacted
-        gamma = rng.integers(0, k + 1, size=B).astype(np.int32) if rng.random() < 0.6 else None
-        gg = None if gamma is None else H.dev(gamma, torch.int32)
-        pseed, step = int(rng.integers(0, 2 ** 62)), int(rng.integers(0, 2 ** 31))
-        vref = O.verify_sample(y["t"], y["d"], x, gamma=gamma, seed=pseed, step=step)
-        sub = lambda dct, m: {n: ([v[i] for i in np.flatnonzero(m)] if isinstance(v, list) else np.asarray(v)[m])
-                              for n, v in dct.items()}
-        for mode in ("dense", "sparse"):
-            tokens, n_acc, flags, ratio = i32(B, k + 1), i32(B), i32(B), f32(B, k)
-            if mode == "dense":
-                P.sv_verify_sample_warped(d["z_t"], None, d["z_d"], xg, gg, par["t"][0], gcut["t"], par["d"][0],
-                                          gcut["d"], pseed, step, tokens, n_acc, flags, ratio, ws)
-            else:
-                P.sv_verify_sample_sparse(sup["t"], None, sup["d"], xg, gg, V, pseed, step, tokens, n_acc, flags, ratio)
-            torch.cuda.synchronize()
-            vgot = dict(tokens=tokens.cpu().numpy(), n_accept=n_acc.cpu().numpy(),
-                        flags=flags.cpu().numpy().astype(np.uint32), ratio=ratio.cpu().numpy())
-            m = ~seq_tie & ((vgot["flags"] & 32) == 0)
-            t, _ = H.assert_verify(sub(vgot, m), sub(vref, m), k)
-            n_tie += t
-            n_seq += int(m.sum())
+        zs = {n: O.upcast(oi["z_" + n]).astype(np.float32) for n in ("t", "d", "c")}   # exactly the stored values
+        s, p, t = _warped_case(rng, zs, cfg["z_d"].dtype, par)
+        n_seq, n_sparse, n_tie = n_seq + s, n_sparse + p, n_tie + t
     print(f"\n  warped block {block}: {n_seq} sequence checks, {n_sparse} compacted pairs, near-tie {n_tie}", flush=True)
     assert n_seq >= 20 and n_sparse >= 20
 
@@ -195,3 +212,39 @@ def test_random_adversarial_values(block):
         t, _ = H.assert_verify(vgot, vref, k)
         n_seq, n_tie = n_seq + B, n_tie + t
     print(f"\n  block {block}: {n_seq} sequences, near-tie {n_tie}", flush=True)
+
+
+@pytest.mark.parametrize("block", range(3))
+def test_random_adversarial_values_warped(block):
+    """The warped and compacted entry points on the adversarial rows above, with
+    temperatures from 1e-3 to 1e3, top-k from 1 to V and top-p from 0.01 to 1.  Problems
+    outside the documented range of the logits (|z| / T beyond 2^29 / log2 e for an entry
+    that is no mask) are left out."""
+    n_seq = n_sparse = n_tie = n_skipped = 0
+    for case in range(40):
+        rng = np.random.default_rng(47000 + 100 * block + case)
+        bf16 = bool(case % 2)
+        V = int(rng.choice([1, 2, 3, 7, 8, 17, 64, 300, 1000, 4096, 5001, 20000]))
+        B, k = int(rng.integers(1, 4)), int(rng.integers(1, 5))
+        z_t, z_d, z_c, _ = _adversarial_rows(rng, B, k, V, bf16)
+        zs = dict(t=z_t, d=z_d, c=z_c)
+        par = {}
+        for name in ("t", "d", "c"):
+            T = float(np.float32(rng.choice([1e-3, 0.05, 0.7, 1.0, 1.3, 10.0, 1e3])))
+            K = int(rng.choice([0, 1, 2, 5, 20, 50, V]))
+            Pp = float(rng.choice([1.0, 0.999, 0.9, 0.5, 0.01]))
+            par[name] = (T, K, Pp)
+        in_range = True
+        for name in ("t", "d", "c"):
+            z = zs[name]
+            no_mask = np.isfinite(z) & (np.abs(z) < 1e20)
+            if no_mask.any() and (np.abs(z[no_mask]) / par[name][0] * 1.4427 > 2 ** 29).any():
+                in_range = False
+        if not in_range:
+            n_skipped += 1
+            continue
+        s, p, t = _warped_case(rng, zs, torch.bfloat16 if bf16 else torch.float32, par, with_kl=False)
+        n_seq, n_sparse, n_tie = n_seq + s, n_sparse + p, n_tie + t
+    print(f"\n  adversarial warped block {block}: {n_seq} sequence checks, {n_sparse} compacted pairs, "
+          f"near-tie {n_tie}, out of range {n_skipped}", flush=True)
+    assert n_seq >= 40 and n_sparse >= 40
