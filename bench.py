@@ -184,7 +184,7 @@ def main():
     hip = Hip()
     names = {Bd.SV_KERNEL_ROW_STATS: "row_stats_stash_kernel", Bd.SV_KERNEL_ACCEPT_ESTIMATE: "accept_estimate_kernel",
              Bd.SV_KERNEL_SELECT_LENGTH: "select_batch_kernel", Bd.SV_KERNEL_VERIFY_ROWS: "verify_rows_kernel",
-             Bd.SV_KERNEL_VERIFY_ACCEPT: "verify_accept_kernel", Bd.SV_KERNEL_VERIFY_MASS: "verify_mass_kernel", Bd.SV_KERNEL_VERIFY_PICK: "verify_pick_kernel"}
+             Bd.SV_KERNEL_VERIFY_MASS: "verify_mass_kernel", Bd.SV_KERNEL_VERIFY_PICK: "verify_pick_kernel"}
     ev = {kid: [(hip.event(), hip.event()) for _ in range(args.steps)] for kid in names}
     for i in range(args.steps):
         for kid in names:
@@ -205,7 +205,7 @@ def main():
     verify_rows = B * (2 * k + 1)
     stats_rows = 2 * B * k
     alg = {"verify_rows_kernel": verify_rows * row_bytes, "row_stats_stash_kernel": stats_rows * row_bytes,
-           "verify_accept_kernel": 0, "verify_mass_kernel": 0, "verify_pick_kernel": 0, "accept_estimate_kernel": 0,
+           "verify_mass_kernel": 0, "verify_pick_kernel": 0, "accept_estimate_kernel": 0,
            "select_batch_kernel": 0}
     kernels = {}
     for n, t_us in us.items():
@@ -223,8 +223,7 @@ def main():
                 "algorithmic_bytes": alg[dominant]}
     metric_kernel = "verify_rows_kernel"
     mk_gbs = alg[metric_kernel] / us[metric_kernel] * 1e-3
-    verify_call_us = (us["verify_rows_kernel"] + us["verify_accept_kernel"] + us["verify_mass_kernel"]
-                      + us["verify_pick_kernel"])
+    verify_call_us = us["verify_rows_kernel"] + us["verify_mass_kernel"] + us["verify_pick_kernel"]
 
     # ---- correctness on the timed buffers + CPU oracle baseline (copy 0)
     step(0, seed=0)

@@ -82,11 +82,10 @@ enum {
   SV_KERNEL_ROW_STATS = 0,
   SV_KERNEL_ACCEPT_ESTIMATE = 1,
   SV_KERNEL_SELECT_LENGTH = 2,
-  SV_KERNEL_VERIFY_ROWS = 3,    /* first kernel of sv_verify_sample: row normalisers   */
-  SV_KERNEL_VERIFY_ACCEPT = 4,  /* second: acceptance ratios, accept count, sampling plan */
-  SV_KERNEL_VERIFY_MASS = 5,    /* third: chunk masses of the sampled row                 */
-  SV_KERNEL_VERIFY_PICK = 6,    /* fourth: chunk scan, LDS prefix scan, token             */
-  SV_KERNEL_COUNT = 7
+  SV_KERNEL_VERIFY_ROWS = 3,    /* first kernel of sv_verify_sample: row normalisers          */
+  SV_KERNEL_VERIFY_MASS = 4,    /* second: accept decision, chunk masses of the sampled row    */
+  SV_KERNEL_VERIFY_PICK = 5,    /* third: chunk scan, LDS prefix scan, token                   */
+  SV_KERNEL_COUNT = 6
 };
 
 /* Human-readable name of a status code (static string, never NULL). */

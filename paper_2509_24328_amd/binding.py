@@ -32,7 +32,7 @@ EXPORTS = ("sv_strerror", "sv_workspace_bytes", "sv_row_stats", "sv_accept_estim
            "sv_warp_compact", "sv_row_stats_sparse", "sv_verify_sample_sparse", "sv_uniforms",
            "sv_accept_ratio_sparse")
 (SV_KERNEL_ROW_STATS, SV_KERNEL_ACCEPT_ESTIMATE, SV_KERNEL_SELECT_LENGTH, SV_KERNEL_VERIFY_ROWS,
- SV_KERNEL_VERIFY_ACCEPT, SV_KERNEL_VERIFY_MASS, SV_KERNEL_VERIFY_PICK, SV_KERNEL_COUNT) = range(8)
+ SV_KERNEL_VERIFY_MASS, SV_KERNEL_VERIFY_PICK, SV_KERNEL_COUNT) = range(7)
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2509_24328_amd.build` "

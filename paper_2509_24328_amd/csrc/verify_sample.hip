@@ -2,7 +2,7 @@
 // prefix of every sequence (Sec. 4.2 last paragraph of the SV paper; the
 // accept / residual / bonus rule is the standard speculative-sampling one).
 //
-// Four kernels on the caller's stream:
+// Three kernels on the caller's stream:
 //
 //  1. verify_rows_kernel   1..8 workgroups per logit row that the step needs
 //     (target rows 0..gamma_b, draft rows 0..gamma_b-1 of every sequence).
@@ -11,15 +11,17 @@
 //     of the drafted token.  Rows outside the verification length exit without
 //     reading.  HBM-bound: V * elem_size bytes per row.
 //
-//  2. verify_accept_kernel  one wavefront per sequence, one lane per drafted
-//     position (k <= 64): folds the row partials, forms the acceptance ratios
-//     in fp64, draws the Philox uniforms, counts the leading accepts and
-//     writes the accepted tokens and the plan of the sampling stage.
+//  2. verify_mass_kernel   grid (chunks, B).  First the accept decision of the
+//     sequence, by one wavefront with one lane per drafted position (k <= 64):
+//     folds the row partials, forms the acceptance ratios in fp64, draws the
+//     Philox uniforms and counts the leading accepts.  Every workgroup of a
+//     sequence does this for itself (a few hundred bytes and two fp64
+//     logarithms: less than a kernel boundary costs); the one of chunk 0 writes
+//     the accepted tokens and the plan of the sampling stage.  Then the
+//     workgroup sums its 8192-entry chunk of the sampling row: residual
+//     max(0, P_t - P_d) and P_t.  Touches B rows (pairs).
 //
-//  3. verify_mass_kernel   grid (chunks, B): sums its 8192-entry chunk of the
-//     sampling row: residual max(0, P_t - P_d) and P_t.  Touches B rows (pairs).
-//
-//  4. verify_pick_kernel   one workgroup per sequence: scans the chunk masses in
+//  3. verify_pick_kernel   one workgroup per sequence: scans the chunk masses in
 //     order (fp64), locates the chunk holding u' * W, stages that chunk's
 //     weights in LDS and finds the token with a block prefix scan.
 //
@@ -234,12 +236,14 @@ struct alignas(16) Plan {
 
 static_assert(sizeof(Plan) == 32, "workspace carve-up reserves 32 bytes per sequence");
 
-// grid (B), one wavefront: accept count of the sequence in fp64 (one lane per
-// drafted position, k <= 64), its flags, and the plan for the sampling stage.
+// Accept count of sequence b in fp64, its flags, and the plan for the sampling
+// stage.  Run by one whole wavefront (lane i = drafted position i, k <= 64);
+// every workgroup of the mass kernel that works on sequence b calls it and gets
+// the same plan, the one with `publish` set also writes the accepted tokens,
+// the ratios, the accept count and the plan itself for the pick kernel.
 template <int DT>
-__global__ __launch_bounds__(kWave) void verify_accept_kernel(VerifyArgs a) {
-  const int b = blockIdx.x;
-  const int i = threadIdx.x;
+__device__ __forceinline__ void accept_plan(const VerifyArgs& a, const int b, const int i, const bool publish,
+                                            Plan* plan_out) {
   const int k = a.k, V = a.V;
   const int g = gamma_of(a, b);
   const bool evaluated = i < g;
@@ -274,38 +278,61 @@ __global__ __launch_bounds__(kWave) void verify_accept_kernel(VerifyArgs a) {
   // flags of the positions that were actually evaluated: 0..min(n, g-1)
   if (!(evaluated && i <= n)) fl = 0;
   for (int off = 32; off >= 1; off >>= 1) fl |= __shfl_xor(fl, off, kWave);
-  if (a.ratio && i < k) a.ratio[b * k + i] = (evaluated && i <= n) ? (float)rho : __builtin_nanf("");
-  int32_t* out = a.out_tokens + (size_t)b * (k + 1);
-  for (int j = i; j <= k; j += kWave) out[j] = (j < n) ? a.x[b * k + j] : -1;
-  if (i == n) {                                   // the lane of the sampled position writes the plan
+  if (publish) {
+    if (a.ratio && i < k) a.ratio[b * k + i] = (evaluated && i <= n) ? (float)rho : __builtin_nanf("");
+    int32_t* out = a.out_tokens + (size_t)b * (k + 1);
+    for (int j = i; j <= k; j += kWave) out[j] = (j < n) ? a.x[b * k + j] : -1;
+  }
+  // the plan of position n, from the values of lane n (position n = 64, the bonus
+  // row of a fully accepted k = 64, has no lane: lane 0 forms them itself)
+  double lse_t_n, lse_d_n;
+  int have_target_n;
+  if (n < kWave) {
+    lse_t_n = __shfl(lse_t, n, kWave);
+    lse_d_n = __shfl(lse_d, n, kWave);
+    have_target_n = __shfl((int)have_target, n, kWave);
+  } else {
+    lse_t_n = lse_from_ms(target_ms(a, b, n), a.sc_t);
+    lse_d_n = __builtin_nan("");
+    have_target_n = target_row<DT>(a, b, n) != nullptr;
+  }
+  if (i == 0) {
     uint32_t flags = fl;
     bool resid = n < g;
-    const bool target_ok = have_target && !isnan(lse_t);
-    if (resid && isnan(lse_d)) {                  // unusable draft row: draw from the target instead
+    const bool target_ok = have_target_n && !isnan(lse_t_n);
+    if (resid && isnan(lse_d_n)) {                // unusable draft row: draw from the target instead
       resid = false;
       flags |= SV_FLAG_BAD_ROW | SV_FLAG_RESIDUAL_FALLBACK;
     }
     if (!target_ok) flags |= SV_FLAG_BAD_ROW;
     Plan pl;
-    pl.lse_t = lse_t; pl.lse_d = resid ? lse_d : 0.0; pl.n = n; pl.flags = flags;
+    pl.lse_t = lse_t_n; pl.lse_d = resid ? lse_d_n : 0.0; pl.n = n; pl.flags = flags;
     pl.resid = resid ? 1 : 0; pl.target_ok = target_ok ? 1 : 0;
-    a.ws.plan[b] = pl;
-    a.n_accept[b] = n;
+    *plan_out = pl;
+    if (publish) {
+      a.ws.plan[b] = pl;
+      a.n_accept[b] = n;
+    }
   }
 }
 
 struct MassShared {
   BlockScratch red;
+  Plan plan;
 };
 
-// grid (chunks, B): residual and target mass of one chunk of the sampling row.
+// grid (chunks, B): the accept decision of the sequence (every workgroup forms it for
+// itself, chunk 0 publishes it), then the residual and target mass of one chunk of the
+// sampling row.
 template <int DT, bool CUT>
 __global__ __launch_bounds__(kSampleThreads) void verify_mass_kernel(VerifyArgs a) {
   __shared__ MassShared sh;
   const int b = blockIdx.y, c = blockIdx.x, C = gridDim.x;
   const int tid = threadIdx.x;
   const int V = a.V;
-  const Plan pl = a.ws.plan[b];
+  if (tid < kWave) accept_plan<DT>(a, b, tid, c == 0, &sh.plan);
+  __syncthreads();
+  const Plan pl = sh.plan;
   const int n = pl.n;
   const bool target_ok = pl.target_ok != 0, resid = pl.resid != 0;
   const void* row_t = target_row<DT>(a, b, n);
@@ -522,11 +549,6 @@ static int launch_verify(const VerifyArgs& a, hipStream_t st) {
   {
     TapScope tap(SV_KERNEL_VERIFY_ROWS, st);
     hipLaunchKernelGGL((verify_rows_kernel<DT, CUT>), dim3(rows * a.split), dim3(kRowsThreads), 0, st, a);
-  }
-  if (launch_status() != SV_OK) return SV_ERR_LAUNCH;
-  {
-    TapScope tap(SV_KERNEL_VERIFY_ACCEPT, st);
-    hipLaunchKernelGGL(verify_accept_kernel<DT>, dim3(a.B), dim3(kWave), 0, st, a);
   }
   if (launch_status() != SV_OK) return SV_ERR_LAUNCH;
   const int C = n_chunks(a.V);

@@ -186,3 +186,20 @@ def test_finite_stand_ins_for_minus_inf(V, dtype, mask):
     gotv, refv = _run_verify(z_t, z_d, x, seed=11, step=2) if dtype == torch.float32 else (None, None)
     if gotv is not None:
         H.assert_verify(gotv, refv, 3)
+
+
+def test_longest_draft_fully_accepted():
+    """k = 64 is the longest draft the verification accepts; when all 64 tokens are accepted
+    the sampled position is the bonus row, number 64."""
+    B, k, V = 3, 64, 500
+    z_t, z_d, z_c, x = _case(B=B, k=k, V=V, seed=64)
+    z_d[0] = z_t[0, :k]                    # identical models: every ratio is 1
+    z_d[2] = z_t[2, :k]
+    x[0] = np.argmax(z_d[0], axis=-1)
+    x[2] = np.argmax(z_d[2], axis=-1)
+    gamma = np.array([64, 64, 37], dtype=np.int32)
+    for g in (None, gamma):
+        got, ref = _run_verify(z_t, z_d, x, gamma=g, seed=5, step=9)
+        H.assert_verify(got, ref, k)
+        assert ref["n_accept"][0] == 64 and got["tokens"][0, 64] >= 0
+        assert ref["n_accept"][2] == (64 if g is None else 37)
