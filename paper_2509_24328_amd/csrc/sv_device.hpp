@@ -258,14 +258,39 @@ __device__ __forceinline__ double kappa_l32(const MS& r, const float L = kL32) {
   return (double)ref_of(r.m, L) + log2(r.s);
 }
 
-// Fold the `split` partial normalisers of one row (consecutive entries).
-__device__ __forceinline__ MS fold_parts(const float* m, const double* s, int split, const float L = kL32) {
+// Fold `n` partial normalisers (consecutive entries).
+__device__ __forceinline__ MS fold_parts(const float* m, const double* s, int n, const float L = kL32) {
   MS r;
   r.m = m[0];
-  for (int p = 1; p < split; ++p) r.m = fmaxf(r.m, m[p]);
+  for (int p = 1; p < n; ++p) r.m = fmaxf(r.m, m[p]);
   const float cr = ref_of(r.m, L);
   r.s = 0.0;
-  for (int p = 0; p < split; ++p) r.s += s[p] * (double)exp2_fast(ref_of(m[p], L) - cr);
+  for (int p = 0; p < n; ++p) r.s += s[p] * (double)exp2_fast(ref_of(m[p], L) - cr);
+  return r;
+}
+
+// The same for the `split` <= kMaxParts parts of a row held in global memory:
+// all loads are issued before the first use (the loop above would pay one
+// memory latency per part).
+constexpr int kMaxParts = 8;
+
+__device__ __forceinline__ MS fold_row_parts(const float* m, const double* s, int split, const float L = kL32) {
+  float mp[kMaxParts];
+  double sp[kMaxParts];
+#pragma unroll
+  for (int p = 0; p < kMaxParts; ++p) {
+    const bool on = p < split;
+    mp[p] = on ? m[p] : -INFINITY;
+    sp[p] = on ? s[p] : 0.0;
+  }
+  MS r;
+  r.m = mp[0];
+#pragma unroll
+  for (int p = 1; p < kMaxParts; ++p) r.m = fmaxf(r.m, mp[p]);
+  const float cr = ref_of(r.m, L);
+  r.s = 0.0;
+#pragma unroll
+  for (int p = 0; p < kMaxParts; ++p) r.s += sp[p] * (double)exp2_fast(ref_of(mp[p], L) - cr);   // absent parts add 0
   return r;
 }
 

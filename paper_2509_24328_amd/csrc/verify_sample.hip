@@ -45,6 +45,7 @@ constexpr int kRowsThreads = 256;
 constexpr int kSampleThreads = 256;
 constexpr int kSeg = kChunk / kSampleThreads;   // contiguous weights per thread in the final scan
 constexpr int kMaxChunks = 2048;                // V <= kMaxChunks * kChunk
+static_assert(kMaxSplit == kMaxParts, "fold_row_parts reads up to kMaxParts partials of a row");
 
 struct VerifyArgs {
   const void* z_t;
@@ -108,11 +109,11 @@ __device__ __forceinline__ const void* draft_row(const VerifyArgs& a, int b, int
 // Normaliser of a whole row from the partials its workgroups left.
 __device__ __forceinline__ MS target_ms(const VerifyArgs& a, int b, int i) {
   const int idx = (b * (a.k + 1) + i) * a.split;
-  return fold_parts(a.ws.m_t + idx, a.ws.s_t + idx, a.split, a.sc_t.L);
+  return fold_row_parts(a.ws.m_t + idx, a.ws.s_t + idx, a.split, a.sc_t.L);
 }
 __device__ __forceinline__ MS draft_ms(const VerifyArgs& a, int b, int i) {
   const int idx = (b * a.k + i) * a.split;
-  return fold_parts(a.ws.m_d + idx, a.ws.s_d + idx, a.split, a.sc_d.L);
+  return fold_row_parts(a.ws.m_d + idx, a.ws.s_d + idx, a.split, a.sc_d.L);
 }
 
 // ---------------------------------------------------------------------------
