@@ -37,30 +37,37 @@ __device__ __forceinline__ double clean_p(float p) {
 
 // Exclusive scan of cnt[b] + 1 over b = 0..B-1 by the whole workgroup; writes
 // gamma[b] = cnt[b] and t_offsets[0..B].  cnt may live in LDS or global memory;
-// `part` holds blockDim.x ints of LDS.
+// `part` holds one int of LDS per wavefront.  Integer sums: exact in any order.
 __device__ __forceinline__ void offsets_scan(const int* cnt, int B, int32_t* gamma, int32_t* t_offsets,
                                              int* part) {
   const int tid = threadIdx.x, nt = blockDim.x;
+  const int lane = tid & (kWave - 1), wave = tid >> 6, nw = nt >> 6;
   const int q = (B + nt - 1) / nt;                    // entries per thread
   const int lo = min(tid * q, B), hi = min(lo + q, B);
   int local = 0;
   for (int b = lo; b < hi; ++b) local += cnt[b] + 1;
-  part[tid] = local;
-  __syncthreads();
-  for (int off = 1; off < nt; off <<= 1) {            // Hillis-Steele on integers (exact)
-    const int add = tid >= off ? part[tid - off] : 0;
-    __syncthreads();
-    part[tid] += add;
-    __syncthreads();
+  int incl = local;                                   // inclusive scan inside the wavefront
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {
+    const int up = __shfl_up(incl, off, kWave);
+    if (lane >= off) incl += up;
   }
-  int run = part[tid] - local;
+  if (lane == kWave - 1) part[wave] = incl;
+  __syncthreads();
+  int before = 0, total = 0;                          // wavefronts before this one, and all of them
+  for (int w = 0; w < nw; ++w) {
+    const int v = part[w];
+    if (w < wave) before += v;
+    total += v;
+  }
+  int run = before + incl - local;
   for (int b = lo; b < hi; ++b) {
     const int gb = cnt[b];
     gamma[b] = gb;
     t_offsets[b] = run;
     run += gb + 1;
   }
-  if (tid == nt - 1) t_offsets[B] = part[nt - 1];
+  if (tid == 0) t_offsets[B] = total;
 }
 
 __global__ __launch_bounds__(kSelThreads) void select_batch_kernel(
@@ -76,6 +83,16 @@ __global__ __launch_bounds__(kSelThreads) void select_batch_kernel(
   while (npad < n) npad <<= 1;
 
   SV_PHASE_MARK(0)
+  // the latencies this lane divides by after the sort: asked for now, so that the
+  // memory latency passes behind the sort
+  constexpr int kRunMax = kSelMax / kSelThreads;
+  const int R = (npad + nt - 1) / nt;                  // keys per lane in the goodput scan
+  float lat_run[kRunMax];
+#pragma unroll
+  for (int j = 0; j < kRunMax; ++j) {
+    const int idx = tid * R + j;
+    lat_run[j] = (j < R && idx < n) ? latency[idx + 1] : 1.f;
+  }
   // estimates into LDS with one round of coalesced loads
   float* p_lds = reinterpret_cast<float*>(key_i);
   for (int j = tid; j < n; j += nt) p_lds[j] = p_hat[j];
@@ -132,7 +149,6 @@ __global__ __launch_bounds__(kSelThreads) void select_batch_kernel(
     // More keys than the second buffer holds: the same merge rounds in place.  Every
     // lane first takes its keys of the round into registers and finds their new
     // positions (reading the old order), then, after a barrier, scatters them.
-    constexpr int kRunMax = kSelMax / kSelThreads;
     for (int len = k; len < n; len <<= 1) {
       double c_reg[kRunMax];
       int i_reg[kRunMax], q_reg[kRunMax];
@@ -183,8 +199,6 @@ __global__ __launch_bounds__(kSelThreads) void select_batch_kernel(
     if (tid == 0) { first_stop = n; first_open = n; }
     const int lane = tid & (kWave - 1), wave = tid >> 6;
     // every lane owns a run of R consecutive keys (R = 1 up to 1024 keys)
-    constexpr int kRunMax = kSelMax / kSelThreads;
-    const int R = (npad + nt - 1) / nt;
     double e_run[kRunMax];
     double run = 0.0;
 #pragma unroll
@@ -209,7 +223,7 @@ __global__ __launch_bounds__(kSelThreads) void select_batch_kernel(
 #pragma unroll
     for (int j = 0; j < kRunMax; ++j) {
       const int idx = tid * R + j;
-      g_run[j] = (j < R && idx < n) ? (base + e_run[j]) / (double)latency[idx + 1] : 0.0;
+      g_run[j] = (j < R && idx < n) ? (base + e_run[j]) / (double)lat_run[j] : 0.0;
     }
     double g_last = 0.0;                           // G' of the last key of the run
 #pragma unroll
