@@ -42,8 +42,9 @@
 namespace sv {
 
 constexpr int kRowsThreads = 256;
-constexpr int kSampleThreads = 256;
-constexpr int kSeg = kChunk / kSampleThreads;   // contiguous weights per thread in the final scan
+constexpr int kSampleThreads = 256;             // mass kernel: one workgroup per chunk
+constexpr int kPickThreads = 1024;              // pick kernel: one workgroup per sequence
+constexpr int kSeg = kChunk / kPickThreads;     // contiguous weights per thread in the final scan
 constexpr int kMaxChunks = 2048;                // V <= kMaxChunks * kChunk
 static_assert(kMaxSplit == kMaxParts, "fold_row_parts reads up to kMaxParts partials of a row");
 
@@ -197,9 +198,9 @@ struct ProbRow {
   }
 };
 
-// LDS position of weight p: one padding word per 32 so that threads walking
-// their own contiguous 32-entry segments hit different banks.
-__device__ __forceinline__ int skew(int p) { return p + (p >> 5); }
+// LDS position of weight p: one padding word per kSeg so that threads walking
+// their own contiguous kSeg-entry segments hit different banks.
+__device__ __forceinline__ int skew(int p) { return p + p / kSeg; }
 
 // grid (B), one wavefront: p_t(x)/p_d(x) of EVERY drafted position (profiling
 // pass: no early stop, no sampling), from the row partials of verify_rows_kernel.
@@ -372,7 +373,7 @@ __global__ __launch_bounds__(kSampleThreads) void verify_mass_kernel(VerifyArgs 
 struct PickShared {
   BlockScratch red;
   union {
-    float w[kChunk + kChunk / 32];  // weights of the located chunk (skewed)
+    float w[kChunk + kChunk / kSeg];  // weights of the located chunk (skewed)
     double mass[2 * kMaxChunks];    // before that: residual / target mass of every chunk
   };
   uint32_t flags;
@@ -382,12 +383,12 @@ struct PickShared {
   double tau_local;
   double W;
 };
-static_assert(sizeof(double) * 2 * kMaxChunks <= sizeof(float) * (kChunk + kChunk / 32), "mass fits under w");
+static_assert(sizeof(double) * 2 * kMaxChunks <= sizeof(float) * (kChunk + kChunk / kSeg), "mass fits under w");
 
 // grid (B): scan the chunk masses of the sequence, locate the chunk holding
 // u' * W, stage its weights in LDS and find the token with a block prefix scan.
 template <int DT, bool CUT>
-__global__ __launch_bounds__(kSampleThreads) void verify_pick_kernel(VerifyArgs a, int C) {
+__global__ __launch_bounds__(kPickThreads) void verify_pick_kernel(VerifyArgs a, int C) {
   __shared__ PickShared sh;
   SV_PHASE_MARK(0)
   const int b = blockIdx.x;
@@ -445,7 +446,7 @@ __global__ __launch_bounds__(kSampleThreads) void verify_pick_kernel(VerifyArgs 
     sh.use_resid = use_resid;
     sh.W = W;
     sh.flags = flags;
-    sh.found_thread = kSampleThreads;
+    sh.found_thread = kPickThreads;
   }
   __syncthreads();
   SV_PHASE_MARK(2)
@@ -476,7 +477,7 @@ __global__ __launch_bounds__(kSampleThreads) void verify_pick_kernel(VerifyArgs 
   SV_PHASE_MARK(3)
 
   // block prefix scan over contiguous per-thread segments (fp64)
-  static_assert(kSeg == 32, "skew() pads once per 32-entry segment");
+  static_assert(kSeg * kPickThreads == kChunk && (kSeg & (kSeg - 1)) == 0, "one segment per thread");
   const float* wseg = sh.w + tid * (kSeg + 1);         // this thread's segment, skewed
   double seg_sum = 0.0;
 #pragma unroll 8
@@ -505,8 +506,8 @@ __global__ __launch_bounds__(kSampleThreads) void verify_pick_kernel(VerifyArgs 
   __syncthreads();
   SV_PHASE_MARK(4)
   int owner = sh.found_thread;
-  const bool beyond = owner >= kSampleThreads;
-  if (beyond) owner = kSampleThreads - 1;
+  const bool beyond = owner >= kPickThreads;
+  if (beyond) owner = kPickThreads - 1;
   if (tid != owner) return;
 
   const double W = sh.W;
@@ -560,7 +561,7 @@ static int launch_verify(const VerifyArgs& a, hipStream_t st) {
   if (launch_status() != SV_OK) return SV_ERR_LAUNCH;
   {
     TapScope tap(SV_KERNEL_VERIFY_PICK, st);
-    hipLaunchKernelGGL((verify_pick_kernel<DT, CUT>), dim3(a.B), dim3(kSampleThreads), 0, st, a, C);
+    hipLaunchKernelGGL((verify_pick_kernel<DT, CUT>), dim3(a.B), dim3(kPickThreads), 0, st, a, C);
   }
   return launch_status();
 }
