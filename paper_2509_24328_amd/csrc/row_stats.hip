@@ -49,7 +49,7 @@ struct StatsArgs {
   float* entropy_d;   // nullable
   float* pd_x;        // nullable
   uint32_t* flags;    // nullable
-  // warped entry point only (the stash kernel is the T = 1, whole-vocabulary path)
+  // warped entry point only
   Scale sc_d, sc_c;       // exponent scales (temperatures) of the two tensors
   const float* cut_d;     // nullable: support cutoff of every draft row
   const float* cut_c;     // nullable: support cutoff of every companion row
@@ -124,11 +124,16 @@ struct MinAcc {
       acc_s += exp2_fast(fminf(ad, ac));
     }
   }
-  template <int DT>
-  __device__ __forceinline__ void add_vec(const u32x4& qd, const u32x4& qc) {
+  template <int DT, bool WARP = false>
+  __device__ __forceinline__ void add_vec(const u32x4& qd, const u32x4& qc, const float cut_d = -INFINITY,
+                                          const float cut_c = -INFINITY) {
     float fd[Elem<DT>::per_vec], fc[Elem<DT>::per_vec];
     unpack<DT>(qd, fd);
     unpack<DT>(qc, fc);
+    if (WARP) {
+#pragma unroll
+      for (int j = 0; j < Elem<DT>::per_vec; ++j) { fd[j] = cut_below(fd[j], cut_d); fc[j] = cut_below(fc[j], cut_c); }
+    }
 #pragma unroll
     for (int j = 0; j < Elem<DT>::per_vec; ++j) {
       add(fd[j], fc[j]);
@@ -223,8 +228,8 @@ __device__ __forceinline__ void load_to_lds(const u32x4* src, u32x4* lds_wave_ba
 template <bool WITH_KL>
 constexpr int reg_iters() { return WITH_KL ? 8 : 10; }
 
-template <int DT, bool WITH_KL>
-__global__ __launch_bounds__(kStashThreads) void row_stats_stash_kernel(StatsArgs a) {
+template <int DT, bool WITH_KL, bool WARP>
+__global__ __launch_bounds__(kStashThreads, 4) void row_stats_stash_kernel(StatsArgs a) {
   constexpr int kRegIters = reg_iters<WITH_KL>();
   extern __shared__ u32x4 park[];                      // [kLdsVecs] draft, then [kLdsVecs] companion
   __shared__ BlockScratch sm;
@@ -242,6 +247,24 @@ __global__ __launch_bounds__(kStashThreads) void row_stats_stash_kernel(StatsArg
   const int lds_begin = kRegIters * nt;
   const int lds_end = min(nvec, lds_begin + kLdsVecs);
   const u32x4 neg = {kNegInfWord, kNegInfWord, kNegInfWord, kNegInfWord};
+  Scale sc_d = unit_scale(), sc_c = unit_scale();
+  float cut_d = -INFINITY, cut_c = -INFINITY;
+  if (WARP) {
+    sc_d = a.sc_d; sc_c = a.sc_c;
+    if (a.cut_d) cut_d = a.cut_d[pair];
+    if (a.cut_c) cut_c = a.cut_c[pair];
+  }
+  const float Ld = sc_d.L, Lc = sc_c.L;
+  // sweep-1 step for one vector of one row
+  auto add1 = [&](Online& o, const u32x4& q, const float L, const float cut) {
+    float f[EPV];
+    unpack<DT>(q, f);
+    if (WARP) {
+#pragma unroll
+      for (int j = 0; j < EPV; ++j) f[j] = cut_below(f[j], cut);
+    }
+    o.add(f, L);
+  };
 
   // ---- sweep 1 ------------------------------------------------------------
   SV_PHASE_MARK(0)
@@ -275,43 +298,39 @@ __global__ __launch_bounds__(kStashThreads) void row_stats_stash_kernel(StatsArg
   SV_PHASE_MARK(1)
 #pragma unroll
   for (int j = 0; j < kRegIters; ++j) {                 // -inf padding adds nothing
-    float f[EPV];
-    unpack<DT>(sd[j], f); od.add(f);
+    add1(od, sd[j], Ld, cut_d);
     __builtin_amdgcn_sched_barrier(0);
-    unpack<DT>(sc[j], f); oc.add(f);
+    add1(oc, sc[j], Lc, cut_c);
     __builtin_amdgcn_sched_barrier(0);                  // one pair at a time: the parked vectors own the registers
   }
   SV_PHASE_MARK(2)
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // LDS share has landed (own lanes only: no barrier)
   for (int i = lds_begin + tid; i < lds_end; i += nt) {
-    float f[EPV];
-    unpack<DT>(park[i - lds_begin], f); od.add(f);
-    unpack<DT>(park[kLdsVecs + i - lds_begin], f); oc.add(f);
+    add1(od, park[i - lds_begin], Ld, cut_d);
+    add1(oc, park[kLdsVecs + i - lds_begin], Lc, cut_c);
   }
   SV_PHASE_MARK(3)
   {
     int i = lds_end + tid;
     for (; i + nt < nvec; i += 2 * nt) {
       const u32x4 d0 = pd[i], c0 = pc[i], d1 = pd[i + nt], c1 = pc[i + nt];
-      float f[EPV];
-      unpack<DT>(d0, f); od.add(f);
+      add1(od, d0, Ld, cut_d);
       __builtin_amdgcn_sched_barrier(0);
-      unpack<DT>(c0, f); oc.add(f);
+      add1(oc, c0, Lc, cut_c);
       __builtin_amdgcn_sched_barrier(0);
-      unpack<DT>(d1, f); od.add(f);
+      add1(od, d1, Ld, cut_d);
       __builtin_amdgcn_sched_barrier(0);
-      unpack<DT>(c1, f); oc.add(f);
+      add1(oc, c1, Lc, cut_c);
       __builtin_amdgcn_sched_barrier(0);
     }
     for (; i < nvec; i += nt) {
       const u32x4 d0 = pd[i], c0 = pc[i];
-      float f[EPV];
-      unpack<DT>(d0, f); od.add(f);
-      unpack<DT>(c0, f); oc.add(f);
+      add1(od, d0, Ld, cut_d);
+      add1(oc, c0, Lc, cut_c);
     }
   }
   SV_PHASE_MARK(4)
-  publish_pair_consts(on, mg, consts);
+  publish_pair_consts(on, mg, consts, sc_d, sc_c);
   const double lse_d = consts.lse[0], lse_c = consts.lse[1];
   const bool bad = isnan(lse_d) || isnan(lse_c);
 
@@ -325,6 +344,7 @@ __global__ __launch_bounds__(kStashThreads) void row_stats_stash_kernel(StatsArg
     acc.kc = (float)kappa_c;
     const double tail_d = kappa_d - (double)acc.kd, tail_c = kappa_c - (double)acc.kc;
     acc.delta = (float)(tail_d - tail_c);
+    acc.Ld = Ld; acc.Lc = Lc;
     {
       // walk the re-read region backwards: its end was read last in sweep 1
       const int n_rest = nvec - lds_end;
@@ -333,19 +353,19 @@ __global__ __launch_bounds__(kStashThreads) void row_stats_stash_kernel(StatsArg
         const int i0 = nvec - 1 - r, i1 = nvec - 1 - (r + nt);
         const u32x4 d0 = __builtin_nontemporal_load(pd + i0), c0 = __builtin_nontemporal_load(pc + i0),
                     d1 = __builtin_nontemporal_load(pd + i1), c1 = __builtin_nontemporal_load(pc + i1);
-        acc.template add_vec<DT>(d0, c0);
+        acc.template add_vec<DT, WARP>(d0, c0, cut_d, cut_c);
         __builtin_amdgcn_sched_barrier(0);
-        acc.template add_vec<DT>(d1, c1);
+        acc.template add_vec<DT, WARP>(d1, c1, cut_d, cut_c);
         __builtin_amdgcn_sched_barrier(0);
       }
       for (; r < n_rest; r += nt) {
         const int i0 = nvec - 1 - r;
-        acc.template add_vec<DT>(pd[i0], pc[i0]);
+        acc.template add_vec<DT, WARP>(pd[i0], pc[i0], cut_d, cut_c);
       }
     }
     SV_PHASE_MARK(6)
     for (int i = lds_begin + tid; i < lds_end; i += nt)
-      acc.template add_vec<DT>(park[i - lds_begin], park[kLdsVecs + i - lds_begin]);
+      acc.template add_vec<DT, WARP>(park[i - lds_begin], park[kLdsVecs + i - lds_begin], cut_d, cut_c);
     SV_PHASE_MARK(7)
 #pragma unroll
     for (int j = 0; j < kRegIters; ++j) {               // -inf padding: 2^-inf = 0
@@ -353,7 +373,7 @@ __global__ __launch_bounds__(kStashThreads) void row_stats_stash_kernel(StatsArg
       // floats of sweep 1 are kept alive for reuse and spill
       asm volatile("" : "+v"(sd[j].x), "+v"(sd[j].y), "+v"(sd[j].z), "+v"(sd[j].w));
       asm volatile("" : "+v"(sc[j].x), "+v"(sc[j].y), "+v"(sc[j].z), "+v"(sc[j].w));
-      acc.template add_vec<DT>(sd[j], sc[j]);
+      acc.template add_vec<DT, WARP>(sd[j], sc[j], cut_d, cut_c);
       __builtin_amdgcn_sched_barrier(0);
     }
     SV_PHASE_MARK(8)
@@ -371,7 +391,7 @@ __global__ __launch_bounds__(kStashThreads) void row_stats_stash_kernel(StatsArg
     }
   }
   SV_PHASE_MARK(9)
-  if (tid == 0) stats_epilogue<DT, WITH_KL>(a, pair, pd, pc, lse_d, lse_c, S, KL, H_d);
+  if (tid == 0) stats_epilogue<DT, WITH_KL, WARP>(a, pair, pd, pc, lse_d, lse_c, S, KL, H_d, cut_d, cut_c);
 }
 
 template <int DT, bool WITH_KL, bool WARP>
@@ -437,11 +457,6 @@ __global__ __launch_bounds__(kStatsThreads) void row_stats_kernel(StatsArgs a) {
 template <int DT, bool WITH_KL, bool WARP>
 static int launch_stats(const StatsArgs& a, bool rows_aligned, hipStream_t st) {
   const dim3 grid(a.B * a.k);
-  if (WARP) {
-    TapScope tap(SV_KERNEL_ROW_STATS, st);
-    hipLaunchKernelGGL((row_stats_kernel<DT, WITH_KL, true>), grid, dim3(kStatsThreads), 0, st, a);
-    return launch_status();
-  }
   if (rows_aligned) {
     // more than 64 KB of dynamic LDS has to be allowed once per kernel and device
     constexpr int kMaxDevices = 64;
@@ -449,16 +464,16 @@ static int launch_stats(const StatsArgs& a, bool rows_aligned, hipStream_t st) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return SV_ERR_LAUNCH;
     if (dev < 0 || dev >= kMaxDevices || !allowed[dev]) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(&row_stats_stash_kernel<DT, WITH_KL>),
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(&row_stats_stash_kernel<DT, WITH_KL, WARP>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kStashLdsBytes) != hipSuccess)
         return SV_ERR_LAUNCH;
       if (dev >= 0 && dev < kMaxDevices) allowed[dev] = true;
     }
     TapScope tap(SV_KERNEL_ROW_STATS, st);
-    hipLaunchKernelGGL((row_stats_stash_kernel<DT, WITH_KL>), grid, dim3(kStashThreads), kStashLdsBytes, st, a);
+    hipLaunchKernelGGL((row_stats_stash_kernel<DT, WITH_KL, WARP>), grid, dim3(kStashThreads), kStashLdsBytes, st, a);
   } else {
     TapScope tap(SV_KERNEL_ROW_STATS, st);
-    hipLaunchKernelGGL((row_stats_kernel<DT, WITH_KL, false>), grid, dim3(kStatsThreads), 0, st, a);
+    hipLaunchKernelGGL((row_stats_kernel<DT, WITH_KL, WARP>), grid, dim3(kStatsThreads), 0, st, a);
   }
   return launch_status();
 }
