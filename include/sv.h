@@ -322,6 +322,10 @@ int sv_verify_sample_warped(const void* z_t, const int32_t* t_offsets_or_null, i
  *   lse    [rows] float        out  log-sum-exp of z / T over the kept set (NaN: bad row / -1)
  *   cutoff_or_null, flags_or_null   as in sv_warp_cutoffs
  * 1 <= cap <= SV_SUPPORT_MAX_CAP.  Entries beyond n_r are left untouched.
+ * Rows are independent, so tensors that share the hyper-parameters and lie one
+ * after the other in memory (draft and companion logits, say) can go through
+ * one call with rows = the sum: a launch with more than two rows per compute
+ * unit overlaps the decisions of some rows with the sweeps of others.
  */
 int sv_warp_compact(const void* z, int rows, int V, int dtype,
                     float temperature, int top_k, float top_p, int cap,
