@@ -163,8 +163,11 @@ int sv_select_length(const float* p_hat, int B, int k,
  * each sequence (Sec. 4.2, last paragraph; the rule itself is Leviathan et al.'s):
  * for i < gamma[b] accept x[b,i] iff u_i < p_t(x)/p_d(x); n = leading accepts;
  * then draw one token at position n: from the normalised residual
- * max(0, p_t - p_d) if n < gamma[b], else from the target distribution of
- * position gamma[b] (bonus token / position the target generates itself).
+ * max(0, p_t - p_d) if n < gamma[b] (from p_t itself, with
+ * SV_FLAG_RESIDUAL_FALLBACK, when the residual's mass is at most 1e-6: the two
+ * distributions then agree to within what float32 probabilities resolve), else
+ * from the target distribution of position gamma[b] (bonus token / position
+ * the target generates itself).
  * Draws are inverse-CDF over ascending token id: the smallest v whose
  * inclusive cumulative weight exceeds u' * W.
  * Uniforms: Philox-4x32-10, key = (seed lo, seed hi), counter = (i, b, 0, step);
