@@ -99,7 +99,10 @@ def close(got, ref, rel=REL, abs_floor=0.0):
 def assert_row_stats(got, ref, with_kl=True):
     """fp32 stats within 1e-5 relative.  TV = 1 - S and KL are sums of
     probability differences whose entries carry ~1e-7 relative error each, so
-    near zero they get an absolute floor of 2e-6."""
+    near zero they get an absolute floor: 2e-6 for KL and the entropy, 5e-6 for
+    TV (on a flat row every term has the same exponent, near -17 at 1e5 entries,
+    so the rounding of that exponent, up to 6.6e-7 relative, and of the equal
+    additions no longer average out: 3.7e-6 has been observed)."""
     for name in ("lse_d", "lse_c"):
         ok = close(got[name], ref[name], REL, 1e-6)
         assert ok.all(), (name, got[name][~ok], ref[name][~ok])
@@ -108,7 +111,7 @@ def assert_row_stats(got, ref, with_kl=True):
     ok = close(got["A"], ref["A"], REL, 1e-30)
     assert ok.all(), ("A", got["A"][~ok], ref["A"][~ok])
     tv = np.maximum(0, 1 - got["S"].astype(np.float64))
-    ok = close(tv, ref["TV"], REL, 2e-6)
+    ok = close(tv, ref["TV"], REL, 5e-6)
     assert ok.all(), ("TV", tv[~ok], ref["TV"][~ok])
     ok = close(got["pd_x"], ref["pd_x"], REL, 1e-37)
     assert ok.all(), ("pd_x", got["pd_x"][~ok], ref["pd_x"][~ok])
