@@ -68,8 +68,9 @@ struct alignas(16) WarpShared {
   union {
     struct {                   // general path
       uint32_t cnt[kBins];
-      float mass[kBins];
-      float mass0[kBins];      // level-0 masses, kept for the top-p pass
+      double mass[kBins];      // fp64: a bin may collect 1e5 nearly equal terms (a flat row at a
+                               // high temperature), whose fp32 sum would be off by 1e-4
+      double mass0[kBins];     // level-0 masses, kept for the top-p pass
     };
     struct {                   // candidate path
       uint64_t key[kCand];     // (order key of the value, ~token id): sorted descending
@@ -98,7 +99,7 @@ __device__ __forceinline__ void scan_bins(WarpShared& sh, int nbins, bool by_cou
   int found = 0;
   for (int d = nbins - 1; d >= 0; --d) {
     const uint32_t c = sh.cnt[d];
-    const double mm = (double)sh.mass[d];
+    const double mm = sh.mass[d];
     const bool hit = by_count ? (c_above + c >= k_rem) : (m_above + mm >= target && c > 0);
     if (!by_count && c > 0 && total_for_tie > 0.0) {
       // the candidate group boundaries at this level: flag a decision that sits on P
@@ -126,14 +127,14 @@ __device__ __noinline__ float general_cutoff(const void* row, int V, float lt, i
 
   // histogram sweep over the entries under `prefix` at `level`, optionally only z >= floor_v
   auto histogram = [&](int level, uint32_t prefix, float floor_v) {
-    for (int d = tid; d < kBins; d += blockDim.x) { sh.cnt[d] = 0; sh.mass[d] = 0.f; }
+    for (int d = tid; d < kBins; d += blockDim.x) { sh.cnt[d] = 0; sh.mass[d] = 0.0; }
     __syncthreads();
-    visit_range<DT, false, 4>(row, nullptr, 0, V, [&](int, float v, float) {
+    visit_range<DT, false, 1>(row, nullptr, 0, V, [&](int, float v, float) {   // (one vector at a time: few registers)
       const uint32_t key = okey(v);
       if (under_prefix(key, prefix, level) && v >= floor_v) {
         const uint32_t d = digit_of(key, level);
         atomicAdd(&sh.cnt[d], 1u);
-        atomicAdd(&sh.mass[d], exp2_fast(__builtin_fmaf(v, lt, -c_ref)));
+        atomicAdd(&sh.mass[d], (double)exp2_fast(__builtin_fmaf(v, lt, -c_ref)));
       }
     });
     __syncthreads();
@@ -145,7 +146,7 @@ __device__ __noinline__ float general_cutoff(const void* row, int V, float lt, i
   double total0 = 0.0;
   {
     double part = 0.0;
-    for (int d = tid; d < kBins; d += blockDim.x) part += (double)sh.mass[d];
+    for (int d = tid; d < kBins; d += blockDim.x) part += sh.mass[d];
     total0 = block_sum_f64(part, sh.red);
   }
 
@@ -181,11 +182,11 @@ __device__ __noinline__ float general_cutoff(const void* row, int V, float lt, i
     const double target = (double)top_p * total_k;
     // level 0 from the saved masses: digits above dk0 survive whole, dk0 in part, below not at all
     for (int d = tid; d < kBins; d += blockDim.x) {
-      float mm = sh.mass0[d];
-      uint32_t c = mm > 0.f ? 1u : 0u;             // counts only mark non-empty bins here
+      double mm = sh.mass0[d];
+      uint32_t c = mm > 0.0 ? 1u : 0u;             // counts only mark non-empty bins here
       if (use_k) {
-        if (d < dk0) { mm = 0.f; c = 0u; }
-        else if (d == dk0) { mm = (float)surv_in_dk0; c = 1u; }
+        if (d < dk0) { mm = 0.0; c = 0u; }
+        else if (d == dk0) { mm = surv_in_dk0; c = 1u; }
       }
       sh.mass[d] = mm;
       sh.cnt[d] = c;

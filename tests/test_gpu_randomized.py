@@ -248,3 +248,17 @@ def test_random_adversarial_values_warped(block):
     print(f"\n  adversarial warped block {block}: {n_seq} sequence checks, {n_sparse} compacted pairs, "
           f"near-tie {n_tie}, out of range {n_skipped}", flush=True)
     assert n_seq >= 40 and n_sparse >= 40
+
+
+def test_flat_companion_row_with_a_wide_support():
+    """A case the sweeps above once found: companion logits near 1e4 at temperature 1000 with
+    top-p 0.9 (115 384 of 128 256 tokens kept, each with a mass of 8.7e-6).  Bin masses summed
+    in fp32 put the cutoff a dozen entries off, which moved S by 1e-4."""
+    rng = np.random.default_rng(90086)
+    V = int(rng.choice([70000, 152064, 128256, 32000]))
+    B, k = int(rng.integers(1, 4)), int(rng.integers(1, 5))
+    assert (V, B, k) == (128256, 3, 2)
+    z_t, z_d, z_c, _ = _adversarial_rows(rng, B, k, V, False)
+    par = {"t": (float(np.float32(1.3)), 2, 0.5), "d": (float(np.float32(1.3)), 20, 0.999), "c": (1000.0, 0, 0.9)}
+    n_seq, n_sparse, _ = _warped_case(rng, dict(t=z_t, d=z_d, c=z_c), torch.float32, par, with_kl=False)
+    assert n_seq > 0

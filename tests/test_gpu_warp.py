@@ -81,3 +81,22 @@ def test_ties_negative_rows_masked_and_bad_rows():
         t = torch.from_numpy(z).to(dtype)
         for T, K, Pp in ((1.0, 10, 1.0), (0.7, 0, 0.9), (0.7, 300, 0.5), (1.0, 4999, 0.9999)):
             _compare(t, T, K, Pp)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_wide_supports_of_nearly_flat_rows(dtype):
+    """Top-p over a nearly flat distribution keeps most of the vocabulary: 1e5 nearly equal
+    masses have to add up to P exactly enough to stop at the right entry (the cumulative mass
+    moves by 8e-6 per entry at V = 128256, less than fp32 sums of that many terms resolve)."""
+    rng = np.random.default_rng(12)
+    V = 128256
+    z = np.empty((4, V), dtype=np.float32)
+    z[0] = 1e4 + 5.0 * rng.standard_normal(V)        # flat after T = 1000
+    z[1] = 0.01 * rng.standard_normal(V)             # flat at any temperature
+    z[2] = rng.standard_normal(V)
+    z[3] = np.round(8 * rng.standard_normal(V)) / 8  # flat-ish with ties
+    t = torch.from_numpy(z).to(dtype)
+    ties = 0
+    for T, K, Pp in ((1000.0, 0, 0.9), (1.0, 0, 0.5), (100.0, 100000, 0.999), (10.0, 0, 0.01)):
+        ties += _compare(t, T, K, Pp)
+    assert ties <= 8
