@@ -77,6 +77,9 @@ enum {
 /* Largest per-row capacity of a compacted support (sv_warp_compact). */
 #define SV_SUPPORT_MAX_CAP 1024
 
+/* Device scratch that sv_verify_sample_static holds on every GPU it runs on. */
+#define SV_STATIC_SCRATCH_BYTES (1 << 20)
+
 /* Kernels of the library, for sv_set_timing_events. */
 enum {
   SV_KERNEL_ROW_STATS = 0,
@@ -192,6 +195,28 @@ int sv_verify_sample(const void* z_t, const int32_t* t_offsets_or_null, int n_t_
                      int32_t* out_tokens, int32_t* n_accept, uint32_t* flags,
                      float* ratio_or_null,
                      void* ws, size_t ws_bytes, sv_stream_t stream);
+
+/*
+ * sv_verify_sample for callers that cannot allocate device memory (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc) and
+ * so have no workspace to pass: the same kernels run on a scratch array of
+ * SV_STATIC_SCRATCH_BYTES that the library holds in device memory on every GPU
+ * it is used on, until the process ends.  Arguments, outputs, flags and errors
+ * are those of sv_verify_sample without ws / ws_bytes.  The call itself
+ * allocates and frees nothing.
+ * Limit: sv_workspace_bytes(B, k, V, dtype) <= SV_STATIC_SCRATCH_BYTES (the
+ * headline shape B=64, k=8, V=152064 needs 36 KB), else SV_ERR_TOO_LARGE.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on
+ * one GPU (two streams, two host threads) race and give undefined results;
+ * calls that follow each other on one stream are fine, nothing in the array
+ * has to survive from one call to the next or to start at zero.
+ */
+int sv_verify_sample_static(const void* z_t, const int32_t* t_offsets_or_null, int n_t_rows,
+                            const void* z_d, const int32_t* x, const int32_t* gamma_or_null,
+                            int B, int k, int V, int dtype,
+                            uint64_t seed, uint32_t step,
+                            int32_t* out_tokens, int32_t* n_accept, uint32_t* flags,
+                            float* ratio_or_null, sv_stream_t stream);
 
 /* ------------------------------------------------------------------------
  * Profile construction and information gain: the offline pass that produces

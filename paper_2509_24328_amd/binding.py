@@ -30,12 +30,13 @@ EXPORTS = ("sv_strerror", "sv_workspace_bytes", "sv_row_stats", "sv_accept_estim
            "sv_quantile_edges", "sv_profile_accumulate", "sv_profile_finalize", "sv_warp_cutoffs",
            "sv_row_stats_warped", "sv_verify_sample_warped",
            "sv_warp_compact", "sv_row_stats_sparse", "sv_verify_sample_sparse", "sv_uniforms",
-           "sv_accept_ratio_sparse")
+           "sv_accept_ratio_sparse", "sv_verify_sample_static")
+SV_STATIC_SCRATCH_BYTES = 1 << 20
 (SV_KERNEL_ROW_STATS, SV_KERNEL_ACCEPT_ESTIMATE, SV_KERNEL_SELECT_LENGTH, SV_KERNEL_VERIFY_ROWS,
  SV_KERNEL_VERIFY_MASS, SV_KERNEL_VERIFY_PICK, SV_KERNEL_COUNT) = range(7)
 
 if not os.path.exists(LIB_PATH):
-    raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2509_24328_amd.build` "
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python paper_2509_24328_amd/build.py` "
                       "(or __graft_entry__.build()); there is no fallback path")
 
 lib = ctypes.CDLL(LIB_PATH)
@@ -54,6 +55,9 @@ lib.sv_select_length.argtypes = [_vp, _i, _i, _vp, _i, _i, _vp, _vp, _vp, _vp]
 lib.sv_verify_sample.restype = _i
 lib.sv_verify_sample.argtypes = [_vp, _vp, _i, _vp, _vp, _vp, _i, _i, _i, _i, ctypes.c_uint64,
                                  ctypes.c_uint32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+lib.sv_verify_sample_static.restype = _i
+lib.sv_verify_sample_static.argtypes = [_vp, _vp, _i, _vp, _vp, _vp, _i, _i, _i, _i, ctypes.c_uint64,
+                                        ctypes.c_uint32, _vp, _vp, _vp, _vp, _vp]
 lib.sv_accept_ratio.restype = _i
 lib.sv_accept_ratio.argtypes = [_vp, _i, _vp, _vp, _i, _i, _i, _i, _vp, _vp, _vp, _sz, _vp]
 lib.sv_quantile_edges.restype = _i
@@ -165,6 +169,15 @@ def sv_verify_sample(z_t, t_offsets, z_d, x, gamma, seed, step, out_tokens, n_ac
                                 B, k, V, _dtype_tag(z_d), seed, step, _ptr(out_tokens), _ptr(n_accept),
                                 _ptr(flags), _ptr(ratio), _ptr(ws), 0 if ws is None else ws.numel(),
                                 _stream(stream)))
+
+
+def sv_verify_sample_static(z_t, t_offsets, z_d, x, gamma, seed, step, out_tokens, n_accept, flags,
+                            ratio=None, stream=None):
+    B, k, V = z_d.shape
+    n_t_rows = z_t.shape[0] if t_offsets is not None else 0
+    _check(lib.sv_verify_sample_static(_ptr(z_t), _ptr(t_offsets), n_t_rows, _ptr(z_d), _ptr(x), _ptr(gamma),
+                                       B, k, V, _dtype_tag(z_d), seed, step, _ptr(out_tokens), _ptr(n_accept),
+                                       _ptr(flags), _ptr(ratio), _stream(stream)))
 
 
 def sv_set_timing_events(kernel, start_event, stop_event):

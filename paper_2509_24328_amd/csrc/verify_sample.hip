@@ -29,6 +29,7 @@
 // chunk masses): device-scope fences inside a kernel were measured to cost far
 // more than a launch on this part.
 #include <algorithm>
+#include <mutex>
 
 #include "sv_device.hpp"
 #include "sv_host.hpp"
@@ -605,7 +606,52 @@ static int verify_sample_checked(const void* z_t, const int32_t* t_offsets, int 
   return dtype == SV_F32 ? launch_verify<DT_F32, false>(a, st) : launch_verify<DT_BF16, false>(a, st);
 }
 
+// ---------------------------------------------------------------------------
+// Scratch of the entry point that takes no workspace: one array per GPU, held
+// until the process ends.  In host code the array's name is only a stand-in;
+// the address on the current device comes from hipGetSymbolAddress, once per
+// device, and only that pointer is ever handed to a kernel.
+// ---------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[SV_STATIC_SCRATCH_BYTES];
+
+static int static_scratch(void** out) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* ptr_of[kMaxDevices] = {};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SV_ERR_LAUNCH;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr_of[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return SV_ERR_LAUNCH;
+    ptr_of[dev] = p;
+  }
+  *out = ptr_of[dev];
+  return SV_OK;
+}
+
 }  // namespace sv
+
+extern "C" int sv_verify_sample_static(const void* z_t, const int32_t* t_offsets_or_null, int n_t_rows,
+                                       const void* z_d, const int32_t* x, const int32_t* gamma_or_null,
+                                       int B, int k, int V, int dtype, uint64_t seed, uint32_t step,
+                                       int32_t* out_tokens, int32_t* n_accept, uint32_t* flags,
+                                       float* ratio_or_null, sv_stream_t stream) {
+  using namespace sv;
+  // sizes first, so that a shape beyond the scratch is told apart from other errors
+  SV_REQUIRE(dtype == SV_F32 || dtype == SV_BF16, SV_ERR_DTYPE);
+  SV_REQUIRE(B >= 0 && k >= 1 && V >= 1, SV_ERR_INVALID_ARG);
+  SV_REQUIRE(k <= SV_MAX_K && n_chunks(V) <= kMaxChunks, SV_ERR_TOO_LARGE);
+  SV_REQUIRE((long long)B * (2 * k + 1) * kMaxSplit <= 0x7fffffffLL && B <= 65535, SV_ERR_TOO_LARGE);
+  SV_REQUIRE(sv_workspace_bytes(B, k, V, dtype) <= (size_t)SV_STATIC_SCRATCH_BYTES, SV_ERR_TOO_LARGE);
+  if (B == 0) return SV_OK;
+  void* ws = nullptr;
+  const int rc = static_scratch(&ws);
+  if (rc != SV_OK) return rc;
+  return verify_sample_checked(z_t, t_offsets_or_null, n_t_rows, z_d, x, gamma_or_null, B, k, V, dtype,
+                               unit_scale(), nullptr, unit_scale(), nullptr, seed, step, out_tokens, n_accept,
+                               flags, ratio_or_null, ws, SV_STATIC_SCRATCH_BYTES, stream);
+}
 
 extern "C" int sv_verify_sample(const void* z_t, const int32_t* t_offsets_or_null, int n_t_rows,
                                 const void* z_d, const int32_t* x, const int32_t* gamma_or_null,
