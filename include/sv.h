@@ -63,8 +63,11 @@ enum {
 enum {
   SV_FLAG_BAD_ROW = 1,            /* a needed row holds NaN/+inf or no entry in range         */
   SV_FLAG_NEAR_TIE = 2,           /* |u - min(1, ratio)| < 1e-6 at an evaluated position      */
-  SV_FLAG_RESIDUAL_FALLBACK = 4,  /* residual mass <= 1e-6 / non-finite: drawn from target    */
-  SV_FLAG_NEAR_CDF_EDGE = 8,      /* sampling threshold within 1e-6 * W of a CDF edge         */
+  SV_FLAG_RESIDUAL_FALLBACK = 4,  /* residual without mass (exactly 0 / non-finite) or bad
+                                     draft row: drawn from the target distribution instead    */
+  SV_FLAG_NEAR_CDF_EDGE = 8,      /* sampling threshold within 1e-6 * W (+ 1e-6 absolute on
+                                     the dense paths, whose probabilities are float32) of an
+                                     edge of the drawn token's CDF interval                   */
   SV_FLAG_BAD_TOKEN = 16,         /* drafted token id outside [0, V)                          */
   SV_FLAG_NOT_COMPACT = 32        /* a needed row has no compact support (count < 0): the
                                      result is not valid, use the dense warped entry points   */
@@ -166,11 +169,15 @@ int sv_select_length(const float* p_hat, int B, int k,
  * each sequence (Sec. 4.2, last paragraph; the rule itself is Leviathan et al.'s):
  * for i < gamma[b] accept x[b,i] iff u_i < p_t(x)/p_d(x); n = leading accepts;
  * then draw one token at position n: from the normalised residual
- * max(0, p_t - p_d) if n < gamma[b] (from p_t itself, with
- * SV_FLAG_RESIDUAL_FALLBACK, when the residual's mass is at most 1e-6: the two
- * distributions then agree to within what float32 probabilities resolve), else
+ * max(0, p_t - p_d) if n < gamma[b], whatever its mass W > 0 (from p_t itself,
+ * with SV_FLAG_RESIDUAL_FALLBACK, only when W is exactly 0 or not finite), else
  * from the target distribution of position gamma[b] (bonus token / position
- * the target generates itself).
+ * the target generates itself).  The probabilities are float32 numbers, so a
+ * cumulative weight carries an absolute error of up to 5e-7: when the threshold
+ * u' * W lies within 1e-6 * W + 1e-6 of an edge of the drawn token's interval
+ * the token next to it may be the exact one, and SV_FLAG_NEAR_CDF_EDGE says so
+ * (always the case for residuals of mass below 2e-6, which float32
+ * probabilities do not resolve; the emitted law is within that mass of exact).
  * Draws are inverse-CDF over ascending token id: the smallest v whose
  * inclusive cumulative weight exceeds u' * W.
  * Uniforms: Philox-4x32-10, key = (seed lo, seed hi), counter = (i, b, 0, step);

@@ -49,8 +49,7 @@ from . import philox
 # Per-sequence / per-row condition bits (data-dependent, never errors).
 FLAG_BAD_ROW = 1            # a row with a NaN or no finite entry was needed
 FLAG_NEAR_TIE = 2           # |u - min(1, rho)| < NEAR_TIE_EPS at an evaluated position
-RESIDUAL_FLOOR = 1e-6       # residual mass at or below this counts as none
-FLAG_RESIDUAL_FALLBACK = 4  # residual mass <= RESIDUAL_FLOOR / non-finite; target row used instead
+FLAG_RESIDUAL_FALLBACK = 4  # residual mass exactly 0 / non-finite, or bad draft row; target row used instead
 FLAG_NEAR_CDF_EDGE = 8      # sampling threshold within CDF_EDGE_EPS * W of a CDF edge
 FLAG_BAD_TOKEN = 16         # drafted token id outside [0, V)
 
@@ -338,13 +337,14 @@ def accept_ratio(z_t_row, z_d_row, token):
 def sampling_weights(z_t_row, z_d_row=None):
     """Unnormalised sampling weights w over the vocabulary and their mass W.
 
-    With a draft row: the residual max(0, P_t - P_d).  Without: P_t itself
-    (bonus token / position the target generates on its own).  A residual whose
-    mass is not above RESIDUAL_FLOOR (P_t and P_d agree to within what fp32
-    probabilities can resolve; a rejection can still happen there when the
-    drafted token has no mass under either model), or is non-finite, falls back
-    to P_t.  Returns (w, W, flag_bits); a
-    bad target row gives (None, nan, FLAG_BAD_ROW).
+    With a draft row: the residual max(0, P_t - P_d), for any mass W > 0
+    however small (the speculative-sampling rule has no floor, and float64 has
+    no resolution limit that would call for one).  Without: P_t itself (bonus
+    token / position the target generates on its own).  Only a residual of
+    mass exactly 0 (P_t = P_d; a rejection can still happen there when the
+    drafted token has no mass under either model), a non-finite one, or a bad
+    draft row falls back to P_t.  Returns (w, W, flag_bits); a bad target row
+    gives (None, nan, FLAG_BAD_ROW).
     """
     lse_t, lp_t = log_softmax_row(upcast(z_t_row))
     if np.isnan(lse_t):
@@ -356,7 +356,7 @@ def sampling_weights(z_t_row, z_d_row=None):
         if not np.isnan(lse_d):
             w = np.maximum(0.0, p_t - np.exp(lp_d))
             W = float(np.sum(w))
-            if np.isfinite(W) and W > RESIDUAL_FLOOR:
+            if np.isfinite(W) and W > 0.0:
                 return w, W, flags
         else:
             flags |= FLAG_BAD_ROW
@@ -364,14 +364,27 @@ def sampling_weights(z_t_row, z_d_row=None):
     return p_t, float(np.sum(p_t)), flags
 
 
-def inverse_cdf(w, W, u):
+def sampling_support(z_t_row):
+    """Tokens the target gives any probability at all (P_t > 0)."""
+    _, lp_t = log_softmax_row(upcast(z_t_row))
+    return np.exp(lp_t) > 0
+
+
+def inverse_cdf(w, W, u, abs_band=0.0, support=None):
     """Token = smallest v with cumsum(w)[v] > u * W; if rounding leaves none,
     the largest v with w_v > 0.
 
     Returns (token, margin, admissible) where margin = distance of the
     threshold to the nearer end of the token's CDF interval, divided by W, and
-    admissible = ids of all positive-weight tokens whose CDF interval meets
-    [tau - eps W, tau + eps W], eps = CDF_EDGE_EPS.
+    admissible = ids of the tokens whose CDF interval meets
+    [tau - h, tau + h], h = CDF_EDGE_EPS * W + abs_band.
+
+    abs_band and support serve the comparison with an implementation whose
+    cumulative sums carry an absolute error of up to abs_band (probabilities
+    held in a narrower type): they change neither the token nor the margin.
+    With abs_band = 0 only tokens of positive weight are admissible; with
+    abs_band > 0 every token of `support` is (a weight that is 0 here can be a
+    rounding-sized positive number there), support = None meaning w > 0.
     """
     cdf = np.cumsum(w)
     tau = u * W
@@ -382,13 +395,15 @@ def inverse_cdf(w, W, u):
         y = int(np.nonzero(w > 0)[0][-1])
     lo = cdf[y - 1] if y > 0 else 0.0
     margin = min(cdf[y] - tau, tau - lo) / W
-    h = CDF_EDGE_EPS * W
+    h = CDF_EDGE_EPS * W + abs_band
     prev = np.concatenate(([0.0], cdf[:-1]))
-    adm = np.nonzero((w > 0) & (cdf >= tau - h) & (prev <= tau + h))[0]
+    can = (w > 0) if (support is None or abs_band == 0.0) else ((w > 0) | np.asarray(support))
+    adm = np.nonzero(can & (cdf >= tau - h) & (prev <= tau + h))[0]
     return y, float(margin), adm.astype(np.int64)
 
 
-def verify_sample(z_t, z_d, x, gamma=None, t_offsets=None, seed=0, step=0, uniforms=None):
+def verify_sample(z_t, z_d, x, gamma=None, t_offsets=None, seed=0, step=0, uniforms=None,
+                  cdf_abs_band=0.0):
     """One speculative-sampling verification step for B sequences.
 
     z_t : dense [B, k+1, V], or packed [sum_b (gamma_b + 1), V] with
@@ -397,9 +412,13 @@ def verify_sample(z_t, z_d, x, gamma=None, t_offsets=None, seed=0, step=0, unifo
     gamma : [B] verification lengths in 0..k (None: all k)
     uniforms : optional (u_accept [B, k], u_sample [B, k+1]) replacing the
           Philox stream (used by enumeration tests)
+    cdf_abs_band : comparison aid, see inverse_cdf: widens FLAG_NEAR_CDF_EDGE
+          and the admissible sets by an absolute band; tokens, accept counts
+          and every other output are unaffected
     Returns dict: tokens int32 [B, k+1] (-1 padded), n_accept int32 [B],
     flags uint32 [B], ratio float64 [B, k] (NaN where not evaluated),
-    margin float64 [B], admissible (list of arrays), W float64 [B],
+    margin float64 [B], admissible (list of arrays), W float64 [B] (mass of
+    the weights drawn from), resid bool [B] (drawn from a residual),
     sample_row int32 [B].
     """
     z_t = np.asarray(z_t)
@@ -423,6 +442,7 @@ def verify_sample(z_t, z_d, x, gamma=None, t_offsets=None, seed=0, step=0, unifo
     margin = np.full(B, np.nan)
     Wout = np.full(B, np.nan)
     sample_row = np.zeros(B, dtype=np.int32)
+    resid = np.zeros(B, dtype=bool)
     admissible = []
     for b in range(B):
         g = int(gamma[b])
@@ -457,11 +477,13 @@ def verify_sample(z_t, z_d, x, gamma=None, t_offsets=None, seed=0, step=0, unifo
         if w is None:
             admissible.append(np.zeros(0, dtype=np.int64))
             continue            # bad target row: no token can be drawn, stays -1
-        y, mg, adm = inverse_cdf(w, W, up)
+        resid[b] = n < g and not (fl & FLAG_RESIDUAL_FALLBACK)
+        support = sampling_support(t_row(b, n)) if cdf_abs_band > 0.0 else None
+        y, mg, adm = inverse_cdf(w, W, up, cdf_abs_band, support)
         tokens[b, n] = y
         margin[b] = mg
         admissible.append(adm)
-        if mg < CDF_EDGE_EPS:
+        if mg * W < CDF_EDGE_EPS * W + cdf_abs_band:
             flags[b] |= FLAG_NEAR_CDF_EDGE
     return dict(tokens=tokens, n_accept=n_accept, flags=flags, ratio=ratio, margin=margin,
-                admissible=admissible, W=Wout, sample_row=sample_row)
+                admissible=admissible, W=Wout, resid=resid, sample_row=sample_row)

@@ -186,7 +186,7 @@ __global__ __launch_bounds__(kWave) void verify_sample_sparse_kernel(SparseVerif
   double part = 0.0;
   for (int j = j0; j < j1; ++j) part += sample_weight(a, trow, j, resid, drow, nd);
   double W = wave_sum_f64(part);
-  if (resid && !(isfinite(W) && W > kResidualFloor)) {   // residual without mass (target mass is 1): draw from the target
+  if (resid && !(isfinite(W) && W > 0.0)) {   // residual without mass: draw from the target
     resid = false;
     fl |= SV_FLAG_RESIDUAL_FALLBACK;
     part = 0.0;
@@ -226,7 +226,7 @@ __global__ __launch_bounds__(kWave) void verify_sample_sparse_kernel(SparseVerif
       }
     }
     if (y >= 0) {
-      if (fmin(run - tau, tau - prev) / W < 1e-6) fl |= SV_FLAG_NEAR_CDF_EDGE;
+      if (fmin(run - tau, tau - prev) < kCdfEdgeRel * W) fl |= SV_FLAG_NEAR_CDF_EDGE;
     } else {
       fl |= SV_FLAG_NEAR_CDF_EDGE;               // take the last entry that carries weight
       for (int j = j1 - 1; j >= 0; --j)

@@ -15,7 +15,14 @@ struct Plan;
 constexpr int kChunk = 8192;          // vocabulary entries per sampling chunk
 constexpr size_t kWsAlign = 256;
 constexpr int kMaxSplit = 8;          // a row may be swept by up to 8 workgroups
-constexpr double kResidualFloor = 1e-6;   // residual mass (relative to the target's) at or below this: none
+// SV_FLAG_NEAR_CDF_EDGE: the sampling threshold lies within kCdfEdgeRel * W + kCdfEdgeAbs of an
+// edge of the chosen token's CDF interval.  The absolute part is the resolution of the dense
+// path's own arithmetic: its probabilities are fp32 numbers with a relative error of at most
+// 2.5e-7 each (row normaliser 1e-7, exponent rounding and v_exp_f32 1.5e-7), so a cumulative
+// sum of max(0, p_t - p_d) is off by at most 2.5e-7 * (P_t + P_d)(<= v) <= 5e-7, and so is the
+// threshold u' * W: 1e-6 between them.  Compacted supports carry fp64 probabilities: no such part.
+constexpr double kCdfEdgeRel = 1e-6;
+constexpr double kCdfEdgeAbs = 1e-6;
 
 inline hipStream_t as_stream(sv_stream_t s) { return reinterpret_cast<hipStream_t>(s); }
 

@@ -347,24 +347,26 @@ __global__ __launch_bounds__(kSampleThreads) void verify_mass_kernel(VerifyArgs 
   if (CUT) { cut_t = target_cut(a, b, n); if (resid) cut_d = draft_cut(a, b, n); }
 
   const int v0 = c * kChunk, v1 = min(V, v0 + kChunk);
-  float acc_r = 0.f, acc_t = 0.f;
+  // fp64 sums of the fp32 weights: the pick kernel forms the same weights again and adds them
+  // in another order, and the two must agree far inside the band of SV_FLAG_NEAR_CDF_EDGE
+  double acc_r = 0.0, acc_t = 0.0;
   if (target_ok) {
     if (resid) {
       visit_range<DT, true, 4>(row_t, row_d, v0, v1, [&](int, float zt, float zd) {
         if (CUT) { zt = cut_below(zt, cut_t); zd = cut_below(zd, cut_d); }
         const float p = pt.p(zt);
-        acc_t += p;
-        acc_r += fmaxf(0.f, p - pd.p(zd));
+        acc_t += (double)p;
+        acc_r += (double)fmaxf(0.f, p - pd.p(zd));
       });
     } else {
       visit_range<DT, false, 4>(row_t, nullptr, v0, v1, [&](int, float zt, float) {
         if (CUT) zt = cut_below(zt, cut_t);
-        acc_t += pt.p(zt);
+        acc_t += (double)pt.p(zt);
       });
     }
   }
-  const double mass_r = block_sum_f64((double)acc_r, sh.red);
-  const double mass_t = block_sum_f64((double)acc_t, sh.red);
+  const double mass_r = block_sum_f64(acc_r, sh.red);
+  const double mass_t = block_sum_f64(acc_t, sh.red);
   if (tid == 0) {
     a.ws.mass_r[b * C + c] = mass_r;
     a.ws.mass_t[b * C + c] = mass_t;
@@ -420,8 +422,8 @@ __global__ __launch_bounds__(kPickThreads) void verify_pick_kernel(VerifyArgs a,
     double Wr = 0.0, Wt = 0.0;
     for (int j = 0; j < C; ++j) { Wr += mr[j]; Wt += mt[j]; }
     int use_resid = resid;
-    // a residual within what fp32 probabilities can resolve of zero counts as none
-    if (target_ok && resid && !(isfinite(Wr) && Wr > kResidualFloor * Wt)) { use_resid = 0; flags |= SV_FLAG_RESIDUAL_FALLBACK; }
+    // a residual of any mass is drawn from; only one without mass (or a non-finite one) is not
+    if (target_ok && resid && !(isfinite(Wr) && Wr > 0.0)) { use_resid = 0; flags |= SV_FLAG_RESIDUAL_FALLBACK; }
     const double W = use_resid ? Wr : Wt;
     int chunk = -1;
     double tau_local = 0.0;
@@ -523,7 +525,7 @@ __global__ __launch_bounds__(kPickThreads) void verify_pick_kernel(VerifyArgs a,
   }
   uint32_t fl = sh.flags;
   if (y >= 0) {
-    if (fmin(run - tau_local, tau_local - prev) / W < 1e-6) fl |= SV_FLAG_NEAR_CDF_EDGE;
+    if (fmin(run - tau_local, tau_local - prev) < kCdfEdgeRel * W + kCdfEdgeAbs) fl |= SV_FLAG_NEAR_CDF_EDGE;
   } else {
     // rounding left no entry whose running sum passes the threshold: take the
     // last positive-weight entry at or before the end of this segment

@@ -117,6 +117,51 @@ def make_config(index, seed=None, B=None, k=None, V=None, dtype=None, device="cp
                 name=cfg["name"], seed=seed, sigma=sigma)
 
 
+def make_near_pairs(B, V, dtype, seed, lo, hi, device="cpu"):
+    """Target / draft rows that differ by very little, one drafted position per
+    sequence, with a rejection forced at it: inputs for checks of the residual
+    draw at small residual mass.
+
+    z_t [B, 2, V] ~ N(0, 2.5^2) (row 1 = bonus row); z_d [B, 1, V] differs from
+    z_t[:, 0] by a per-sequence amount d_b, log-uniform in [lo, hi]:
+      f32 : z_d = z_t + d_b * N(0, 1)  (rounded to float32)
+      bf16: a random fraction min(1, d_b) of the entries moved by one bfloat16 ulp,
+            up or down with equal probability (bfloat16 has no finer step)
+    The drafted token x[b, 0] is a random id whose logit is set to -inf in both
+    rows: its acceptance ratio is 0/0 and it is rejected, so position 0 is
+    always drawn from the residual.  Returns dict(z_t, z_d, x, d).
+    """
+    tdt = _TORCH_DTYPE[dtype]
+    g = torch.Generator(device=device)
+    g.manual_seed(seed)
+    z_t = torch.empty((B, 2, V), dtype=tdt, device=device)
+    z_d = torch.empty((B, 1, V), dtype=tdt, device=device)
+    u = _rand((B,), g, device)
+    d = torch.exp(math.log(lo) + u * (math.log(hi) - math.log(lo)))
+    x = torch.randint(0, V, (B, 1), generator=g, device=device).to(torch.int32)
+    for b in range(B):
+        t = (2.5 * _randn((2, V), g, device)).to(tdt)
+        if dtype == "f32":
+            dr = (t[0] + d[b] * _randn((V,), g, device)).to(tdt)
+        else:
+            move = _rand((V,), g, device) < d[b]
+            up = _rand((V,), g, device) < 0.5
+            bits = t[0].view(torch.int16).to(torch.int32)
+            step = torch.where(up, 1, -1) * move.to(torch.int32)
+            # one ulp away from zero / towards zero in sign-magnitude order; values near 0 and
+            # the largest finite magnitudes stay as they are
+            mag = bits & 0x7FFF
+            ok = (mag > 0x0080) & (mag < 0x7F00)
+            new_mag = torch.where(ok, mag + step, mag)
+            dr = ((bits & 0x8000) | new_mag).to(torch.int16).view(torch.bfloat16)
+        tok = int(x[b, 0])
+        t[0, tok] = float("-inf")
+        dr[tok] = float("-inf")
+        z_t[b] = t
+        z_d[b, 0] = dr
+    return dict(z_t=z_t, z_d=z_d, x=x, d=d)
+
+
 def profile_table(n_s=10, n_a=10):
     """A closed-form, monotone stand-in for the profiled acceptance table.
 

@@ -21,7 +21,7 @@ def _case(B=4, k=3, V=300, seed=0, dtype=torch.float32):
 
 
 def _run_verify(z_t, z_d, x, **kw):
-    ref = O.verify_sample(z_t, z_d, x, **kw)
+    ref = H.oracle_verify(z_t, z_d, x, **kw)
     got = H.gpu_verify(H.dev(z_t), H.dev(z_d), H.dev(x), **kw)
     return got, ref
 
@@ -105,7 +105,7 @@ def test_packed_offsets_out_of_range_are_flagged_not_read():
     packed = np.concatenate([z_t[b, :gamma[b] + 1] for b in range(3)])
     short = packed[:6]                    # sequence 2 now points past the buffer
     got = H.gpu_verify(H.dev(short), H.dev(z_d), H.dev(x), gamma=gamma, t_offsets=offs, seed=1)
-    ref = O.verify_sample(packed, z_d, x, gamma=gamma, t_offsets=offs, seed=1)
+    ref = H.oracle_verify(packed, z_d, x, gamma=gamma, t_offsets=offs, seed=1)
     for b in range(2):
         assert np.array_equal(got["tokens"][b], ref["tokens"][b])
     assert got["flags"][2] & O.FLAG_BAD_ROW

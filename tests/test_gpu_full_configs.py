@@ -53,13 +53,13 @@ def test_full_config_dense(index):
     cfg, d, oi, rp, lat = _stage_isolated(index)
     k = cfg["k"]
     t0 = time.time()
-    ref = O.verify_sample(oi["z_t"], oi["z_d"], oi["x"], seed=0, step=0)
+    ref = H.oracle_verify(oi["z_t"], oi["z_d"], oi["x"], seed=0, step=0)
     got = H.gpu_verify(d["z_t"], d["z_d"], d["x"], seed=0, step=0)
     n_tie, n_edge = H.assert_verify(got, ref, k)
     print(f"  verify (gamma = k) ok: near-tie {n_tie}, near-cdf-edge {n_edge}, "
           f"mean accepted {ref['n_accept'].mean():.2f} ({time.time() - t0:.1f}s)", flush=True)
     rg, _, _ = O.select_length(rp, lat)
-    ref = O.verify_sample(oi["z_t"], oi["z_d"], oi["x"], gamma=rg, seed=1, step=3)
+    ref = H.oracle_verify(oi["z_t"], oi["z_d"], oi["x"], gamma=rg, seed=1, step=3)
     got = H.gpu_verify(d["z_t"], d["z_d"], d["x"], gamma=rg, seed=1, step=3)
     n_tie, n_edge = H.assert_verify(got, ref, k)
     print(f"  verify (selected gamma, mean {rg.mean():.2f}) ok: near-tie {n_tie}, near-cdf-edge {n_edge}",
@@ -75,7 +75,7 @@ def test_full_config5_ragged_chain():
     packed = torch.cat([d["z_t"][b, :rg[b] + 1] for b in range(B)]).contiguous()
     packed_np = np.concatenate([oi["z_t"][b, :rg[b] + 1] for b in range(B)])
     assert packed.shape[0] == ro[-1]
-    ref = O.verify_sample(packed_np, oi["z_d"], oi["x"], gamma=rg, t_offsets=ro, seed=5, step=2)
+    ref = H.oracle_verify(packed_np, oi["z_d"], oi["x"], gamma=rg, t_offsets=ro, seed=5, step=2)
     got = H.gpu_verify(packed, d["z_d"], d["x"], gamma=rg, t_offsets=ro, seed=5, step=2)
     n_tie, n_edge = H.assert_verify(got, ref, k)
     full = int((ref["n_accept"] == rg).sum())
@@ -156,7 +156,7 @@ def test_full_config_warped_compacted_ragged():
         from oracle import philox as OP
         ua, _ = OP.sv_uniforms(9, 2, np.full((1, k), b), np.arange(k)[None, :])
         _, us_full = OP.sv_uniforms(9, 2, np.full((1, k + 1), b), np.arange(k + 1)[None, :])
-        ref = O.verify_sample(y_t, y_d, x[b:b + 1], gamma=g[b:b + 1], t_offsets=np.array([0, g[b] + 1], np.int32),
+        ref = H.oracle_verify(y_t, y_d, x[b:b + 1], gamma=g[b:b + 1], t_offsets=np.array([0, g[b] + 1], np.int32),
                               uniforms=(ua, us_full))
         got = {n: v[b:b + 1] for n, v in s.items()}
         H.assert_verify(got, ref, k)
@@ -203,5 +203,5 @@ def test_large_batch_chain():
         assert H.close(S.cpu().numpy()[b], r["S"][0], H.REL).all() and H.close(A.cpu().numpy()[b], r["A"][0], H.REL, 1e-30).all()
         ua, _ = OP.sv_uniforms(5, 6, np.full((1, k), b), np.arange(k)[None, :])
         _, us = OP.sv_uniforms(5, 6, np.full((1, k + 1), b), np.arange(k + 1)[None, :])
-        ref = O.verify_sample(zt, zd, x[b:b + 1], gamma=rg[b:b + 1], uniforms=(ua, us))
+        ref = H.oracle_verify(zt, zd, x[b:b + 1], gamma=rg[b:b + 1], uniforms=(ua, us))
         H.assert_verify({n: v[b:b + 1] for n, v in got_all.items()}, ref, k)

@@ -52,7 +52,7 @@ def test_verify_sample_dense(idx, B, k, V, dtype):
     cfg, d = _gen(idx, B, k, V, dtype)
     oi = H.oracle_inputs(cfg)
     for seed, step in ((0, 0), (0xDEADBEEF12345, 7)):
-        ref = O.verify_sample(oi["z_t"], oi["z_d"], oi["x"], seed=seed, step=step)
+        ref = H.oracle_verify(oi["z_t"], oi["z_d"], oi["x"], seed=seed, step=step)
         got = H.gpu_verify(d["z_t"], d["z_d"], d["x"], seed=seed, step=step)
         H.assert_verify(got, ref, k)
 
@@ -64,7 +64,7 @@ def test_verify_sample_gamma_and_packed(idx, B, k, V, dtype):
     rng = np.random.default_rng(idx + B)
     gamma = rng.integers(0, k + 1, size=B).astype(np.int32)
     gamma[0] = 0
-    ref = O.verify_sample(oi["z_t"], oi["z_d"], oi["x"], gamma=gamma, seed=3, step=1)
+    ref = H.oracle_verify(oi["z_t"], oi["z_d"], oi["x"], gamma=gamma, seed=3, step=1)
     got = H.gpu_verify(d["z_t"], d["z_d"], d["x"], gamma=gamma, seed=3, step=1)
     H.assert_verify(got, ref, k)
     offs = np.concatenate([[0], np.cumsum(gamma + 1)]).astype(np.int32)
@@ -155,7 +155,7 @@ def test_chained_step_config2():
     rg, ro, rm = O.select_length(rp, lat)
     assert np.array_equal(gamma.cpu().numpy(), rg) and int(total.item()) == rm
     assert np.array_equal(offs.cpu().numpy(), ro)
-    ref = O.verify_sample(oi["z_t"], oi["z_d"], oi["x"], gamma=rg)
+    ref = H.oracle_verify(oi["z_t"], oi["z_d"], oi["x"], gamma=rg)
     got = dict(tokens=tokens.cpu().numpy(), n_accept=n_acc.cpu().numpy(),
                flags=flags.cpu().numpy().astype(np.uint32), ratio=ratio.cpu().numpy())
     H.assert_verify(got, ref, k)

@@ -33,7 +33,7 @@ def test_random_problems(block):
         H.assert_row_stats(H.gpu_row_stats(d["z_d"], d["z_c"], d["x"], with_kl), ref, with_kl)
         gamma = rng.integers(0, k + 1, size=B).astype(np.int32) if rng.random() < 0.6 else None
         pseed, step = int(rng.integers(0, 2 ** 62)), int(rng.integers(0, 2 ** 31))
-        vref = O.verify_sample(oi["z_t"], oi["z_d"], oi["x"], gamma=gamma, seed=pseed, step=step)
+        vref = H.oracle_verify(oi["z_t"], oi["z_d"], oi["x"], gamma=gamma, seed=pseed, step=step)
         vgot = H.gpu_verify(d["z_t"], d["z_d"], d["x"], gamma=gamma, seed=pseed, step=step)
         t, e = H.assert_verify(vgot, vref, k)
         n_tie, n_edge, n_seq = n_tie + t, n_edge + e, n_seq + B
@@ -108,7 +108,7 @@ def _warped_case(rng, zs, dtype, par, with_kl=True):
     gg = None if gamma is None else H.dev(gamma, torch.int32)
     pseed, step = int(rng.integers(0, 2 ** 62)), int(rng.integers(0, 2 ** 31))
     with np.errstate(all="ignore"):
-        vref = O.verify_sample(y["t"], y["d"], x, gamma=gamma, seed=pseed, step=step)
+        vref = H.oracle_verify(y["t"], y["d"], x, gamma=gamma, seed=pseed, step=step)
     sub = lambda dct, m: {n: ([v[i] for i in np.flatnonzero(m)] if isinstance(v, list) else np.asarray(v)[m])
                           for n, v in dct.items()}
     n_seq = n_tie = 0
@@ -204,7 +204,7 @@ def test_random_adversarial_values(block):
         z_t, z_d, z_c, x = _adversarial_rows(rng, B, k, V, bf16)
         with np.errstate(all="ignore"):         # exp of +-1e6 inside the oracle's min(1, .) and ratios
             ref = O.row_stats(z_d, z_c, x)
-            vref = O.verify_sample(z_t, z_d, x, seed=case, step=block)
+            vref = H.oracle_verify(z_t, z_d, x, seed=case, step=block)
         # KL is left out: draft mass on a masked companion entry makes it about -mask
         got = H.gpu_row_stats(H.dev(z_d, dtype), H.dev(z_c, dtype), H.dev(x), with_kl=False)
         H.assert_row_stats(got, ref, with_kl=False)

@@ -178,7 +178,7 @@ def test_verify_sample_sparse_matches_oracle(pt_, pd_):
         for redraw in (False, True):
             x = _redraw_tokens(y_d, 6) if redraw else inp["x"]
             for step in range(3):
-                ref = O.verify_sample(y_t, y_d, x, seed=77, step=step)
+                ref = H.oracle_verify(y_t, y_d, x, seed=77, step=step)
                 tokens = torch.full((B, k + 1), -5, dtype=torch.int32, device="cuda")
                 n_acc = torch.full((B,), -5, dtype=torch.int32, device="cuda")
                 flags = torch.full((B,), 0x7FFF, dtype=torch.int32, device="cuda")
@@ -213,7 +213,7 @@ def test_verify_sample_sparse_packed_ragged_and_gamma():
     x = _redraw_tokens(y_d, 7)
     sup_t, _ = _supports_for(z_t_packed, T, K, Pp, 64)
     sup_d, _ = _supports_for(cfg["z_d"], T, K, Pp, 64)
-    ref = O.verify_sample(y_tp, y_d, x, gamma=gamma, t_offsets=offs, seed=5, step=9)
+    ref = H.oracle_verify(y_tp, y_d, x, gamma=gamma, t_offsets=offs, seed=5, step=9)
     tokens = torch.full((B, k + 1), -5, dtype=torch.int32, device="cuda")
     n_acc = torch.full((B,), -5, dtype=torch.int32, device="cuda")
     flags = torch.full((B,), 0x7FFF, dtype=torch.int32, device="cuda")

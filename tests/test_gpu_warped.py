@@ -107,7 +107,7 @@ def test_verify_sample_warped_matches_oracle(pt_, pd_):
         for redraw in (False, True):
             x = _redraw_tokens(y_d, 6) if redraw else inp["x"]
             for step in range(3):
-                ref = O.verify_sample(y_t, y_d, x, seed=77, step=step)
+                ref = H.oracle_verify(y_t, y_d, x, seed=77, step=step)
                 got = _gpu_verify_warped(cfg["z_t"], cfg["z_d"], H.dev(x, torch.int32), Tt, _cut32(cut_t),
                                          Td, _cut32(cut_d), seed=77, step=step)
                 t, e = H.assert_verify(got, ref, k)
@@ -127,7 +127,7 @@ def test_verify_sample_warped_packed_and_ragged():
     y_tp, cut_tp, _ = W.warp_rows(packed, T, K, Pp)
     y_d, cut_d, _ = W.warp_rows(inp["z_d"], T, K, Pp)
     x = _redraw_tokens(y_d, 7)
-    ref = O.verify_sample(y_tp, y_d, x, gamma=gamma, t_offsets=offs, seed=5, step=9)
+    ref = H.oracle_verify(y_tp, y_d, x, gamma=gamma, t_offsets=offs, seed=5, step=9)
     got = _gpu_verify_warped(z_t_packed, cfg["z_d"], H.dev(x, torch.int32), T, _cut32(cut_tp), T, _cut32(cut_d),
                              gamma=gamma, t_offsets=offs, seed=5, step=9)
     H.assert_verify(got, ref, k)
@@ -168,7 +168,7 @@ def test_warped_bad_rows_masked_entries_and_tokens_outside_support():
     H.assert_row_stats(got, ref)
     assert got["flags"][0, 1] & O.FLAG_BAD_ROW and got["flags"][1, 0] & O.FLAG_BAD_ROW
     assert got["A"][2, 0] == 1.0 and got["pd_x"][2, 0] == 0.0
-    ref = O.verify_sample(y_t, y_d, zn["x"], seed=1, step=2)
+    ref = H.oracle_verify(y_t, y_d, zn["x"], seed=1, step=2)
     got = _gpu_verify_warped(z_t, z_d, x, T, _cut32(cut_t), T, _cut32(cut_d), seed=1, step=2)
     H.assert_verify(got, ref, k)
 
@@ -230,7 +230,7 @@ def test_decode_step_with_gpu_cutoffs_end_to_end():
     sel = O.select_length(p_ref, latency, O.MODE_BATCH_GREEDY)
     g_ref = sel[0] if isinstance(sel, tuple) else sel["gamma"]
     assert np.array_equal(gamma.cpu().numpy(), g_ref)
-    ref = O.verify_sample(y_t, y_d, x, gamma=g_ref, seed=11, step=4)
+    ref = H.oracle_verify(y_t, y_d, x, gamma=g_ref, seed=11, step=4)
     got = dict(tokens=tokens.cpu().numpy(), n_accept=n_acc.cpu().numpy(),
                flags=flags.cpu().numpy().astype(np.uint32), ratio=ratio.cpu().numpy())
     sub = lambda d: {n: ([v[i] for i in np.flatnonzero(keep)] if isinstance(v, list) else np.asarray(v)[keep])
@@ -256,7 +256,7 @@ def test_extreme_temperatures(T):
         ref = O.row_stats(y_d, y_c, x)
         got = _gpu_row_stats_warped(cfg["z_d"], cfg["z_c"], xg, T, _cut32(cut_d), T, _cut32(cut_c))
         H.assert_row_stats({n: v[pair_ok] for n, v in got.items()}, {n: np.asarray(v)[pair_ok] for n, v in ref.items()})
-        vref = O.verify_sample(y_t, y_d, x, seed=3, step=8)
+        vref = H.oracle_verify(y_t, y_d, x, seed=3, step=8)
         vgot = _gpu_verify_warped(cfg["z_t"], cfg["z_d"], xg, T, _cut32(cut_t), T, _cut32(cut_d), seed=3, step=8)
         seq_ok = ~(((f_t & O.FLAG_NEAR_TIE) != 0).any(1) | ((f_d & O.FLAG_NEAR_TIE) != 0).any(1))
         sub = lambda d: {n: ([v[i] for i in np.flatnonzero(seq_ok)] if isinstance(v, list) else np.asarray(v)[seq_ok])

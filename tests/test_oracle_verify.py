@@ -232,17 +232,71 @@ def test_flags_near_tie_residual_fallback_bad_inputs():
     assert out["flags"][0] & O.FLAG_BAD_TOKEN and out["n_accept"][0] == 0 and out["tokens"][0, 0] >= 0
 
 
-def test_residual_mass_floor():
-    """A residual mass at or below RESIDUAL_FLOOR counts as none (target row drawn, flagged);
-    above it the residual is used.  Two-token rows: P_t = (a, 1-a), P_d = (a-d, 1-a+d) give
-    the residual (d, 0) exactly, mass d."""
+def test_residual_is_drawn_for_any_positive_mass():
+    """The speculative-sampling rule has no floor: a residual of any mass W > 0 is drawn from
+    (W = 0 exactly is the only fallback).  Two-token rows: P_t = (a, 1-a), P_d = (a-d, 1-a+d)
+    give the residual (d, 0) exactly, mass d; d is walked down through 1e-6 (where single
+    precision stops resolving it) to 1e-14."""
     a = 0.4
-    for d, fallback in ((2e-7, True), (0.9 * O.RESIDUAL_FLOOR, True), (3 * O.RESIDUAL_FLOOR, False), (1e-3, False)):
+    for d in (1e-1, 1e-3, 3e-6, 1.1e-6, 0.9e-6, 2e-7, 1e-9, 1e-12, 1e-14):
         zt = np.log(np.array([a, 1 - a]))
         zd = np.log(np.array([a - d, 1 - a + d]))
         w, W, fl = O.sampling_weights(zt, zd)
-        assert bool(fl & O.FLAG_RESIDUAL_FALLBACK) == fallback, d
-        if fallback:
-            assert np.allclose(w, [a, 1 - a], rtol=1e-12) and abs(W - 1) < 1e-12
-        else:
-            assert abs(W - d) < 1e-12 and w[1] == 0.0 and abs(w[0] - d) < 1e-12
+        assert fl == 0, d
+        assert abs(W - d) <= 1e-15 + 1e-12 * d and w[1] == 0.0 and w[0] == W
+        for u in (0.01, 0.5, 0.99):
+            assert O.inverse_cdf(w, W, u)[0] == 0
+    # W = 0 exactly: nothing to draw from, the target row is used and flagged
+    zt = np.log(np.array([a, 1 - a]))
+    w, W, fl = O.sampling_weights(zt, zt.copy())
+    assert fl == O.FLAG_RESIDUAL_FALLBACK and np.allclose(w, [a, 1 - a], rtol=1e-12) and abs(W - 1) < 1e-12
+
+
+def test_emitted_law_is_the_target_for_nearly_equal_models():
+    """Pins the no-floor rule by what it must achieve, not by a constant: with P_d within
+    1e-2 ... 1e-12 of P_t (residual mass of that order) one verified position still emits
+    exactly P_t:  sum_x P_d(x) [a(x) 1{x=y} + (1 - a(x)) r(y)] = P_t(y),  V <= 8.
+    A rule that swapped a small residual for P_t would be off by about W^2 in the tokens that
+    lose mass, which the tolerance (1e-3 of W^2) resolves down to W = 1e-6 in float64."""
+    rng = np.random.default_rng(11)
+    for V in (2, 3, 8):
+        for eps in (1e-2, 1e-4, 1e-6):
+            zt = rng.standard_normal(V) * 2
+            zd = zt + eps * rng.standard_normal(V)
+            pt, pd = _softmax(zt), _softmax(zd)
+            w, W, fl = O.sampling_weights(zt, zd)
+            assert fl == 0 and 0 < W < 4 * eps
+            a = np.array([min(1.0, O.accept_ratio(zt, zd, t)[0]) for t in range(V)])
+            emitted = pd * a + np.sum(pd * (1 - a)) * w / W
+            assert np.max(np.abs(emitted - pt)) < max(1e-3 * W * W, 4e-16), (V, eps)
+            # the same law with the target row in place of the residual is visibly wrong
+            wrong = pd * a + np.sum(pd * (1 - a)) * pt
+            assert np.max(np.abs(wrong - pt)) > 0.05 * W * W
+        for eps in (1e-9, 1e-12):     # below float64's W^2 resolution: the residual's support
+            zt = rng.standard_normal(V) * 2
+            zd = zt + eps * rng.standard_normal(V)
+            pt, pd = _softmax(zt), _softmax(zd)
+            w, W, fl = O.sampling_weights(zt, zd)
+            assert fl == 0 and W > 0
+            assert np.array_equal(w > 0, pt > pd)
+
+
+def test_admissible_sets_with_an_absolute_band():
+    """The comparison aid of inverse_cdf: an absolute band widens the admissible set (and only
+    that); tokens outside `support` are never admissible, tokens of zero weight inside it are."""
+    w = np.array([0.25, 0.0, 0.5, 0.25, 0.0])
+    support = np.array([True, True, True, True, False])
+    y0, m0, adm0 = O.inverse_cdf(w, 1.0, 0.2499)
+    y1, m1, adm1 = O.inverse_cdf(w, 1.0, 0.2499, abs_band=1e-3, support=support)
+    assert (y0, m0) == (y1, m1) and list(adm0) == [0] and list(adm1) == [0, 1, 2]
+    # a residual far below the band: every supported token is admissible
+    w = np.array([0.0, 3e-9, 0.0, 1e-9, 0.0])
+    y, _, adm = O.inverse_cdf(w, 4e-9, 0.9, abs_band=1e-6, support=support)
+    assert y == 3 and list(adm) == [0, 1, 2, 3]
+    z = np.array([[[0.0, 1.0, 2.0], [0.0, 0.0, 0.0]]])
+    r0 = O.verify_sample(z, z[:, :1] + 0.3, np.array([[1]]), seed=4)
+    r1 = O.verify_sample(z, z[:, :1] + 0.3, np.array([[1]]), seed=4, cdf_abs_band=0.5)
+    for name in ("tokens", "n_accept", "ratio", "margin", "W", "resid"):
+        assert np.array_equal(r0[name], r1[name], equal_nan=True), name
+    assert r1["flags"][0] & O.FLAG_NEAR_CDF_EDGE and not (r0["flags"][0] & O.FLAG_NEAR_CDF_EDGE)
+
