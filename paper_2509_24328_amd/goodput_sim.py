@@ -1,22 +1,31 @@
-"""Step-level goodput simulation of SV against plain speculative decoding on
-synthetic logits, entirely through the C ABI.
+"""Step-level goodput simulation on synthetic logits, entirely through the C ABI:
+plain speculative decoding against verification lengths chosen from three
+acceptance estimators - SV's (S, A) pair and the two prior predictor families the
+paper discusses (Sec. 2 "Predicting Speculation Accuracy": the entropy of the
+draft distribution; the draft's probability of its own token).
 
 What the paper measures end to end with real models (goodput = accepted tokens
 per unit time, Sec. 5 and Sec. 7.2) is modelled here per decode step:
 
-  * profile:  P(T | S, A) is built on a held-out batch (distinct seed) with the
-              profile pass (sv_row_stats, sv_accept_ratio, sv_profile_accumulate,
-              sv_profile_finalize), as the paper builds it from profiled samples;
+  * profiles: for every estimator the mean acceptance probability per cell of its
+              signal (appendix definition of the observed P(T | S, A), applied to
+              each signal alike) is built on a held-out batch (distinct seed) with
+              the profile pass (sv_row_stats, sv_accept_ratio, sv_quantile_edges,
+              sv_profile_accumulate, sv_profile_finalize); (S, A) uses a 10 x 10
+              uniform grid, the entropy H(P_d) and P_d(x) 100 equal-count cells
+              each (second axis: one bin), so all three have the same resolution;
   * SD step:  every sequence verifies all k drafted tokens;
-  * SV step:  sv_row_stats -> sv_accept_estimate -> sv_select_length picks the
-              lengths, only those positions are verified;
+  * other steps: sv_row_stats -> sv_accept_estimate (the estimator's signal and
+              table) -> sv_select_length picks the lengths, only those positions
+              are verified;
   * cost:     latency[M] of the caller's latency table, M = drafted tokens sent to
               the target in the step (the paper's profiled verification latency).
 
 Goodput of a run = accepted drafted tokens / sum of step latencies; the accept
 rate is accepted / verified.  Only the qualitative picture can be compared with
 the paper (its numbers need its models and hardware): SV trades a little
-acceptance volume for much less verification work where drafts are poor.
+acceptance volume for much less verification work where drafts are poor, and the
+(S, A) signal carries more information about acceptance than the other two.
 
 With --temperature / --top-k / --top-p the whole simulation runs on the warped
 distributions the paper's experiments sample from (appendix table of sampling
@@ -37,9 +46,9 @@ import torch
 
 from . import binding as B_
 from .binding import (SV_BATCH_GREEDY, Supports, alloc_workspace, sv_accept_estimate, sv_accept_ratio,
-                      sv_accept_ratio_sparse, sv_profile_accumulate, sv_profile_finalize, sv_row_stats,
-                      sv_row_stats_sparse, sv_select_length, sv_verify_sample, sv_verify_sample_sparse,
-                      sv_warp_compact)
+                      sv_accept_ratio_sparse, sv_profile_accumulate, sv_profile_finalize, sv_quantile_edges,
+                      sv_row_stats, sv_row_stats_sparse, sv_select_length, sv_verify_sample,
+                      sv_verify_sample_sparse, sv_warp_compact)
 
 SUPPORT_CAP = 256
 
@@ -61,78 +70,135 @@ def _compact(batch, warp):
     return sups
 
 
-def build_profile(batch, n_s=10, n_a=10, n_x=10, warp=None):
-    """Profile table and information figures from one batch of logits (GPU)."""
-    z_t, z_d, z_c, x = batch["z_t"], batch["z_d"], batch["z_c"], batch["x"]
+ESTIMATORS = ("sv", "entropy", "probability")
+
+
+def _signals(batch, sups, ws):
+    """S, A, H(P_d), P_d(x) of a batch ([B, k] float32 device tensors)."""
+    z_d, z_c, x = batch["z_d"], batch["z_c"], batch["x"]
     B, k, V = z_d.shape
     f32 = lambda *s: torch.empty(s, dtype=torch.float32, device="cuda")
-    lse_d, lse_c, S, A, ratio = (f32(B, k) for _ in range(5))
+    lse_d, lse_c, S, A, kl, H, pdx = (f32(B, k) for _ in range(7))
+    if sups is None:
+        sv_row_stats(z_d, z_c, x, lse_d, lse_c, S, A, kl, None, ws, entropy_d=H, pd_x=pdx)
+    else:
+        sv_row_stats_sparse(sups["z_d"], sups["z_c"], x, V, lse_d, lse_c, S, A, kl, entropy_d=H, pd_x=pdx)
+    return dict(S=S, A=A, H_d=H, pd_x=pdx)
+
+
+def _axes(name, sig):
+    if name == "sv":
+        return sig["S"], sig["A"]
+    zero = torch.zeros_like(sig["S"])
+    return (sig["H_d"] if name == "entropy" else sig["pd_x"]), zero
+
+
+def build_profiles(batch, cells=100, n_x=10, warp=None, estimators=ESTIMATORS):
+    """{estimator: (edges_1, edges_2, table, info)} from one held-out batch (GPU);
+    info = (H(X), H(X | signal), information gain) in bits."""
+    z_t, z_d, x = batch["z_t"], batch["z_d"], batch["x"]
+    B, k, V = z_d.shape
+    f32 = lambda *s: torch.empty(s, dtype=torch.float32, device="cuda")
     ws = alloc_workspace(B, k, V, B_._dtype_tag(z_d))
-    edges_s = torch.linspace(0, 1, n_s + 1, device="cuda", dtype=torch.float32)
-    edges_a = torch.linspace(0, 1, n_a + 1, device="cuda", dtype=torch.float32)
-    counts = torch.zeros((n_s, n_a, n_x), dtype=torch.int32, device="cuda")
-    sum_x = torch.zeros((n_s, n_a), dtype=torch.float64, device="cuda")
-    table, info = f32(n_s, n_a), torch.zeros(3, dtype=torch.float64, device="cuda")
+    sups = None if warp is None else _compact(batch, warp)
+    sig = _signals(batch, sups, ws)
+    ratio = f32(B, k)
     if warp is None:
-        sv_row_stats(z_d, z_c, x, lse_d, lse_c, S, A, None, None, ws)
         sv_accept_ratio(z_t, z_d, x, ratio, None, ws)
     else:
-        sups = _compact(batch, warp)
-        sv_row_stats_sparse(sups["z_d"], sups["z_c"], x, V, lse_d, lse_c, S, A)
         sv_accept_ratio_sparse(sups["z_t"], sups["z_d"], x, V, ratio)
-    sv_profile_accumulate(S, A, ratio, edges_s, edges_a, n_x, counts, sum_x)
-    sv_profile_finalize(counts, sum_x, table, info)
-    torch.cuda.synchronize()
-    return edges_s, edges_a, table, info.cpu().numpy()
+    out = {}
+    for name in estimators:
+        a1, a2 = _axes(name, sig)
+        if name == "sv":
+            n = int(round(cells ** 0.5))
+            e1 = torch.linspace(0, 1, n + 1, device="cuda", dtype=torch.float32)
+            e2 = e1.clone()
+        else:
+            hi = float(np.float32(np.log(V))) if name == "entropy" else 1.0
+            e1 = f32(cells + 1)
+            sv_quantile_edges(a1, cells, 0.0, hi, e1)
+            e2 = torch.tensor([0.0, 1.0], device="cuda", dtype=torch.float32)
+        n1, n2 = e1.numel() - 1, e2.numel() - 1
+        counts = torch.zeros((n1, n2, n_x), dtype=torch.int32, device="cuda")
+        sum_x = torch.zeros((n1, n2), dtype=torch.float64, device="cuda")
+        table, info = f32(n1, n2), torch.zeros(3, dtype=torch.float64, device="cuda")
+        sv_profile_accumulate(a1, a2, ratio, e1, e2, n_x, counts, sum_x)
+        sv_profile_finalize(counts, sum_x, table, info)
+        torch.cuda.synchronize()
+        out[name] = (e1, e2, table, info.cpu().numpy())
+    return out
 
 
-def simulate(make_batch, latency, steps, profile, warp=None):
-    """Run `steps` decode steps on fresh batches; returns SD and SV totals."""
-    edges_s, edges_a, table, _ = profile
+def build_profile(batch, n_s=10, n_a=10, n_x=10, warp=None):
+    """The (S, A) profile alone: (edges_s, edges_a, table, info)."""
+    assert n_s == n_a
+    return build_profiles(batch, cells=n_s * n_a, n_x=n_x, warp=warp, estimators=("sv",))["sv"]
+
+
+def simulate(make_batch, latency, steps, profiles, warp=None, keep_steps=False):
+    """Run `steps` decode steps on fresh batches under plain SD ("sd") and under every
+    estimator of `profiles` ({name: (edges_1, edges_2, table, ...)} with device tensors; a
+    bare (edges_s, edges_a, table, ...) tuple means the (S, A) estimator alone).  The same
+    Philox step serves all of them; only the verified lengths differ.  Returns the totals
+    per name; with keep_steps also "steps": per step and name the lengths, the number of
+    verified tokens, the accept counts and the flags (host arrays), and the signals."""
+    if not isinstance(profiles, dict):
+        profiles = {"sv": profiles}
     first = make_batch(0)
     B, k, V = first["z_d"].shape
     f32 = lambda *s: torch.empty(s, dtype=torch.float32, device="cuda")
     i32 = lambda *s: torch.empty(s, dtype=torch.int32, device="cuda")
-    lse_d, lse_c, S, A, p_hat = (f32(B, k) for _ in range(5))
+    p_hat = f32(B, k)
+    edge = torch.empty((B, k), dtype=torch.uint8, device="cuda")
     gamma, offs, total = i32(B), i32(B + 1), i32(1)
     tokens, n_acc, flags = i32(B, k + 1), i32(B), i32(B)
     ws = alloc_workspace(B, k, V, B_._dtype_tag(first["z_d"]))
     lat = torch.as_tensor(latency, dtype=torch.float32).cuda()
-    res = {m: dict(accepted=0, verified=0, latency=0.0) for m in ("sd", "sv")}
+    names = ("sd",) + tuple(profiles)
+    res = {m: dict(accepted=0, verified=0, latency=0.0) for m in names}
+    log = []
     for t in range(steps):
         b = first if t == 0 else make_batch(t)
-        z_t, z_d, z_c, x = b["z_t"], b["z_d"], b["z_c"], b["x"]
+        z_t, z_d, x = b["z_t"], b["z_d"], b["x"]
         sups = None if warp is None else _compact(b, warp)
-        # plain speculative decoding: verify everything
-        if warp is None:
-            sv_verify_sample(z_t, None, z_d, x, None, 1234, t, tokens, n_acc, flags, None, ws)
-        else:
-            sv_verify_sample_sparse(sups["z_t"], None, sups["z_d"], x, None, V, 1234, t, tokens, n_acc, flags)
-        torch.cuda.synchronize()
-        res["sd"]["accepted"] += int(n_acc.sum())
-        res["sd"]["verified"] += B * k
-        res["sd"]["latency"] += float(latency[B * k])
-        # speculative verification: verify what the estimate says is worth it
-        if warp is None:
-            sv_row_stats(z_d, z_c, x, lse_d, lse_c, S, A, None, None, ws)
-        else:
-            sv_row_stats_sparse(sups["z_d"], sups["z_c"], x, V, lse_d, lse_c, S, A)
-        sv_accept_estimate(S, A, edges_s, edges_a, table, p_hat, None)
-        sv_select_length(p_hat, lat, SV_BATCH_GREEDY, gamma, offs, total)
-        if warp is None:
-            sv_verify_sample(z_t, None, z_d, x, gamma, 1234, t, tokens, n_acc, flags, None, ws)
-        else:
-            sv_verify_sample_sparse(sups["z_t"], None, sups["z_d"], x, gamma, V, 1234, t, tokens, n_acc, flags)
-        torch.cuda.synchronize()
-        M = int(total.item())
-        res["sv"]["accepted"] += int(n_acc.sum())
-        res["sv"]["verified"] += M
-        res["sv"]["latency"] += float(latency[M])
-    for m in res:
+        sig = _signals(b, sups, ws)
+        rec = {}
+        for m in names:
+            near_edge = False
+            if m == "sd":                       # plain speculative decoding: verify everything
+                g, M = None, B * k
+            else:                               # verify what the estimate says is worth it
+                e1, e2, table = profiles[m][:3]
+                a1, a2 = _axes(m, sig)
+                sv_accept_estimate(a1, a2, e1, e2, table, p_hat, edge)
+                sv_select_length(p_hat, lat, SV_BATCH_GREEDY, gamma, offs, total)
+                g = gamma
+            if warp is None:
+                sv_verify_sample(z_t, None, z_d, x, g, 1234, t, tokens, n_acc, flags, None, ws)
+            else:
+                sv_verify_sample_sparse(sups["z_t"], None, sups["z_d"], x, g, V, 1234, t, tokens, n_acc, flags)
+            torch.cuda.synchronize()
+            if m != "sd":
+                M = int(total.item())
+                near_edge = bool(edge.any())
+            res[m]["accepted"] += int(n_acc.sum())
+            res[m]["verified"] += M
+            res[m]["latency"] += float(latency[M])
+            if keep_steps:
+                rec[m] = dict(gamma=(np.full(B, k, np.int32) if g is None else gamma.cpu().numpy().copy()), M=M,
+                              n_accept=n_acc.cpu().numpy().copy(), flags=flags.cpu().numpy().astype(np.uint32),
+                              near_edge=near_edge)
+        if keep_steps:
+            rec["signals"] = {n: v.cpu().numpy() for n, v in sig.items()}
+            log.append(rec)
+    for m in names:
         r = res[m]
         r["goodput"] = r["accepted"] / r["latency"] if r["latency"] else 0.0
         r["accept_rate"] = r["accepted"] / r["verified"] if r["verified"] else 0.0
         r["mean_verified_per_seq"] = r["verified"] / (steps * B)
+    if keep_steps:
+        res["steps"] = log
     return res
 
 
@@ -167,14 +233,15 @@ def main():
     held = mk(777_000)
     Bn, k = held["B"], held["k"]
     latency = svgen.latency_table(Bn * k, t0=args.t0, d=args.d, m0=args.m0)
-    profile = build_profile(held, warp=warp)
-    res = simulate(lambda t: mk(888_000 + t), latency, args.steps, profile, warp=warp)
+    profiles = build_profiles(held, warp=warp)
+    res = simulate(lambda t: mk(888_000 + t), latency, args.steps, profiles, warp=warp)
+    sd_goodput = res["sd"]["goodput"]
     out = {"workload": held["name"], "B": Bn, "k": k, "V": held["V"], "steps": args.steps,
            "warp": None if warp is None else {"temperature": warp[0], "top_k": warp[1], "top_p": warp[2]},
-           "profile_info_bits": {"H_X": float(profile[3][0]), "H_X_given_SA": float(profile[3][1]),
-                                 "info_gain": float(profile[3][2])},
-           "sd": res["sd"], "sv": res["sv"],
-           "sv_over_sd_goodput": res["sv"]["goodput"] / res["sd"]["goodput"] if res["sd"]["goodput"] else None}
+           "H_X_bits": float(profiles["sv"][3][0]),
+           "info_gain_bits": {m: float(profiles[m][3][2]) for m in profiles},
+           "runs": res,
+           "goodput_over_sd": {m: (res[m]["goodput"] / sd_goodput if sd_goodput else None) for m in profiles}}
     print(json.dumps(out))
 
 

@@ -14,7 +14,7 @@ import torch
 
 import svgen
 from oracle import sv_oracle as O
-from tests import harness as H
+import harness as H
 
 pytestmark = pytest.mark.gpu
 
