@@ -157,7 +157,8 @@ int sv_accept_estimate(const float* S, const float* A, int n,
  *   gamma   [B] int32       out  0..k
  *   t_offsets [B+1] int32   out  exclusive scan of gamma[b] + 1
  *   total_M [1] int32       out  sum_b gamma[b]
- * Limit: B*k <= SV_SELECT_MAX_KEYS, else SV_ERR_TOO_LARGE.
+ * Limit: B*k <= SV_SELECT_MAX_KEYS, else SV_ERR_TOO_LARGE.  B = 0 is accepted and
+ * does nothing (no output is written), as in the other calls.
  */
 int sv_select_length(const float* p_hat, int B, int k,
                      const float* latency, int n_latency, int mode,

@@ -4,7 +4,8 @@
 //
 // With c[b,j] = prod_{i<=j} p_hat[b,i] the expected accepted length of
 // verifying gamma tokens of sequence b is sum_{j<gamma} c[b,j], so the token
-// "with the highest increase in expected acceptance length" is always the
+// whose verification raises the expected accepted length most (the choice of
+// the batch-level greedy rule, Sec. 5, batch scheduling) is always the
 // largest not-yet-taken c.  Because c is non-increasing along a sequence,
 // sorting all (b,j) by (c descending, b, j ascending) reproduces the greedy
 // order.  One workgroup: products (one lane per sequence); pairwise merging of
@@ -324,8 +325,9 @@ extern "C" int sv_select_length(const float* p_hat, int B, int k, const float* l
                                 sv_stream_t stream) {
   using namespace sv;
   SV_REQUIRE(mode == SV_BATCH_GREEDY || mode == SV_PER_SEQUENCE, SV_ERR_INVALID_ARG);
-  SV_REQUIRE(B >= 1 && k >= 1, SV_ERR_INVALID_ARG);
+  SV_REQUIRE(B >= 0 && k >= 1, SV_ERR_INVALID_ARG);
   SV_REQUIRE((long long)B * k <= SV_SELECT_MAX_KEYS, SV_ERR_TOO_LARGE);
+  if (B == 0) return SV_OK;
   SV_REQUIRE(n_latency >= (mode == SV_BATCH_GREEDY ? B * k + 1 : k + 1), SV_ERR_INVALID_ARG);
   SV_REQUIRE(p_hat && latency && gamma && t_offsets && total_M, SV_ERR_NULL);
   SV_REQUIRE(is_aligned(p_hat, 4) && is_aligned(latency, 4) && is_aligned(gamma, 4) &&

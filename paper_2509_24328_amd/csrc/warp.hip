@@ -8,19 +8,23 @@
 //   sweep 1  per-lane online (max, sum-exp): row maximum m, normaliser Z, bad-row
 //            detection; the 512 lane maxima are distinct entries of the row, so the
 //            K-th largest of them is a lower bound of the K-th largest entry
-//   select   tau = that bound (top-k), or the 384-th largest lane maximum (top-p
-//            alone: a guess that leaves a few hundred to a few thousand candidates)
+//   select   tau = that bound (top-k); top-p alone has no K: the 48-th largest lane
+//            maximum if those 48 already carry P of the row's mass, else the 256-th
+//            (a guess of how deep the nucleus reaches)
 //   sweep 2  (from cache) append every entry >= tau to a list in LDS
 //   settle   sort the list, read off the K-th largest value, walk the groups of equal
 //            value until their mass reaches P
 // The list is exact whenever it holds at least K entries and (top-p alone) at
-// least P of the row's mass.  Otherwise - flat rows, huge K, more than 2048
-// candidates - the general path takes over: radix selection on an order-preserving
-// 32-bit key of the logit (11 + 11 + 10 bits; bfloat16 rows are resolved after two
-// levels), one histogram sweep of counts and masses per level.
-// Masses are fp64 exponentials (candidate path; the row total of top-p alone comes
-// from the fp32 sweep) or fp32 ones summed with LDS float atomics (general path); a
-// top-p decision within 3e-6 of P is flagged SV_FLAG_NEAR_TIE.
+// least P of the row's mass; a list that does not settle a top-p row is rebuilt
+// once with a lower tau (the 384-th lane maximum).  Otherwise - flat rows, huge K,
+// more than 2048 candidates - the general path takes over: radix selection on an
+// order-preserving 32-bit key of the logit (11 + 11 + 10 bits; bfloat16 rows are
+// resolved after two levels), one histogram sweep of counts and masses per level.
+// Masses are fp64 sums of exponentials everywhere: on the candidate path in a fixed
+// order (the row total of top-p alone comes from the fp32 sweep), on the general
+// path accumulated per bin with LDS fp64 atomics, i.e. in an order that can change
+// from run to run in the last bits; a top-p decision within 3e-6 of P is flagged
+// SV_FLAG_NEAR_TIE, which covers that by ten orders of magnitude.
 //
 // sv_warp_compact is the same kernel with one more step: the kept entries of a
 // settled list are the whole support of the warped distribution, so their token

@@ -74,6 +74,8 @@ def test_argument_errors_are_reported_before_any_launch():
     assert sl(nl=16) == Bd.SV_ERR_INVALID_ARG
     assert sl(B=Bd.SV_SELECT_MAX_KEYS + 1, k=1, nl=10000) == Bd.SV_ERR_TOO_LARGE
     assert sl(p=None) == Bd.SV_ERR_NULL
+    assert sl(B=0) == Bd.SV_OK and sl(B=0, p=None) == Bd.SV_OK      # empty batch: nothing to do, as in the other calls
+    assert sl(B=-1) == Bd.SV_ERR_INVALID_ARG
 
 
 def test_profile_pass_argument_errors():

@@ -125,6 +125,46 @@ def test_results_are_reproducible_run_to_run():
             assert np.array_equal(s1[n], s2[n], equal_nan=True)
 
 
+def test_kernels_with_floating_point_atomics_reproduce_their_outputs():
+    """Two kernels add floating-point numbers with atomics, in whatever order the hardware
+    serves them: the radix fallback of the warp kernel (fp64 bin masses in LDS) and the
+    profile histogram (fp64 per-cell sums of X in global memory).  What they hand on is
+    discrete or rounded far above that noise - a cutoff is a value of the row, and a top-p
+    decision within 3e-6 of P is flagged; counts are integers; the table is an fp32 mean -
+    so those outputs repeat bit for bit; the fp64 sums themselves repeat to 1e-15."""
+    P = H.sv()
+    rng = np.random.default_rng(12)
+    rows, V = 6, 40000
+    flat = (rng.standard_normal((rows, V)) * 0.01).astype(np.float32)    # flat rows take the radix path
+    z = H.dev(flat)
+    runs = []
+    for _ in range(4):
+        cut = torch.empty(rows, dtype=torch.float32, device="cuda")
+        fl = torch.zeros(rows, dtype=torch.int32, device="cuda")
+        P.sv_warp_cutoffs(z, 1.0, 0, 0.9, cut, fl)
+        torch.cuda.synchronize()
+        runs.append((cut.cpu().numpy(), fl.cpu().numpy()))
+    for c, f in runs[1:]:
+        assert np.array_equal(c, runs[0][0]) and np.array_equal(f, runs[0][1])
+    n, n_s, n_a, n_x = 6000, 7, 5, 9
+    S, A = rng.random(n).astype(np.float32), rng.random(n).astype(np.float32)
+    ratio = (rng.random(n) * 1.3).astype(np.float32)
+    es, ea = H.dev(np.linspace(0, 1, n_s + 1).astype(np.float32)), H.dev(np.linspace(0, 1, n_a + 1).astype(np.float32))
+    outs = []
+    for _ in range(4):
+        counts = torch.zeros((n_s, n_a, n_x), dtype=torch.int32, device="cuda")
+        sum_x = torch.zeros((n_s, n_a), dtype=torch.float64, device="cuda")
+        table = torch.empty((n_s, n_a), dtype=torch.float32, device="cuda")
+        info = torch.zeros(3, dtype=torch.float64, device="cuda")
+        P.sv_profile_accumulate(H.dev(S), H.dev(A), H.dev(ratio), es, ea, n_x, counts, sum_x)
+        P.sv_profile_finalize(counts, sum_x, table, info)
+        torch.cuda.synchronize()
+        outs.append((counts.cpu().numpy(), sum_x.cpu().numpy(), table.cpu().numpy(), info.cpu().numpy()))
+    for c, sx, t, i in outs[1:]:
+        assert np.array_equal(c, outs[0][0]) and np.array_equal(t, outs[0][2])
+        assert np.allclose(sx, outs[0][1], rtol=1e-15, atol=0) and np.allclose(i, outs[0][3], rtol=1e-13, atol=1e-15)
+
+
 @pytest.mark.parametrize("V,dtype", [(70000, torch.bfloat16), (40000, torch.float32), (152064, torch.bfloat16)])
 def test_row_stats_when_the_running_reference_has_to_move(V, dtype):
     """The online sum-exp of sv_row_stats rescales its per-lane sums whenever the running
