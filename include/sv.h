@@ -340,6 +340,24 @@ int sv_verify_sample_warped(const void* z_t, const int32_t* t_offsets_or_null, i
                             int32_t* out_tokens, int32_t* n_accept, uint32_t* flags,
                             float* ratio_or_null, void* ws, size_t ws_bytes, sv_stream_t stream);
 
+/*
+ * sv_accept_ratio on warped distributions, on the logits themselves (for rows
+ * whose support does not compact, and for profiles built without compaction):
+ * X = P_t(x) / P_d(x) of every drafted position with P_t = soft-max(z_t / T_t) over
+ * {v : z_t[v] >= cutoff_t[row]} and P_d likewise.
+ *   cutoff_t_or_null  [B * t_rows_per_seq] float in  one cutoff per row of z_t (dense
+ *        layout b * t_rows_per_seq + i), as written by sv_warp_cutoffs on z_t
+ *   cutoff_d_or_null  [B*k] float in
+ * +inf where the draft's support misses the token but the target's holds it, NaN
+ * where neither holds it.  Everything else is as for sv_accept_ratio.
+ */
+int sv_accept_ratio_warped(const void* z_t, int t_rows_per_seq, const void* z_d, const int32_t* x,
+                           int B, int k, int V, int dtype,
+                           float temperature_t, const float* cutoff_t_or_null,
+                           float temperature_d, const float* cutoff_d_or_null,
+                           float* ratio, uint32_t* flags_or_null,
+                           void* ws, size_t ws_bytes, sv_stream_t stream);
+
 /* ------------------------------------------------------------------------
  * The step on compacted supports.  With the paper's sampling hyper-parameters
  * (top-k 20, or top-p 0.6-0.9 at temperature 0.6-0.95) a warped distribution

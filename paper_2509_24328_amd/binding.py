@@ -30,7 +30,7 @@ EXPORTS = ("sv_strerror", "sv_workspace_bytes", "sv_row_stats", "sv_accept_estim
            "sv_quantile_edges", "sv_profile_accumulate", "sv_profile_finalize", "sv_warp_cutoffs",
            "sv_row_stats_warped", "sv_verify_sample_warped",
            "sv_warp_compact", "sv_row_stats_sparse", "sv_verify_sample_sparse", "sv_uniforms",
-           "sv_accept_ratio_sparse", "sv_verify_sample_static")
+           "sv_accept_ratio_sparse", "sv_verify_sample_static", "sv_accept_ratio_warped")
 SV_STATIC_SCRATCH_BYTES = 1 << 20
 (SV_KERNEL_ROW_STATS, SV_KERNEL_ACCEPT_ESTIMATE, SV_KERNEL_SELECT_LENGTH, SV_KERNEL_VERIFY_ROWS,
  SV_KERNEL_VERIFY_MASS, SV_KERNEL_VERIFY_PICK, SV_KERNEL_COUNT) = range(7)
@@ -60,6 +60,9 @@ lib.sv_verify_sample_static.argtypes = [_vp, _vp, _i, _vp, _vp, _vp, _i, _i, _i,
                                         ctypes.c_uint32, _vp, _vp, _vp, _vp, _vp]
 lib.sv_accept_ratio.restype = _i
 lib.sv_accept_ratio.argtypes = [_vp, _i, _vp, _vp, _i, _i, _i, _i, _vp, _vp, _vp, _sz, _vp]
+lib.sv_accept_ratio_warped.restype = _i
+lib.sv_accept_ratio_warped.argtypes = [_vp, _i, _vp, _vp, _i, _i, _i, _i, ctypes.c_float, _vp, ctypes.c_float, _vp,
+                                       _vp, _vp, _vp, _sz, _vp]
 lib.sv_quantile_edges.restype = _i
 lib.sv_quantile_edges.argtypes = [_vp, _i, _i, ctypes.c_float, ctypes.c_float, _vp, _vp]
 lib.sv_profile_accumulate.restype = _i
@@ -190,6 +193,15 @@ def sv_accept_ratio(z_t, z_d, x, ratio, flags=None, ws=None, stream=None):
     _check(lib.sv_accept_ratio(_ptr(z_t), z_t.shape[1], _ptr(z_d), _ptr(x), B, k, V, _dtype_tag(z_d),
                                _ptr(ratio), _ptr(flags), _ptr(ws), 0 if ws is None else ws.numel(),
                                _stream(stream)))
+
+
+def sv_accept_ratio_warped(z_t, z_d, x, temperature_t, cutoff_t, temperature_d, cutoff_d, ratio, flags=None,
+                           ws=None, stream=None):
+    B, k, V = z_d.shape
+    _check(lib.sv_accept_ratio_warped(_ptr(z_t), z_t.shape[1], _ptr(z_d), _ptr(x), B, k, V, _dtype_tag(z_d),
+                                      temperature_t, _ptr(cutoff_t), temperature_d, _ptr(cutoff_d),
+                                      _ptr(ratio), _ptr(flags), _ptr(ws), 0 if ws is None else ws.numel(),
+                                      _stream(stream)))
 
 
 def sv_quantile_edges(values, n_bins, lo, hi, edges, stream=None):

@@ -682,10 +682,13 @@ extern "C" int sv_verify_sample_warped(const void* z_t, const int32_t* t_offsets
                                flags, ratio_or_null, ws, ws_bytes, stream);
 }
 
-extern "C" int sv_accept_ratio(const void* z_t, int t_rows_per_seq, const void* z_d, const int32_t* x,
-                               int B, int k, int V, int dtype, float* ratio, uint32_t* flags_or_null,
-                               void* ws, size_t ws_bytes, sv_stream_t stream) {
-  using namespace sv;
+namespace sv {
+// Argument checks and launch shared by sv_accept_ratio (T = 1, no cutoffs) and
+// sv_accept_ratio_warped.
+static int accept_ratio_checked(const void* z_t, int t_rows_per_seq, const void* z_d, const int32_t* x,
+                                int B, int k, int V, int dtype, const Scale& sc_t, const float* cut_t,
+                                const Scale& sc_d, const float* cut_d, float* ratio, uint32_t* flags,
+                                void* ws, size_t ws_bytes, sv_stream_t stream) {
   SV_REQUIRE(dtype == SV_F32 || dtype == SV_BF16, SV_ERR_DTYPE);
   SV_REQUIRE(B >= 0 && k >= 1 && V >= 1, SV_ERR_INVALID_ARG);
   SV_REQUIRE(t_rows_per_seq == k || t_rows_per_seq == k + 1, SV_ERR_INVALID_ARG);
@@ -694,7 +697,7 @@ extern "C" int sv_accept_ratio(const void* z_t, int t_rows_per_seq, const void* 
   SV_REQUIRE(z_t && z_d && x && ratio, SV_ERR_NULL);
   const int eb = elem_bytes(dtype);
   SV_REQUIRE(is_aligned(z_t, eb) && is_aligned(z_d, eb) && is_aligned(x, 4) && is_aligned(ratio, 4) &&
-                 is_aligned(flags_or_null, 4),
+                 is_aligned(flags, 4) && is_aligned(cut_t, 4) && is_aligned(cut_d, 4),
              SV_ERR_ALIGN);
   SV_REQUIRE(ws && is_aligned(ws, kWsAlign) && ws_bytes >= sv_workspace_bytes(B, k, V, dtype),
              SV_ERR_WORKSPACE);
@@ -705,18 +708,45 @@ extern "C" int sv_accept_ratio(const void* z_t, int t_rows_per_seq, const void* 
   a.split = rows_split(B * 2 * k, V);
   a.t_seq_rows = t_rows_per_seq;
   a.with_bonus = 0;
-  a.sc_t = unit_scale(); a.sc_d = unit_scale();
+  a.sc_t = sc_t; a.sc_d = sc_d; a.cut_t = cut_t; a.cut_d = cut_d;
   a.ws = carve_verify_ws(ws, B, k, V);
   hipStream_t st = as_stream(stream);
   const int rows = B * (2 * k + 1);               // the bonus slots exit at once
+  const bool cut = cut_t || cut_d;
   {
     TapScope tap(SV_KERNEL_VERIFY_ROWS, st);
-    if (dtype == SV_F32)
-      hipLaunchKernelGGL((verify_rows_kernel<DT_F32, false>), dim3(rows * a.split), dim3(kRowsThreads), 0, st, a);
-    else
-      hipLaunchKernelGGL((verify_rows_kernel<DT_BF16, false>), dim3(rows * a.split), dim3(kRowsThreads), 0, st, a);
+    const dim3 grid(rows * a.split), block(kRowsThreads);
+    if (dtype == SV_F32) {
+      if (cut) hipLaunchKernelGGL((verify_rows_kernel<DT_F32, true>), grid, block, 0, st, a);
+      else hipLaunchKernelGGL((verify_rows_kernel<DT_F32, false>), grid, block, 0, st, a);
+    } else {
+      if (cut) hipLaunchKernelGGL((verify_rows_kernel<DT_BF16, true>), grid, block, 0, st, a);
+      else hipLaunchKernelGGL((verify_rows_kernel<DT_BF16, false>), grid, block, 0, st, a);
+    }
   }
   if (launch_status() != SV_OK) return SV_ERR_LAUNCH;
-  hipLaunchKernelGGL(accept_ratio_kernel, dim3(B), dim3(kWave), 0, st, a, ratio, flags_or_null);
+  hipLaunchKernelGGL(accept_ratio_kernel, dim3(B), dim3(kWave), 0, st, a, ratio, flags);
   return launch_status();
+}
+}  // namespace sv
+
+extern "C" int sv_accept_ratio(const void* z_t, int t_rows_per_seq, const void* z_d, const int32_t* x,
+                               int B, int k, int V, int dtype, float* ratio, uint32_t* flags_or_null,
+                               void* ws, size_t ws_bytes, sv_stream_t stream) {
+  using namespace sv;
+  return accept_ratio_checked(z_t, t_rows_per_seq, z_d, x, B, k, V, dtype, unit_scale(), nullptr, unit_scale(),
+                              nullptr, ratio, flags_or_null, ws, ws_bytes, stream);
+}
+
+extern "C" int sv_accept_ratio_warped(const void* z_t, int t_rows_per_seq, const void* z_d, const int32_t* x,
+                                      int B, int k, int V, int dtype,
+                                      float temperature_t, const float* cutoff_t_or_null,
+                                      float temperature_d, const float* cutoff_d_or_null,
+                                      float* ratio, uint32_t* flags_or_null,
+                                      void* ws, size_t ws_bytes, sv_stream_t stream) {
+  using namespace sv;
+  Scale sc_t, sc_d;
+  SV_REQUIRE(scale_of(temperature_t, &sc_t) && scale_of(temperature_d, &sc_d), SV_ERR_INVALID_ARG);
+  return accept_ratio_checked(z_t, t_rows_per_seq, z_d, x, B, k, V, dtype, sc_t, cutoff_t_or_null, sc_d,
+                              cutoff_d_or_null, ratio, flags_or_null, ws, ws_bytes, stream);
 }

@@ -279,3 +279,48 @@ def test_extreme_temperatures(T):
                     assert np.array_equal(tok[b, i, :count[b, i]], keep)
                     e = np.exp(y_d[b, i][keep] - y_d[b, i].max())
                     assert np.allclose(prob[b, i, :count[b, i]], e / e.sum(), rtol=1e-12, atol=0)
+
+
+@pytest.mark.parametrize("T,K,Pp", SERIES)
+@pytest.mark.parametrize("t_rows", ["k", "k+1"])
+def test_accept_ratio_warped_every_position(T, K, Pp, t_rows):
+    """X = P_t(x) / P_d(x) of every drafted position under the warped distributions, on the
+    logits themselves (profiles for rows that do not compact), against the oracle's ratio on
+    warped rows; drafted tokens both from the unwarped and from the warped draft distribution,
+    with the oracle's own cutoffs and with those of sv_warp_cutoffs."""
+    from oracle import profile_oracle as PO
+    P = H.sv()
+    T = _t32(T)
+    B, k, V = 5, 4, 30000
+    cfg = svgen.make_config(3, seed=640, B=B, k=k, V=V, dtype="bf16", device="cuda")
+    z_t = cfg["z_t"] if t_rows == "k+1" else cfg["z_t"][:, :k].contiguous()
+    inp = H.oracle_inputs(cfg)
+    y_t, c_t, f_t = W.warp_rows(svgen.to_numpy_bits(z_t), T, K, Pp)
+    y_d, c_d, f_d = W.warp_rows(inp["z_d"], T, K, Pp)
+    ws = P.alloc_workspace(B, k, V, P.SV_BF16)
+    rng = np.random.default_rng(3)
+    x_warped = inp["x"].copy()
+    for b in range(B):                     # a token of the warped draft's support for half of the positions
+        for i in range(0, k, 2):
+            x_warped[b, i] = rng.choice(np.nonzero(np.isfinite(y_d[b, i]))[0])
+    gcut_t = torch.empty(z_t.shape[0] * z_t.shape[1], dtype=torch.float32, device="cuda")
+    gcut_d = torch.empty(B * k, dtype=torch.float32, device="cuda")
+    gf_t, gf_d = torch.zeros_like(gcut_t, dtype=torch.int32), torch.zeros_like(gcut_d, dtype=torch.int32)
+    P.sv_warp_cutoffs(z_t, T, K, Pp, gcut_t, gf_t)
+    P.sv_warp_cutoffs(cfg["z_d"], T, K, Pp, gcut_d, gf_d)
+    checked = 0
+    for x in (inp["x"], x_warped):
+        ref, _ = PO.accept_probability_ratio(y_t, y_d, x)
+        for cuts in ((_cut32(c_t), _cut32(c_d)), (gcut_t, gcut_d)):
+            ratio = torch.full((B, k), -5.0, dtype=torch.float32, device="cuda")
+            flags = torch.full((B, k), 77, dtype=torch.int32, device="cuda")
+            P.sv_accept_ratio_warped(z_t, cfg["z_d"], H.dev(x, torch.int32), T, cuts[0], T, cuts[1], ratio, flags, ws)
+            torch.cuda.synchronize()
+            got, fl = ratio.cpu().numpy(), flags.cpu().numpy()
+            tie = ((f_t[:, :k] | f_d | gf_t.cpu().numpy().reshape(B, -1)[:, :k].astype(np.uint32)
+                    | gf_d.cpu().numpy().reshape(B, k).astype(np.uint32)) & O.FLAG_NEAR_TIE) != 0
+            assert (fl == 0).all()
+            ok = ~tie
+            assert H.close(got[ok], np.asarray(ref)[ok], H.REL, 1e-30).all(), (got[ok], np.asarray(ref)[ok])
+            checked += int(ok.sum())
+    assert checked >= 3 * B * k
