@@ -45,7 +45,6 @@ namespace sv {
 constexpr int kRowsThreads = 256;
 constexpr int kSampleThreads = 256;             // mass kernel: one workgroup per chunk
 constexpr int kPickThreads = 1024;              // pick kernel: one workgroup per sequence
-constexpr int kSeg = kChunk / kPickThreads;     // contiguous weights per thread in the final scan
 constexpr int kMaxChunks = 2048;                // V <= kMaxChunks * kChunk
 static_assert(kMaxSplit == kMaxParts, "fold_row_parts reads up to kMaxParts partials of a row");
 
@@ -121,48 +120,68 @@ __device__ __forceinline__ MS draft_ms(const VerifyArgs& a, int b, int i) {
 // ---------------------------------------------------------------------------
 // kernel 1: row normalisers
 // ---------------------------------------------------------------------------
+// What one workgroup of the row sweep is about and what it found.
+struct RowPart {
+  int b, i, part;
+  bool is_target, needed;
+  MS ms;          // (m, s) of this part of the row
+  float zx;       // logit of the drafted token (part 0 of rows i < k), else NaN
+};
+
+// The sweep of one part of one needed row by the whole workgroup (results in thread 0).
+template <int DT, bool CUT>
+__device__ __forceinline__ RowPart sweep_row_part(const VerifyArgs& a, MergeScratch<1>& sm) {
+  RowPart r;
+  const int per_seq = 2 * a.k + 1;
+  const int slot = blockIdx.x / a.split;
+  r.part = blockIdx.x - slot * a.split;
+  r.b = slot / per_seq;
+  const int q = slot - r.b * per_seq;
+  r.is_target = q <= a.k;
+  r.i = r.is_target ? q : q - (a.k + 1);
+  const int g = gamma_of(a, r.b);
+  r.needed = r.i < (r.is_target ? g + a.with_bonus : g);
+  r.zx = __builtin_nanf("");
+  if (!r.needed) return r;                               // no bytes read
+
+  const void* row = r.is_target ? target_row<DT>(a, r.b, r.i) : draft_row<DT>(a, r.b, r.i);
+  const float L = r.is_target ? a.sc_t.L : a.sc_d.L;
+  float cut = -INFINITY;
+  if (CUT) cut = r.is_target ? target_cut(a, r.b, r.i) : draft_cut(a, r.b, r.i);
+  Online acc[1];
+  acc[0].init();
+  if (row) sweep_online<DT, CUT>(row, a.V, r.part, a.split, acc[0], L, cut);
+  MS merged[1];
+  block_merge<1>(acc, sm, merged, L);
+  r.ms = merged[0];                                      // s = 0 for a missing row => bad row
+  if (threadIdx.x == 0 && r.part == 0 && r.i < a.k && row) {
+    const int tok = a.x[r.b * a.k + r.i];
+    if (tok >= 0 && tok < a.V) r.zx = load_elem<DT>(row, tok);
+    if (CUT) r.zx = cut_below(r.zx, cut);
+  }
+  return r;
+}
+
+// Thread 0 leaves the part's results in the workspace.
+__device__ __forceinline__ void store_row_part(const VerifyArgs& a, const RowPart& r) {
+  if (r.is_target) {
+    const int idx = (r.b * (a.k + 1) + r.i) * a.split + r.part;
+    a.ws.m_t[idx] = r.ms.m;
+    a.ws.s_t[idx] = r.ms.s;
+    if (r.part == 0 && r.i < a.k) a.ws.zx_t[r.b * a.k + r.i] = r.zx;
+  } else {
+    const int idx = (r.b * a.k + r.i) * a.split + r.part;
+    a.ws.m_d[idx] = r.ms.m;
+    a.ws.s_d[idx] = r.ms.s;
+    if (r.part == 0) a.ws.zx_d[r.b * a.k + r.i] = r.zx;
+  }
+}
+
 template <int DT, bool CUT>
 __global__ __launch_bounds__(kRowsThreads) void verify_rows_kernel(VerifyArgs a) {
   __shared__ MergeScratch<1> sm;
-  const int per_seq = 2 * a.k + 1;
-  const int slot = blockIdx.x / a.split;
-  const int part = blockIdx.x - slot * a.split;
-  const int b = slot / per_seq;
-  const int r = slot - b * per_seq;
-  const bool is_target = r <= a.k;
-  const int i = is_target ? r : r - (a.k + 1);
-  const int g = gamma_of(a, b);
-  if (i >= (is_target ? g + a.with_bonus : g)) return;   // not needed: no bytes read
-
-  const void* row = is_target ? target_row<DT>(a, b, i) : draft_row<DT>(a, b, i);
-  const float L = is_target ? a.sc_t.L : a.sc_d.L;
-  float cut = -INFINITY;
-  if (CUT) cut = is_target ? target_cut(a, b, i) : draft_cut(a, b, i);
-  Online acc[1];
-  acc[0].init();
-  if (row) sweep_online<DT, CUT>(row, a.V, part, a.split, acc[0], L, cut);
-  MS merged[1];
-  block_merge<1>(acc, sm, merged, L);
-  const MS ms = merged[0];
-  if (threadIdx.x == 0) {
-    float zx = __builtin_nanf("");
-    if (part == 0 && i < a.k && row) {
-      const int tok = a.x[b * a.k + i];
-      if (tok >= 0 && tok < a.V) zx = load_elem<DT>(row, tok);
-      if (CUT) zx = cut_below(zx, cut);
-    }
-    if (is_target) {
-      const int idx = (b * (a.k + 1) + i) * a.split + part;
-      a.ws.m_t[idx] = ms.m;
-      a.ws.s_t[idx] = ms.s;                 // s = 0 for a missing row => bad row
-      if (part == 0 && i < a.k) a.ws.zx_t[b * a.k + i] = zx;
-    } else {
-      const int idx = (b * a.k + i) * a.split + part;
-      a.ws.m_d[idx] = ms.m;
-      a.ws.s_d[idx] = ms.s;
-      if (part == 0) a.ws.zx_d[b * a.k + i] = zx;
-    }
-  }
+  const RowPart r = sweep_row_part<DT, CUT>(a, sm);
+  if (r.needed && threadIdx.x == 0) store_row_part(a, r);
 }
 
 // ---------------------------------------------------------------------------
@@ -198,10 +217,6 @@ struct ProbRow {
     return e > 0.f ? __builtin_fmaf(e, (float)kLn2 * r, e) : 0.f;   // z = -inf: a is -inf or NaN, mass is 0
   }
 };
-
-// LDS position of weight p: one padding word per kSeg so that threads walking
-// their own contiguous kSeg-entry segments hit different banks.
-__device__ __forceinline__ int skew(int p) { return p + p / kSeg; }
 
 // grid (B), one wavefront: p_t(x)/p_d(x) of EVERY drafted position (profiling
 // pass: no early stop, no sampling), from the row partials of verify_rows_kernel.
@@ -319,23 +334,13 @@ __device__ __forceinline__ void accept_plan(const VerifyArgs& a, const int b, co
   }
 }
 
-struct MassShared {
-  BlockScratch red;
-  Plan plan;
-};
-
-// grid (chunks, B): the accept decision of the sequence (every workgroup forms it for
-// itself, chunk 0 publishes it), then the residual and target mass of one chunk of the
-// sampling row.
+// Residual and target mass of chunk c of the sampling row of sequence b, by the whole
+// workgroup (results in every thread).  fp64 sums of the fp32 weights: the pick stage forms
+// the same weights again and adds them in another order, and the two must agree far inside
+// the band of SV_FLAG_NEAR_CDF_EDGE.
 template <int DT, bool CUT>
-__global__ __launch_bounds__(kSampleThreads) void verify_mass_kernel(VerifyArgs a) {
-  __shared__ MassShared sh;
-  const int b = blockIdx.y, c = blockIdx.x, C = gridDim.x;
-  const int tid = threadIdx.x;
-  const int V = a.V;
-  if (tid < kWave) accept_plan<DT>(a, b, tid, c == 0, &sh.plan);
-  __syncthreads();
-  const Plan pl = sh.plan;
+__device__ __forceinline__ void chunk_masses(const VerifyArgs& a, int b, const Plan& pl, int c, BlockScratch& red,
+                                             double* mass_r, double* mass_t) {
   const int n = pl.n;
   const bool target_ok = pl.target_ok != 0, resid = pl.resid != 0;
   const void* row_t = target_row<DT>(a, b, n);
@@ -345,10 +350,7 @@ __global__ __launch_bounds__(kSampleThreads) void verify_mass_kernel(VerifyArgs 
   pd.set(pl.lse_d, a.sc_d);
   float cut_t = -INFINITY, cut_d = -INFINITY;
   if (CUT) { cut_t = target_cut(a, b, n); if (resid) cut_d = draft_cut(a, b, n); }
-
-  const int v0 = c * kChunk, v1 = min(V, v0 + kChunk);
-  // fp64 sums of the fp32 weights: the pick kernel forms the same weights again and adds them
-  // in another order, and the two must agree far inside the band of SV_FLAG_NEAR_CDF_EDGE
+  const int v0 = c * kChunk, v1 = min(a.V, v0 + kChunk);
   double acc_r = 0.0, acc_t = 0.0;
   if (target_ok) {
     if (resid) {
@@ -365,19 +367,41 @@ __global__ __launch_bounds__(kSampleThreads) void verify_mass_kernel(VerifyArgs 
       });
     }
   }
-  const double mass_r = block_sum_f64(acc_r, sh.red);
-  const double mass_t = block_sum_f64(acc_t, sh.red);
+  *mass_r = block_sum_f64(acc_r, red);
+  *mass_t = block_sum_f64(acc_t, red);
+}
+
+struct MassShared {
+  BlockScratch red;
+  Plan plan;
+};
+
+// grid (chunks, B): the accept decision of the sequence (every workgroup forms it for
+// itself, chunk 0 publishes it), then the residual and target mass of one chunk of the
+// sampling row.
+template <int DT, bool CUT>
+__global__ __launch_bounds__(kSampleThreads) void verify_mass_kernel(VerifyArgs a) {
+  __shared__ MassShared sh;
+  const int b = blockIdx.y, c = blockIdx.x, C = gridDim.x;
+  const int tid = threadIdx.x;
+  if (tid < kWave) accept_plan<DT>(a, b, tid, c == 0, &sh.plan);
+  __syncthreads();
+  const Plan pl = sh.plan;
+  double mass_r, mass_t;
+  chunk_masses<DT, CUT>(a, b, pl, c, sh.red, &mass_r, &mass_t);
   if (tid == 0) {
     a.ws.mass_r[b * C + c] = mass_r;
     a.ws.mass_t[b * C + c] = mass_t;
   }
 }
 
+template <int THREADS>
 struct PickShared {
+  static constexpr int kSegT = kChunk / THREADS;      // contiguous weights per thread in the final scan
   BlockScratch red;
   union {
-    float w[kChunk + kChunk / kSeg];  // weights of the located chunk (skewed)
-    double mass[2 * kMaxChunks];    // before that: residual / target mass of every chunk
+    float w[kChunk + kChunk / kSegT];  // weights of the located chunk (skewed)
+    double mass[2 * kMaxChunks];     // before that: residual / target mass of every chunk
   };
   uint32_t flags;
   int chunk;
@@ -386,18 +410,18 @@ struct PickShared {
   double tau_local;
   double W;
 };
-static_assert(sizeof(double) * 2 * kMaxChunks <= sizeof(float) * (kChunk + kChunk / kSeg), "mass fits under w");
 
-// grid (B): scan the chunk masses of the sequence, locate the chunk holding
+// The token of sequence b from the chunk masses in sh.mass ([0, C) residual, [C, 2C) target;
+// filled and visible to the whole workgroup of THREADS lanes): locate the chunk holding
 // u' * W, stage its weights in LDS and find the token with a block prefix scan.
-template <int DT, bool CUT>
-__global__ __launch_bounds__(kPickThreads) void verify_pick_kernel(VerifyArgs a, int C) {
-  __shared__ PickShared sh;
-  SV_PHASE_MARK(0)
-  const int b = blockIdx.x;
+template <int DT, bool CUT, int THREADS>
+__device__ __forceinline__ void pick_token(const VerifyArgs& a, const int b, const Plan& pl, PickShared<THREADS>& sh,
+                                           const int C) {
+  constexpr int kSegT = PickShared<THREADS>::kSegT;
+  static_assert(sizeof(double) * 2 * kMaxChunks <= sizeof(float) * (kChunk + kChunk / kSegT), "mass fits under w");
+  auto skew = [](int p) { return p + p / kSegT; };     // one padding word per segment: segment walks hit different banks
   const int tid = threadIdx.x;
   const int k = a.k, V = a.V;
-  const Plan pl = a.ws.plan[b];
   const int n = pl.n;
   const bool target_ok = pl.target_ok != 0;
   const bool resid = pl.resid != 0;
@@ -408,13 +432,6 @@ __global__ __launch_bounds__(kPickThreads) void verify_pick_kernel(VerifyArgs a,
   pd.set(resid ? pl.lse_d : 0.0, a.sc_d);
   float cut_t = -INFINITY, cut_d = -INFINITY;
   if (CUT) { cut_t = target_cut(a, b, n); if (resid) cut_d = draft_cut(a, b, n); }
-
-  for (int j = tid; j < C; j += blockDim.x) {          // all chunk masses in one round of loads
-    sh.mass[j] = a.ws.mass_r[(size_t)b * C + j];
-    sh.mass[C + j] = a.ws.mass_t[(size_t)b * C + j];
-  }
-  __syncthreads();
-  SV_PHASE_MARK(1)
   if (tid == 0) {
     uint32_t flags = pl.flags;
     const double* mr = sh.mass;
@@ -449,7 +466,7 @@ __global__ __launch_bounds__(kPickThreads) void verify_pick_kernel(VerifyArgs a,
     sh.use_resid = use_resid;
     sh.W = W;
     sh.flags = flags;
-    sh.found_thread = kPickThreads;
+    sh.found_thread = THREADS;
   }
   __syncthreads();
   SV_PHASE_MARK(2)
@@ -464,7 +481,7 @@ __global__ __launch_bounds__(kPickThreads) void verify_pick_kernel(VerifyArgs a,
 
   // stage the chunk's weights in LDS in vocabulary order
   const int w0 = chunk * kChunk, w1 = min(V, w0 + kChunk);
-  for (int j = (w1 - w0) + tid; j < kChunk; j += blockDim.x) sh.w[skew(j)] = 0.f;
+  for (int j = (w1 - w0) + tid; j < kChunk; j += THREADS) sh.w[skew(j)] = 0.f;
   if (use_resid) {
     visit_range<DT, true, 4>(row_t, row_d, w0, w1, [&](int v, float zt, float zd) {
       if (CUT) { zt = cut_below(zt, cut_t); zd = cut_below(zd, cut_d); }
@@ -480,11 +497,11 @@ __global__ __launch_bounds__(kPickThreads) void verify_pick_kernel(VerifyArgs a,
   SV_PHASE_MARK(3)
 
   // block prefix scan over contiguous per-thread segments (fp64)
-  static_assert(kSeg * kPickThreads == kChunk && (kSeg & (kSeg - 1)) == 0, "one segment per thread");
-  const float* wseg = sh.w + tid * (kSeg + 1);         // this thread's segment, skewed
+  static_assert(kSegT * THREADS == kChunk && (kSegT & (kSegT - 1)) == 0, "one segment per thread");
+  const float* wseg = sh.w + tid * (kSegT + 1);         // this thread's segment, skewed
   double seg_sum = 0.0;
 #pragma unroll 8
-  for (int j = 0; j < kSeg; ++j) seg_sum += (double)wseg[j];
+  for (int j = 0; j < kSegT; ++j) seg_sum += (double)wseg[j];
   // inclusive scan inside the wavefront, then across wavefronts through LDS
   double incl = seg_sum;
   const int lane = tid & 63, wave = tid >> 6;
@@ -509,18 +526,18 @@ __global__ __launch_bounds__(kPickThreads) void verify_pick_kernel(VerifyArgs a,
   __syncthreads();
   SV_PHASE_MARK(4)
   int owner = sh.found_thread;
-  const bool beyond = owner >= kPickThreads;
-  if (beyond) owner = kPickThreads - 1;
+  const bool beyond = owner >= THREADS;
+  if (beyond) owner = THREADS - 1;
   if (tid != owner) return;
 
   const double W = sh.W;
   double run = excl, prev = excl;
   int y = -1;
   if (!beyond) {
-    for (int j = 0; j < kSeg; ++j) {
+    for (int j = 0; j < kSegT; ++j) {
       prev = run;
       run += (double)wseg[j];
-      if (run > tau_local) { y = tid * kSeg + j; break; }
+      if (run > tau_local) { y = tid * kSegT + j; break; }
     }
   }
   uint32_t fl = sh.flags;
@@ -530,11 +547,27 @@ __global__ __launch_bounds__(kPickThreads) void verify_pick_kernel(VerifyArgs a,
     // rounding left no entry whose running sum passes the threshold: take the
     // last positive-weight entry at or before the end of this segment
     fl |= SV_FLAG_NEAR_CDF_EDGE;
-    for (int p = (tid + 1) * kSeg - 1; p >= 0; --p)
+    for (int p = (tid + 1) * kSegT - 1; p >= 0; --p)
       if (sh.w[skew(p)] > 0.f) { y = p; break; }
   }
   if (y >= 0) out[n] = w0 + y; else fl |= SV_FLAG_BAD_ROW;   // y < 0: the chunk holds no mass at all
   a.flags[b] = fl;
+}
+
+// grid (B): the chunk masses of the sequence from the workspace, then the token.
+template <int DT, bool CUT>
+__global__ __launch_bounds__(kPickThreads) void verify_pick_kernel(VerifyArgs a, int C) {
+  __shared__ PickShared<kPickThreads> sh;
+  SV_PHASE_MARK(0)
+  const int b = blockIdx.x;
+  const Plan pl = a.ws.plan[b];
+  for (int j = threadIdx.x; j < C; j += kPickThreads) {          // all chunk masses in one round of loads
+    sh.mass[j] = a.ws.mass_r[(size_t)b * C + j];
+    sh.mass[C + j] = a.ws.mass_t[(size_t)b * C + j];
+  }
+  __syncthreads();
+  SV_PHASE_MARK(1)
+  pick_token<DT, CUT, kPickThreads>(a, b, pl, sh, C);
   SV_PHASE_MARK(5)
 }
 
