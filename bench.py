@@ -555,10 +555,10 @@ def main():
             c0 = dict(c0, z_t=cpu_cfg["z_t"].cuda())
         cut_t, cut_d, cut_c = f32(B * (k + 1)), f32(B * k), f32(B * k)
 
+        w_zs, w_cuts = [c0["z_t"], c0["z_d"], c0["z_c"]], [cut_t, cut_d, cut_c]
+
         def warped_once(i):
-            P.sv_warp_cutoffs(c0["z_t"], wT, wK, wP, cut_t, None, stream)
-            P.sv_warp_cutoffs(c0["z_d"], wT, wK, wP, cut_d, None, stream)
-            P.sv_warp_cutoffs(c0["z_c"], wT, wK, wP, cut_c, None, stream)
+            P.sv_warp_cutoffs_multi(w_zs, wT, wK, wP, w_cuts, None, stream)     # the three tensors in one launch
             P.sv_row_stats_warped(c0["z_d"], c0["z_c"], c0["x"], wT, cut_d, wT, cut_c, lse_d, lse_c, S, A,
                                   None, None, ws, stream)
             P.sv_accept_estimate(S, A, d_es, d_ea, d_tab, p_hat, None, stream)
@@ -577,19 +577,25 @@ def main():
         w1 = time.perf_counter()
         ce0, ce1 = hip.event(), hip.event()
         torch.cuda.synchronize()
-        # the cutoff pass alone (all three tensors), bracketed by events on the launch stream
+        # the cutoff pass alone (all three tensors in one launch), bracketed by events on the launch
+        # stream; then one launch per tensor for comparison
         hip.record(ce0, stream.cuda_stream)
-        P.sv_warp_cutoffs(c0["z_t"], wT, wK, wP, cut_t, None, stream)
-        P.sv_warp_cutoffs(c0["z_d"], wT, wK, wP, cut_d, None, stream)
-        P.sv_warp_cutoffs(c0["z_c"], wT, wK, wP, cut_c, None, stream)
+        P.sv_warp_cutoffs_multi(w_zs, wT, wK, wP, w_cuts, None, stream)
         hip.record(ce1, stream.cuda_stream)
         torch.cuda.synchronize()
         cut_us = hip.elapsed_ms(ce0, ce1) * 1e3
+        hip.record(ce0, stream.cuda_stream)
+        for z_, c_ in zip(w_zs, w_cuts):
+            P.sv_warp_cutoffs(z_, wT, wK, wP, c_, None, stream)
+        hip.record(ce1, stream.cuda_stream)
+        torch.cuda.synchronize()
+        cut3_us = hip.elapsed_ms(ce0, ce1) * 1e3
         warped_step = {"temperature": 0.7, "top_k": wK, "top_p": wP,
                        "ms_per_step": round((w1 - w0) * 1e3 / reps, 4),
                        "cutoff_pass_us": round(cut_us, 1),
                        "cutoff_rows": B * (3 * k + 1),
-                       "cutoff_pass_GBps": round(B * (3 * k + 1) * row_bytes / cut_us * 1e-3, 1)}
+                       "cutoff_pass_GBps": round(B * (3 * k + 1) * row_bytes / cut_us * 1e-3, 1),
+                       "cutoff_pass_one_launch_per_tensor_us": round(cut3_us, 1)}
 
         # the same warped step on compacted supports: one compaction pass per tensor, then
         # every later stage works on the few kept tokens of each row
@@ -599,9 +605,7 @@ def main():
         s_S, s_A = f32(B, k), f32(B, k)
 
         def sparse_once(i):
-            P.sv_warp_compact(c0["z_t"], wT, wK, wP, sup_t, None, None, stream)
-            P.sv_warp_compact(c0["z_d"], wT, wK, wP, sup_d, None, None, stream)
-            P.sv_warp_compact(c0["z_c"], wT, wK, wP, sup_c, None, None, stream)
+            P.sv_warp_compact_multi(w_zs, wT, wK, wP, [sup_t, sup_d, sup_c], None, None, stream)
             P.sv_row_stats_sparse(sup_d, sup_c, c0["x"], V, lse_d, lse_c, s_S, s_A, None, None, stream)
             P.sv_accept_estimate(s_S, s_A, d_es, d_ea, d_tab, p_hat, None, stream)
             P.sv_select_length(p_hat, d_lat, P.SV_BATCH_GREEDY, gamma, offs, total, stream)

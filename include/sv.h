@@ -77,6 +77,8 @@ enum {
 #define SV_SELECT_MAX_KEYS 8192
 /* Largest k accepted by sv_verify_sample. */
 #define SV_MAX_K 64
+/* Largest number of tensors one sv_warp_*_multi call takes. */
+#define SV_WARP_MAX_TENSORS 8
 /* Largest per-row capacity of a compacted support (sv_warp_compact). */
 #define SV_SUPPORT_MAX_CAP 1024
 
@@ -298,6 +300,23 @@ int sv_warp_cutoffs(const void* z, int rows, int V, int dtype,
                     float* cutoff, uint32_t* flags_or_null, sv_stream_t stream);
 
 /*
+ * sv_warp_cutoffs for up to SV_WARP_MAX_TENSORS logit tensors of one vocabulary size
+ * and dtype in one launch (the draft, companion and target logits of a step, each
+ * with the sampling hyper-parameters of its model series).  The rows are independent,
+ * so the results are those of one sv_warp_cutoffs call per tensor; one launch over
+ * all rows keeps the memory system busy while some rows are being decided.
+ *   n                         number of tensors
+ *   z, rows, temperature, top_k, top_p, cutoff, flags_or_null
+ *                             HOST arrays of length n holding, per tensor, the
+ *                             arguments of sv_warp_cutoffs (z[t], cutoff[t],
+ *                             flags_or_null[t] are device pointers; flags_or_null
+ *                             itself, or single entries of it, may be NULL)
+ */
+int sv_warp_cutoffs_multi(int n, const void* const* z, const int* rows, int V, int dtype,
+                          const float* temperature, const int* top_k, const float* top_p,
+                          float* const* cutoff, uint32_t* const* flags_or_null, sv_stream_t stream);
+
+/*
  * sv_row_stats on warped distributions: P_d = soft-max(z_d / temperature_d) over
  * {v : z_d[v] >= cutoff_d[row]}, P_c likewise with its own temperature and
  * cutoffs (the draft and the companion are run with the sampling
@@ -385,6 +404,17 @@ int sv_warp_compact(const void* z, int rows, int V, int dtype,
                     float temperature, int top_k, float top_p, int cap,
                     int32_t* count, int32_t* token, double* prob, float* lse,
                     float* cutoff_or_null, uint32_t* flags_or_null, sv_stream_t stream);
+
+/*
+ * sv_warp_compact for up to SV_WARP_MAX_TENSORS tensors in one launch: HOST arrays of
+ * length n as in sv_warp_cutoffs_multi, plus the per-tensor output arrays of
+ * sv_warp_compact (one capacity for all).
+ */
+int sv_warp_compact_multi(int n, const void* const* z, const int* rows, int V, int dtype,
+                          const float* temperature, const int* top_k, const float* top_p, int cap,
+                          int32_t* const* count, int32_t* const* token, double* const* prob,
+                          float* const* lse, float* const* cutoff_or_null,
+                          uint32_t* const* flags_or_null, sv_stream_t stream);
 
 /*
  * sv_row_stats on compacted supports (draft and companion, one support per

@@ -30,7 +30,9 @@ EXPORTS = ("sv_strerror", "sv_workspace_bytes", "sv_row_stats", "sv_accept_estim
            "sv_quantile_edges", "sv_profile_accumulate", "sv_profile_finalize", "sv_warp_cutoffs",
            "sv_row_stats_warped", "sv_verify_sample_warped",
            "sv_warp_compact", "sv_row_stats_sparse", "sv_verify_sample_sparse", "sv_uniforms",
-           "sv_accept_ratio_sparse", "sv_verify_sample_static", "sv_accept_ratio_warped")
+           "sv_accept_ratio_sparse", "sv_verify_sample_static", "sv_accept_ratio_warped",
+           "sv_warp_cutoffs_multi", "sv_warp_compact_multi")
+SV_WARP_MAX_TENSORS = 8
 SV_STATIC_SCRATCH_BYTES = 1 << 20
 (SV_KERNEL_ROW_STATS, SV_KERNEL_ACCEPT_ESTIMATE, SV_KERNEL_SELECT_LENGTH, SV_KERNEL_VERIFY_ROWS,
  SV_KERNEL_VERIFY_MASS, SV_KERNEL_VERIFY_PICK, SV_KERNEL_COUNT) = range(7)
@@ -72,6 +74,10 @@ lib.sv_profile_finalize.argtypes = [_vp, _vp, _i, _i, _i, _vp, _vp, _vp]
 lib.sv_warp_cutoffs.restype = _i
 lib.sv_warp_cutoffs.argtypes = [_vp, _i, _i, _i, ctypes.c_float, _i, ctypes.c_float, _vp, _vp, _vp]
 _f = ctypes.c_float
+lib.sv_warp_cutoffs_multi.restype = _i
+lib.sv_warp_cutoffs_multi.argtypes = [_i, _vp, _vp, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp]
+lib.sv_warp_compact_multi.restype = _i
+lib.sv_warp_compact_multi.argtypes = [_i, _vp, _vp, _i, _i, _vp, _vp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.sv_row_stats_warped.restype = _i
 lib.sv_row_stats_warped.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _f, _vp, _f, _vp,
                                     _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
@@ -225,6 +231,43 @@ def sv_warp_cutoffs(z, temperature, top_k, top_p, cutoff, flags=None, stream=Non
     rows = z.numel() // V
     _check(lib.sv_warp_cutoffs(_ptr(z), rows, V, _dtype_tag(z), temperature, top_k, top_p, _ptr(cutoff),
                                _ptr(flags), _stream(stream)))
+
+
+def _host_ptrs(tensors):
+    """Host array of the device addresses of `tensors` (None entries -> NULL)."""
+    return (ctypes.c_void_p * len(tensors))(*[None if t is None else _ptr(t).value for t in tensors])
+
+
+def _warp_lists(zs, temperature, top_k, top_p):
+    n = len(zs)
+    V = zs[0].shape[-1]
+    tag = _dtype_tag(zs[0])
+    if any(z.shape[-1] != V or _dtype_tag(z) != tag for z in zs):
+        raise SvError(SV_ERR_INVALID_ARG)
+    as_list = lambda v: list(v) if isinstance(v, (list, tuple)) else [v] * n
+    rows = (ctypes.c_int * n)(*[z.numel() // V for z in zs])
+    T = (ctypes.c_float * n)(*as_list(temperature))
+    K = (ctypes.c_int * n)(*as_list(top_k))
+    Pp = (ctypes.c_float * n)(*as_list(top_p))
+    return n, V, tag, rows, T, K, Pp
+
+
+def sv_warp_cutoffs_multi(zs, temperature, top_k, top_p, cutoffs, flags=None, stream=None):
+    """zs, cutoffs (, flags): lists of tensors; temperature / top_k / top_p: one value or a list."""
+    n, V, tag, rows, T, K, Pp = _warp_lists(zs, temperature, top_k, top_p)
+    _check(lib.sv_warp_cutoffs_multi(n, _host_ptrs(zs), rows, V, tag, T, K, Pp, _host_ptrs(cutoffs),
+                                     None if flags is None else _host_ptrs(flags), _stream(stream)))
+
+
+def sv_warp_compact_multi(zs, temperature, top_k, top_p, sups, cutoffs=None, flags=None, stream=None):
+    n, V, tag, rows, T, K, Pp = _warp_lists(zs, temperature, top_k, top_p)
+    if any(s.cap != sups[0].cap or s.rows != z.numel() // V for s, z in zip(sups, zs)):
+        raise SvError(SV_ERR_INVALID_ARG)
+    _check(lib.sv_warp_compact_multi(n, _host_ptrs(zs), rows, V, tag, T, K, Pp, sups[0].cap,
+                                     _host_ptrs([s.count for s in sups]), _host_ptrs([s.token for s in sups]),
+                                     _host_ptrs([s.prob for s in sups]), _host_ptrs([s.lse for s in sups]),
+                                     None if cutoffs is None else _host_ptrs(cutoffs),
+                                     None if flags is None else _host_ptrs(flags), _stream(stream)))
 
 
 def sv_row_stats_warped(z_d, z_c, x, temperature_d, cutoff_d, temperature_c, cutoff_c, lse_d, lse_c, S, A,

@@ -356,13 +356,11 @@ __device__ __forceinline__ void sort_desc_runs(uint64_t* keys, uint64_t* tmp, in
 constexpr int kNucleusRank = 48;
 constexpr int kNucleusRank2 = 256;
 
+// One row (r of tensor z) by the whole workgroup.
 template <int DT>
-__global__ __launch_bounds__(kWarpThreads) void warp_cutoffs_kernel(const void* z, int V, Scale sc, int top_k,
-                                                                    float top_p, float* cutoff, uint32_t* flags,
-                                                                    CompactOut out) {
-  __shared__ WarpShared sh;
+__device__ __forceinline__ void warp_row(const void* z, const int r, int V, const Scale sc, int top_k, float top_p,
+                                         float* cutoff, uint32_t* flags, const CompactOut out, WarpShared& sh) {
   const int tid = threadIdx.x;
-  const int r = blockIdx.x;
   const void* row = static_cast<const char*>(z) + (size_t)r * V * Elem<DT>::bytes;
   const float lt = sc.L;
 
@@ -747,27 +745,78 @@ __global__ __launch_bounds__(kWarpThreads) void warp_cutoffs_kernel(const void* 
   SV_PHASE_MARK(7)
 }
 
+// Up to kWarpMaxTensors logit tensors of one vocabulary size in one launch (one workgroup
+// per row of any of them): with about two rows per compute unit all workgroups of a
+// launch sweep, then all decide, and the memory system idles meanwhile; more rows per
+// launch overlap the decisions of some rows with the sweeps of others.
+constexpr int kWarpMaxTensors = SV_WARP_MAX_TENSORS;
+struct WarpBatch {
+  int n;
+  int row_end[kWarpMaxTensors];          // running totals of the tensors' rows
+  const void* z[kWarpMaxTensors];
+  Scale sc[kWarpMaxTensors];
+  int top_k[kWarpMaxTensors];
+  float top_p[kWarpMaxTensors];
+  float* cutoff[kWarpMaxTensors];
+  uint32_t* flags[kWarpMaxTensors];
+  CompactOut out[kWarpMaxTensors];
+};
+
+template <int DT>
+__global__ __launch_bounds__(kWarpThreads) void warp_cutoffs_kernel(int V, WarpBatch b) {
+  __shared__ WarpShared sh;
+  int t = 0;
+  while (t + 1 < b.n && (int)blockIdx.x >= b.row_end[t]) ++t;
+  const int r = (int)blockIdx.x - (t ? b.row_end[t - 1] : 0);
+  warp_row<DT>(b.z[t], r, V, b.sc[t], b.top_k[t], b.top_p[t], b.cutoff[t], b.flags[t], b.out[t], sh);
+}
+
 }  // namespace sv
 
 namespace {
 
-int launch_warp(const void* z, int rows, int V, int dtype, float temperature, int top_k, float top_p,
-                float* cutoff, uint32_t* flags, const sv::CompactOut& out, sv_stream_t stream) {
+// Checks and launch of one or several tensors (arrays of length n on the host).
+int launch_warp(int n, const void* const* z, const int* rows, int V, int dtype, const float* temperature,
+                const int* top_k, const float* top_p, float* const* cutoff, uint32_t* const* flags,
+                const sv::CompactOut* outs, bool need_cutoff, sv_stream_t stream) {
   using namespace sv;
   SV_REQUIRE(dtype == SV_F32 || dtype == SV_BF16, SV_ERR_DTYPE);
-  SV_REQUIRE(rows >= 0 && V >= 1 && top_p > 0.f, SV_ERR_INVALID_ARG);
-  Scale sc;
-  SV_REQUIRE(scale_of(temperature, &sc), SV_ERR_INVALID_ARG);
-  if (rows == 0) return SV_OK;
-  SV_REQUIRE(z, SV_ERR_NULL);
-  SV_REQUIRE(is_aligned(z, elem_bytes(dtype)) && is_aligned(cutoff, 4) && is_aligned(flags, 4), SV_ERR_ALIGN);
+  SV_REQUIRE(n >= 1 && n <= kWarpMaxTensors && V >= 1, SV_ERR_INVALID_ARG);
+  WarpBatch b = {};
+  long long total = 0;
+  for (int t = 0; t < n; ++t) {
+    SV_REQUIRE(rows[t] >= 0 && top_p[t] > 0.f, SV_ERR_INVALID_ARG);
+    SV_REQUIRE(scale_of(temperature[t], &b.sc[t]), SV_ERR_INVALID_ARG);
+    if (rows[t] > 0) {
+      SV_REQUIRE(z[t] && (!need_cutoff || cutoff[t]), SV_ERR_NULL);
+      if (outs) SV_REQUIRE(outs[t].count && outs[t].token && outs[t].prob && outs[t].lse, SV_ERR_NULL);
+    }
+    SV_REQUIRE(is_aligned(z[t], elem_bytes(dtype)) && is_aligned(cutoff ? cutoff[t] : nullptr, 4) &&
+                   is_aligned(flags ? flags[t] : nullptr, 4),
+               SV_ERR_ALIGN);
+    if (outs) {
+      SV_REQUIRE(outs[t].cap >= 1 && outs[t].cap <= SV_SUPPORT_MAX_CAP, SV_ERR_INVALID_ARG);
+      SV_REQUIRE(is_aligned(outs[t].count, 4) && is_aligned(outs[t].token, 4) && is_aligned(outs[t].prob, 8) &&
+                     is_aligned(outs[t].lse, 4),
+                 SV_ERR_ALIGN);
+      b.out[t] = outs[t];
+    }
+    total += rows[t];
+    SV_REQUIRE(total <= 0x7fffffffLL, SV_ERR_TOO_LARGE);
+    b.row_end[t] = (int)total;
+    b.z[t] = z[t];
+    b.top_k[t] = top_k[t];
+    b.top_p[t] = top_p[t];
+    b.cutoff[t] = cutoff ? cutoff[t] : nullptr;
+    b.flags[t] = flags ? flags[t] : nullptr;
+  }
+  b.n = n;
+  if (total == 0) return SV_OK;
   hipStream_t st = as_stream(stream);
   if (dtype == SV_F32)
-    hipLaunchKernelGGL(warp_cutoffs_kernel<DT_F32>, dim3(rows), dim3(kWarpThreads), 0, st, z, V, sc, top_k, top_p,
-                       cutoff, flags, out);
+    hipLaunchKernelGGL(warp_cutoffs_kernel<DT_F32>, dim3((unsigned)total), dim3(kWarpThreads), 0, st, V, b);
   else
-    hipLaunchKernelGGL(warp_cutoffs_kernel<DT_BF16>, dim3(rows), dim3(kWarpThreads), 0, st, z, V, sc, top_k, top_p,
-                       cutoff, flags, out);
+    hipLaunchKernelGGL(warp_cutoffs_kernel<DT_BF16>, dim3((unsigned)total), dim3(kWarpThreads), 0, st, V, b);
   return launch_status();
 }
 
@@ -775,8 +824,16 @@ int launch_warp(const void* z, int rows, int V, int dtype, float temperature, in
 
 extern "C" int sv_warp_cutoffs(const void* z, int rows, int V, int dtype, float temperature, int top_k,
                                float top_p, float* cutoff, uint32_t* flags_or_null, sv_stream_t stream) {
-  SV_REQUIRE(cutoff || rows <= 0, SV_ERR_NULL);
-  return launch_warp(z, rows, V, dtype, temperature, top_k, top_p, cutoff, flags_or_null, sv::CompactOut{}, stream);
+  return launch_warp(1, &z, &rows, V, dtype, &temperature, &top_k, &top_p, &cutoff, &flags_or_null, nullptr, true,
+                     stream);
+}
+
+extern "C" int sv_warp_cutoffs_multi(int n, const void* const* z, const int* rows, int V, int dtype,
+                                     const float* temperature, const int* top_k, const float* top_p,
+                                     float* const* cutoff, uint32_t* const* flags_or_null, sv_stream_t stream) {
+  SV_REQUIRE(n >= 1 && n <= SV_WARP_MAX_TENSORS, SV_ERR_INVALID_ARG);
+  SV_REQUIRE(z && rows && temperature && top_k && top_p && cutoff, SV_ERR_NULL);
+  return launch_warp(n, z, rows, V, dtype, temperature, top_k, top_p, cutoff, flags_or_null, nullptr, true, stream);
 }
 
 extern "C" int sv_warp_compact(const void* z, int rows, int V, int dtype, float temperature, int top_k,
@@ -784,9 +841,21 @@ extern "C" int sv_warp_compact(const void* z, int rows, int V, int dtype, float 
                                float* cutoff_or_null, uint32_t* flags_or_null, sv_stream_t stream) {
   using namespace sv;
   SV_REQUIRE(cap >= 1 && cap <= SV_SUPPORT_MAX_CAP, SV_ERR_INVALID_ARG);
-  SV_REQUIRE((count && token && prob && lse) || rows <= 0, SV_ERR_NULL);
-  SV_REQUIRE(is_aligned(count, 4) && is_aligned(token, 4) && is_aligned(prob, 8) && is_aligned(lse, 4),
-             SV_ERR_ALIGN);
-  return launch_warp(z, rows, V, dtype, temperature, top_k, top_p, cutoff_or_null, flags_or_null,
-                     CompactOut{count, token, prob, lse, cap}, stream);
+  const CompactOut out{count, token, prob, lse, cap};
+  return launch_warp(1, &z, &rows, V, dtype, &temperature, &top_k, &top_p, &cutoff_or_null, &flags_or_null, &out,
+                     false, stream);
+}
+
+extern "C" int sv_warp_compact_multi(int n, const void* const* z, const int* rows, int V, int dtype,
+                                     const float* temperature, const int* top_k, const float* top_p, int cap,
+                                     int32_t* const* count, int32_t* const* token, double* const* prob,
+                                     float* const* lse, float* const* cutoff_or_null,
+                                     uint32_t* const* flags_or_null, sv_stream_t stream) {
+  using namespace sv;
+  SV_REQUIRE(n >= 1 && n <= SV_WARP_MAX_TENSORS, SV_ERR_INVALID_ARG);
+  SV_REQUIRE(z && rows && temperature && top_k && top_p && count && token && prob && lse, SV_ERR_NULL);
+  CompactOut outs[SV_WARP_MAX_TENSORS];
+  for (int t = 0; t < n; ++t) outs[t] = CompactOut{count[t], token[t], prob[t], lse[t], cap};
+  return launch_warp(n, z, rows, V, dtype, temperature, top_k, top_p, cutoff_or_null, flags_or_null, outs, false,
+                     stream);
 }

@@ -100,3 +100,49 @@ def test_wide_supports_of_nearly_flat_rows(dtype):
     for T, K, Pp in ((1000.0, 0, 0.9), (1.0, 0, 0.5), (100.0, 100000, 0.999), (10.0, 0, 0.01)):
         ties += _compare(t, T, K, Pp)
     assert ties <= 8
+
+
+def test_several_tensors_in_one_launch_equal_one_launch_each():
+    """sv_warp_cutoffs_multi / sv_warp_compact_multi: the draft, companion and target logits of a
+    step, each with its own hyper-parameters, in one launch: bit for bit what one call per tensor
+    gives (rows are independent)."""
+    P = H.sv()
+    B, k, V = 6, 3, 40000
+    cfg = svgen.make_config(3, seed=51, B=B, k=k, V=V, dtype="bf16", device="cuda")
+    zs = [cfg["z_t"], cfg["z_d"], cfg["z_c"]]
+    Ts, Ks, Ps = [0.7, 0.95, 0.6], [20, 50, 0], [0.8, 1.0, 0.9]
+    f32 = lambda n: torch.full((n,), -3.0, dtype=torch.float32, device="cuda")
+    i32 = lambda n: torch.full((n,), -3, dtype=torch.int32, device="cuda")
+    rows = [z.shape[0] * z.shape[1] for z in zs]
+    one = [(f32(r), i32(r)) for r in rows]
+    for z, T, K, Pp, (c, f) in zip(zs, Ts, Ks, Ps, one):
+        P.sv_warp_cutoffs(z, float(np.float32(T)), K, Pp, c, f)
+    many = [(f32(r), i32(r)) for r in rows]
+    P.sv_warp_cutoffs_multi(zs, [float(np.float32(T)) for T in Ts], Ks, Ps, [c for c, _ in many], [f for _, f in many])
+    torch.cuda.synchronize()
+    for (c1, f1), (c2, f2) in zip(one, many):
+        assert torch.equal(c1.view(torch.int32), c2.view(torch.int32)) and torch.equal(f1, f2)
+    # without flags, and with a single entry of the flag list missing
+    many2 = [f32(r) for r in rows]
+    P.sv_warp_cutoffs_multi(zs, 0.7, 20, 0.8, many2, None)
+    P.sv_warp_cutoffs_multi(zs, 0.7, 20, 0.8, many2, [None, i32(rows[1]), None])
+    # compaction
+    cap = 64
+    s1 = [P.Supports(r, cap) for r in rows]
+    s2 = [P.Supports(r, cap) for r in rows]
+    for s in s1 + s2:
+        s.count.fill_(-7); s.token.fill_(-7); s.prob.fill_(-7.0); s.lse.fill_(-7.0)
+    for z, T, K, Pp, s in zip(zs, Ts, Ks, Ps, s1):
+        P.sv_warp_compact(z, float(np.float32(T)), K, Pp, s)
+    P.sv_warp_compact_multi(zs, [float(np.float32(T)) for T in Ts], Ks, Ps, s2)
+    torch.cuda.synchronize()
+    for a, b in zip(s1, s2):
+        assert torch.equal(a.count, b.count) and torch.equal(a.token, b.token)
+        assert torch.equal(a.prob.view(torch.int64), b.prob.view(torch.int64))
+        assert torch.equal(a.lse.view(torch.int32), b.lse.view(torch.int32))
+    assert (s2[0].count > 0).all()
+    # limits
+    from paper_2509_24328_amd import binding as Bd
+    with pytest.raises(P.SvError) as e:
+        P.sv_warp_cutoffs_multi(zs * 3, 0.7, 20, 0.8, [f32(r) for r in rows * 3])
+    assert e.value.status == Bd.SV_ERR_INVALID_ARG
