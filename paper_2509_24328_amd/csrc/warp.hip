@@ -74,7 +74,6 @@ struct alignas(16) WarpShared {
       uint32_t cnt[kBins];
       double mass[kBins];      // fp64: a bin may collect 1e5 nearly equal terms (a flat row at a
                                // high temperature), whose fp32 sum would be off by 1e-4
-      double mass0[kBins];     // level-0 masses, kept for the top-p pass
     };
     struct {                   // candidate path
       uint64_t key[kCand];     // (order key of the value, ~token id): sorted descending
@@ -146,7 +145,6 @@ __device__ __noinline__ float general_cutoff(const void* row, int V, float lt, i
 
   // sweep 2: level 0 over everything
   histogram(0, 0u, -INFINITY);
-  for (int d = tid; d < kBins; d += blockDim.x) sh.mass0[d] = sh.mass[d];
   double total0 = 0.0;
   {
     double part = 0.0;
@@ -184,9 +182,12 @@ __device__ __noinline__ float general_cutoff(const void* row, int V, float lt, i
   float theta = t_k;
   if (use_p) {
     const double target = (double)top_p * total_k;
-    // level 0 from the saved masses: digits above dk0 survive whole, dk0 in part, below not at all
+    // level 0 again (the top-k levels have overwritten it; keeping a copy would cost the 16 KB of LDS
+    // that decide whether three or four workgroups fit a compute unit, and this path is the rare one):
+    // digits above dk0 survive whole, dk0 in part, below not at all
+    if (use_k) histogram(0, 0u, -INFINITY);
     for (int d = tid; d < kBins; d += blockDim.x) {
-      double mm = sh.mass0[d];
+      double mm = sh.mass[d];
       uint32_t c = mm > 0.0 ? 1u : 0u;             // counts only mark non-empty bins here
       if (use_k) {
         if (d < dk0) { mm = 0.0; c = 0u; }
@@ -762,8 +763,10 @@ struct WarpBatch {
   CompactOut out[kWarpMaxTensors];
 };
 
+// (8 wavefronts per SIMD = four workgroups per compute unit: the decisions of some rows overlap the
+// sweeps of others; needs <= 64 VGPRs and <= 40 KB of LDS)
 template <int DT>
-__global__ __launch_bounds__(kWarpThreads) void warp_cutoffs_kernel(int V, WarpBatch b) {
+__global__ __launch_bounds__(kWarpThreads, 8) void warp_cutoffs_kernel(int V, WarpBatch b) {
   __shared__ WarpShared sh;
   int t = 0;
   while (t + 1 < b.n && (int)blockIdx.x >= b.row_end[t]) ++t;
