@@ -55,6 +55,8 @@ def parse():
                     help="skip the timing of the profile-construction pass")
     ap.add_argument("--no-warped", action="store_true",
                     help="skip the timing of the step on temperature/top-k/top-p warped distributions")
+    ap.add_argument("--no-chained", action="store_true",
+                    help="skip the timing of the step with sv_verify_sample_chained")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for rocprofv3 byte counters)")
     return ap.parse_args()
@@ -197,6 +199,7 @@ class Runner:
         self.eb = 2 if self.desc["dtype"] == "bf16" else 4
         self.tag = P.SV_BF16 if self.eb == 2 else P.SV_F32
         self.ragged = ragged
+        self.chained = False     # True: sv_verify_sample_chained (draft normalisers from sv_row_stats)
         B, k, V = self.B, self.k, self.V
         self.copies = []
         if cpu_cfg is not None:      # copy 0 = the canonical CPU-seeded batch (the one the oracle gets)
@@ -242,12 +245,13 @@ class Runner:
 
     def verify(self, c, seed, step, s=None):
         P, s = self.P, (s or self.stream)
+        call = P.sv_verify_sample_chained if self.chained else P.sv_verify_sample
         if self.ragged:      # lengths and offsets as the selection left them on the device
-            P.sv_verify_sample(c["z_t_packed"], self.offs, c["z_d"], c["x"], self.gamma, seed, step,
-                               self.tokens, self.n_acc, self.flags, None, self.ws, s)
+            call(c["z_t_packed"], self.offs, c["z_d"], c["x"], self.gamma, seed, step,
+                 self.tokens, self.n_acc, self.flags, None, self.ws, s)
         else:
-            P.sv_verify_sample(c["z_t"], None, c["z_d"], c["x"], None, seed, step,
-                               self.tokens, self.n_acc, self.flags, None, self.ws, s)
+            call(c["z_t"], None, c["z_d"], c["x"], None, seed, step,
+                 self.tokens, self.n_acc, self.flags, None, self.ws, s)
 
     def step(self, i, seed=0, s=None):
         c = self.copies[i % len(self.copies)]
@@ -441,6 +445,36 @@ def main():
                   "gamma_equal": bool(np.array_equal(got["gamma"], ref["gamma"])),
                   "offsets_equal": bool(np.array_equal(got["t_offsets"], ref["t_offsets"]))}
         assert bad == 0 and s_err < 1e-5 and a_err < 1e-5 and parity["gamma_equal"], parity
+
+    # ---- the same step with sv_verify_sample_chained: the draft rows' normalisers come from what
+    # sv_row_stats left in the workspace, so verification sweeps the target rows only.  Reported
+    # beside the headline, which keeps the four independent calls and their byte count.
+    chained_step = None
+    if not args.no_chained:
+        run.chained = True
+        ch_ms = run.time_steps(args.warmup, args.steps)
+        ch_samples, ch_call = run.time_kernels(hip, Bd, args.steps)
+        run.step(0, seed=0)
+        torch.cuda.synchronize()
+        run.chained = False
+        ch = dict(tokens=tokens.cpu().numpy(), n_accept=n_acc.cpu().numpy(), flags=flags.cpu().numpy())
+        soft = ((ch["flags"] | got["flags"]) & (2 | 8)) != 0
+        same = bool(np.array_equal(ch["tokens"][~soft], got["tokens"][~soft]) and
+                    np.array_equal(ch["n_accept"][~soft], got["n_accept"][~soft]) and
+                    np.array_equal(ch["flags"][~soft], got["flags"][~soft]))
+        assert same and not (ch["flags"] & 64).any(), "chained verification differs from the plain call"
+        t_rows = (verify_rows + B) / 2                      # sum_b (gamma_b + 1) target rows
+        rows_us = float(np.mean(ch_samples["verify_rows_kernel"]))
+        call_ch = float(np.mean(ch_call))
+        chained_step = {"calls": "row_stats+accept_estimate+select_length+verify_sample_chained",
+                        "ms_per_step": round(ch_ms, 5),
+                        "rows_swept_per_step": round(stats_rows + t_rows, 1),
+                        "verify_rows_swept": round(t_rows, 1),
+                        "verify_call_us": round(call_ch, 2),
+                        "verify_rows_kernel_us": round(rows_us, 2),
+                        "verify_rows_kernel_GBps": round(t_rows * row_bytes / rows_us * 1e-3, 1),
+                        "kernel_us": {n: round(float(np.mean(v)), 2) for n, v in ch_samples.items()},
+                        "same_tokens_counts_flags_as_plain_off_near_flags": same}
 
     # ---- the other configurations, briefly (their full-size parity is in tests/)
     other = None
@@ -682,6 +716,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "verify_step": verify_call,
+        "chained_step": chained_step,
         "kernels": kernels,
         "sum_kernel_us": round(sum(us.values()), 2),
         "graph_replay": None if graph_ms is None else {

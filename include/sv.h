@@ -69,8 +69,12 @@ enum {
                                      the dense paths, whose probabilities are float32) of an
                                      edge of the drawn token's CDF interval                   */
   SV_FLAG_BAD_TOKEN = 16,         /* drafted token id outside [0, V)                          */
-  SV_FLAG_NOT_COMPACT = 32        /* a needed row has no compact support (count < 0): the
+  SV_FLAG_NOT_COMPACT = 32,       /* a needed row has no compact support (count < 0): the
                                      result is not valid, use the dense warped entry points   */
+  SV_FLAG_NO_CHAIN = 64           /* sv_verify_sample_chained: the workspace does not hold the
+                                     draft normalisers of these arguments (no sv_row_stats call
+                                     on it, or one with another z_d, x, shape, dtype, draft
+                                     temperature or draft cutoffs): the draft rows count as bad   */
 };
 
 /* Largest B*k accepted by sv_select_length (keys are sorted in one workgroup). */
@@ -100,7 +104,8 @@ enum {
 const char* sv_strerror(int status);
 
 /* Bytes of device scratch sv_row_stats / sv_verify_sample need for this shape
- * (0 if the shape is invalid). */
+ * (0 if the shape is invalid).  sv_row_stats leaves the normalisers of the draft
+ * rows in it (see sv_verify_sample_chained); nothing else survives a call. */
 size_t sv_workspace_bytes(int B, int k, int V, int dtype);
 
 /*
@@ -118,6 +123,9 @@ size_t sv_workspace_bytes(int B, int k, int V, int dtype);
  *   kl_or_null, entropy_d_or_null, pd_x_or_null [B,k] float   out  optional
  *   flags_or_null [B,k] uint32      out  optional, SV_FLAG_BAD_ROW / SV_FLAG_BAD_TOKEN
  * B, k, V >= 1.  B = 0 is accepted and does nothing.
+ * The call also leaves, in ws, the normalisers of the draft rows and the draft
+ * logits of the drafted tokens under a header naming its arguments: what
+ * sv_verify_sample_chained picks up.  Nothing else reads them.
  */
 int sv_row_stats(const void* z_d, const void* z_c, const int32_t* x,
                  int B, int k, int V, int dtype,
@@ -207,6 +215,34 @@ int sv_verify_sample(const void* z_t, const int32_t* t_offsets_or_null, int n_t_
                      void* ws, size_t ws_bytes, sv_stream_t stream);
 
 /*
+ * sv_verify_sample for the step as it runs in serving (Sec. 5 and 6: S and A are
+ * computed from the draft and companion logits, the lengths are chosen, the
+ * target runs, then verification): the draft rows that verification needs the
+ * normalisers of are the rows sv_row_stats has already swept in this step.
+ * sv_row_stats (and sv_row_stats_warped) leave those normalisers - row maximum
+ * and sum of exponentials in float64, and the draft logit of each drafted token -
+ * in the workspace; this call takes them from there and sweeps only the target
+ * rows, i.e. sum_b (gamma[b] + 1) rows instead of sum_b (2 gamma[b] + 1).
+ * Same arguments, outputs, flags, limits and errors as sv_verify_sample.
+ * Requirements: the same ws, z_d, x, B, k, V and dtype as the latest
+ * sv_row_stats call on that workspace, which must precede this call on the same
+ * stream (or be ordered before it by the caller), and z_d unchanged in between.
+ * The kernels check the names (addresses, shape, dtype, draft temperature and
+ * cutoff pointer) against a header the statistics pass leaves beside the
+ * normalisers; on a mismatch every sequence gets SV_FLAG_NO_CHAIN, its draft
+ * rows count as bad rows (SV_FLAG_BAD_ROW: no token accepted) and its token is
+ * drawn from the target distribution.  Whether z_d still holds what
+ * sv_row_stats read cannot be checked.
+ */
+int sv_verify_sample_chained(const void* z_t, const int32_t* t_offsets_or_null, int n_t_rows,
+                             const void* z_d, const int32_t* x, const int32_t* gamma_or_null,
+                             int B, int k, int V, int dtype,
+                             uint64_t seed, uint32_t step,
+                             int32_t* out_tokens, int32_t* n_accept, uint32_t* flags,
+                             float* ratio_or_null,
+                             void* ws, size_t ws_bytes, sv_stream_t stream);
+
+/*
  * sv_verify_sample for callers that cannot allocate device memory (code under
  * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc) and
  * so have no workspace to pass: the same kernels run on a scratch array of
@@ -215,7 +251,7 @@ int sv_verify_sample(const void* z_t, const int32_t* t_offsets_or_null, int n_t_
  * are those of sv_verify_sample without ws / ws_bytes.  The call itself
  * allocates and frees nothing.
  * Limit: sv_workspace_bytes(B, k, V, dtype) <= SV_STATIC_SCRATCH_BYTES (the
- * headline shape B=64, k=8, V=152064 needs 36 KB), else SV_ERR_TOO_LARGE.
+ * headline shape B=64, k=8, V=152064 needs 135 KB), else SV_ERR_TOO_LARGE.
  * All calls on one GPU share that GPU's array: calls that overlap in time on
  * one GPU (two streams, two host threads) race and give undefined results;
  * calls that follow each other on one stream are fine, nothing in the array
@@ -358,6 +394,21 @@ int sv_verify_sample_warped(const void* z_t, const int32_t* t_offsets_or_null, i
                             uint64_t seed, uint32_t step,
                             int32_t* out_tokens, int32_t* n_accept, uint32_t* flags,
                             float* ratio_or_null, void* ws, size_t ws_bytes, sv_stream_t stream);
+
+/*
+ * sv_verify_sample_chained on warped distributions: the draft normalisers are
+ * those sv_row_stats_warped left in the workspace, so temperature_d and
+ * cutoff_d_or_null must be the draft temperature and cutoff array that call was
+ * given (checked by value and by address; SV_FLAG_NO_CHAIN otherwise).
+ */
+int sv_verify_sample_warped_chained(const void* z_t, const int32_t* t_offsets_or_null, int n_t_rows,
+                                    const void* z_d, const int32_t* x, const int32_t* gamma_or_null,
+                                    int B, int k, int V, int dtype,
+                                    float temperature_t, const float* cutoff_t_or_null,
+                                    float temperature_d, const float* cutoff_d_or_null,
+                                    uint64_t seed, uint32_t step,
+                                    int32_t* out_tokens, int32_t* n_accept, uint32_t* flags,
+                                    float* ratio_or_null, void* ws, size_t ws_bytes, sv_stream_t stream);
 
 /*
  * sv_accept_ratio on warped distributions, on the logits themselves (for rows

@@ -21,6 +21,7 @@ SV_ERR_INVALID_ARG, SV_ERR_NULL, SV_ERR_DTYPE, SV_ERR_ALIGN = -1, -2, -3, -4
 SV_ERR_WORKSPACE, SV_ERR_LAUNCH, SV_ERR_TOO_LARGE = -5, -6, -7
 FLAG_BAD_ROW, FLAG_NEAR_TIE, FLAG_RESIDUAL_FALLBACK, FLAG_NEAR_CDF_EDGE, FLAG_BAD_TOKEN = 1, 2, 4, 8, 16
 FLAG_NOT_COMPACT = 32
+FLAG_NO_CHAIN = 64
 SV_SUPPORT_MAX_CAP = 1024
 SV_SELECT_MAX_KEYS = 8192
 SV_MAX_K = 64
@@ -31,7 +32,8 @@ EXPORTS = ("sv_strerror", "sv_workspace_bytes", "sv_row_stats", "sv_accept_estim
            "sv_row_stats_warped", "sv_verify_sample_warped",
            "sv_warp_compact", "sv_row_stats_sparse", "sv_verify_sample_sparse", "sv_uniforms",
            "sv_accept_ratio_sparse", "sv_verify_sample_static", "sv_accept_ratio_warped",
-           "sv_warp_cutoffs_multi", "sv_warp_compact_multi")
+           "sv_warp_cutoffs_multi", "sv_warp_compact_multi", "sv_verify_sample_chained",
+           "sv_verify_sample_warped_chained")
 SV_WARP_MAX_TENSORS = 8
 SV_STATIC_SCRATCH_BYTES = 1 << 20
 (SV_KERNEL_ROW_STATS, SV_KERNEL_ACCEPT_ESTIMATE, SV_KERNEL_SELECT_LENGTH, SV_KERNEL_VERIFY_ROWS,
@@ -57,6 +59,8 @@ lib.sv_select_length.argtypes = [_vp, _i, _i, _vp, _i, _i, _vp, _vp, _vp, _vp]
 lib.sv_verify_sample.restype = _i
 lib.sv_verify_sample.argtypes = [_vp, _vp, _i, _vp, _vp, _vp, _i, _i, _i, _i, ctypes.c_uint64,
                                  ctypes.c_uint32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+lib.sv_verify_sample_chained.restype = _i
+lib.sv_verify_sample_chained.argtypes = lib.sv_verify_sample.argtypes
 lib.sv_verify_sample_static.restype = _i
 lib.sv_verify_sample_static.argtypes = [_vp, _vp, _i, _vp, _vp, _vp, _i, _i, _i, _i, ctypes.c_uint64,
                                         ctypes.c_uint32, _vp, _vp, _vp, _vp, _vp]
@@ -84,6 +88,8 @@ lib.sv_row_stats_warped.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _f, _vp, _f, 
 lib.sv_verify_sample_warped.restype = _i
 lib.sv_verify_sample_warped.argtypes = [_vp, _vp, _i, _vp, _vp, _vp, _i, _i, _i, _i, _f, _vp, _f, _vp,
                                         ctypes.c_uint64, ctypes.c_uint32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+lib.sv_verify_sample_warped_chained.restype = _i
+lib.sv_verify_sample_warped_chained.argtypes = lib.sv_verify_sample_warped.argtypes
 lib.sv_warp_compact.restype = _i
 lib.sv_warp_compact.argtypes = [_vp, _i, _i, _i, _f, _i, _f, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.sv_row_stats_sparse.restype = _i
@@ -178,6 +184,16 @@ def sv_verify_sample(z_t, t_offsets, z_d, x, gamma, seed, step, out_tokens, n_ac
                                 B, k, V, _dtype_tag(z_d), seed, step, _ptr(out_tokens), _ptr(n_accept),
                                 _ptr(flags), _ptr(ratio), _ptr(ws), 0 if ws is None else ws.numel(),
                                 _stream(stream)))
+
+
+def sv_verify_sample_chained(z_t, t_offsets, z_d, x, gamma, seed, step, out_tokens, n_accept, flags,
+                             ratio=None, ws=None, stream=None):
+    B, k, V = z_d.shape
+    n_t_rows = z_t.shape[0] if t_offsets is not None else 0
+    _check(lib.sv_verify_sample_chained(_ptr(z_t), _ptr(t_offsets), n_t_rows, _ptr(z_d), _ptr(x), _ptr(gamma),
+                                        B, k, V, _dtype_tag(z_d), seed, step, _ptr(out_tokens),
+                                        _ptr(n_accept), _ptr(flags), _ptr(ratio), _ptr(ws),
+                                        0 if ws is None else ws.numel(), _stream(stream)))
 
 
 def sv_verify_sample_static(z_t, t_offsets, z_d, x, gamma, seed, step, out_tokens, n_accept, flags,
@@ -289,6 +305,18 @@ def sv_verify_sample_warped(z_t, t_offsets, z_d, x, gamma, temperature_t, cutoff
                                        temperature_d, _ptr(cutoff_d), seed, step, _ptr(out_tokens),
                                        _ptr(n_accept), _ptr(flags), _ptr(ratio), _ptr(ws),
                                        0 if ws is None else ws.numel(), _stream(stream)))
+
+
+def sv_verify_sample_warped_chained(z_t, t_offsets, z_d, x, gamma, temperature_t, cutoff_t, temperature_d,
+                                    cutoff_d, seed, step, out_tokens, n_accept, flags, ratio=None, ws=None,
+                                    stream=None):
+    B, k, V = z_d.shape
+    n_t_rows = z_t.shape[0] if t_offsets is not None else 0
+    _check(lib.sv_verify_sample_warped_chained(_ptr(z_t), _ptr(t_offsets), n_t_rows, _ptr(z_d), _ptr(x),
+                                               _ptr(gamma), B, k, V, _dtype_tag(z_d), temperature_t,
+                                               _ptr(cutoff_t), temperature_d, _ptr(cutoff_d), seed, step,
+                                               _ptr(out_tokens), _ptr(n_accept), _ptr(flags), _ptr(ratio),
+                                               _ptr(ws), 0 if ws is None else ws.numel(), _stream(stream)))
 
 
 class Supports:

@@ -53,6 +53,13 @@ struct StatsArgs {
   Scale sc_d, sc_c;       // exponent scales (temperatures) of the two tensors
   const float* cut_d;     // nullable: support cutoff of every draft row
   const float* cut_c;     // nullable: support cutoff of every companion row
+  // left in the workspace for sv_verify_sample_chained: the draft rows' normalisers
+  // and the draft logits of the drafted tokens, under a header that names this call
+  ChainHeader* chain;
+  double* chain_s;
+  float* chain_m;
+  float* chain_zx;
+  int dtype;
 };
 
 // Online sweep of two rows at once (more independent loads in flight).
@@ -152,15 +159,31 @@ __device__ __forceinline__ void stats_epilogue(const StatsArgs& a, int pair, con
   const bool bad = isnan(lse_d) || isnan(lse_c);
   uint32_t fl = bad ? SV_FLAG_BAD_ROW : 0u;
   double A = __builtin_nan(""), pdx = __builtin_nan("");
+  const int tok = a.x[pair];
+  const bool tok_ok = tok >= 0 && tok < a.V;
+  float zxd = __builtin_nanf("");
+  if (tok_ok) {
+    zxd = load_elem<DT>(rd, tok);
+    if (WARP) zxd = cut_below(zxd, cut_d);
+  }
+  a.chain_zx[pair] = zxd;                  // whatever the companion row is like
+  if (pair == 0) {
+    ChainHeader h;
+    h.z_d = reinterpret_cast<uint64_t>(a.z_d); h.x = reinterpret_cast<uint64_t>(a.x);
+    h.cut_d = WARP ? reinterpret_cast<uint64_t>(a.cut_d) : 0;
+    h.B = a.B; h.k = a.k; h.V = a.V; h.dtype = a.dtype;
+    h.scale_bits = __float_as_uint(WARP ? a.sc_d.L : kL32);
+    h.magic = kChainMagic;
+    *a.chain = h;
+  }
   if (!bad) {
-    const int tok = a.x[pair];
-    if (tok < 0 || tok >= a.V) {
+    if (!tok_ok) {
       fl |= SV_FLAG_BAD_TOKEN;
     } else {
-      float zxd = load_elem<DT>(rd, tok), zxc = load_elem<DT>(rc, tok);
+      float zxc = load_elem<DT>(rc, tok);
       double inv_td = 1.0, inv_tc = 1.0;
       if (WARP) {
-        zxd = cut_below(zxd, cut_d); zxc = cut_below(zxc, cut_c);
+        zxc = cut_below(zxc, cut_c);
         inv_td = a.sc_d.inv_t; inv_tc = a.sc_c.inv_t;
       }
       const double ld = (double)zxd * inv_td - lse_d;
@@ -194,6 +217,7 @@ struct PairConsts {
 // Folds the per-wavefront partials left by the first half of block_merge and
 // publishes the constants.  Must be called by all threads; ends with a barrier.
 __device__ __forceinline__ void publish_pair_consts(const Online (&on)[2], MergeScratch<2>& mg, PairConsts& pc,
+                                                    const StatsArgs& a, const int pair,
                                                     const Scale sc_d = unit_scale(), const Scale sc_c = unit_scale()) {
   const int wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
 #pragma unroll
@@ -210,6 +234,7 @@ __device__ __forceinline__ void publish_pair_consts(const Online (&on)[2], Merge
     const MS ms = fold_parts(mg.m[r], mg.s[r], nw, sc.L);
     pc.lse[r] = lse_from_ms(ms, sc);
     pc.kappa[r] = kappa_l32(ms, sc.L);
+    if (r == 0) { a.chain_m[pair] = ms.m; a.chain_s[pair] = ms.s; }
   }
   __syncthreads();
 }
@@ -330,7 +355,7 @@ __global__ __launch_bounds__(kStashThreads, 4) void row_stats_stash_kernel(Stats
     }
   }
   SV_PHASE_MARK(4)
-  publish_pair_consts(on, mg, consts, sc_d, sc_c);
+  publish_pair_consts(on, mg, consts, a, pair, sc_d, sc_c);
   const double lse_d = consts.lse[0], lse_c = consts.lse[1];
   const bool bad = isnan(lse_d) || isnan(lse_c);
 
@@ -415,7 +440,7 @@ __global__ __launch_bounds__(kStatsThreads) void row_stats_kernel(StatsArgs a) {
   on[0].init();
   on[1].init();
   sweep_online_pair<DT, WARP>(rd, rc, a.V, on[0], on[1], sc_d.L, sc_c.L, cut_d, cut_c);
-  publish_pair_consts(on, mg, consts, sc_d, sc_c);
+  publish_pair_consts(on, mg, consts, a, pair, sc_d, sc_c);
   const double lse_d = consts.lse[0], lse_c = consts.lse[1];
   const bool bad = isnan(lse_d) || isnan(lse_c);
 
@@ -497,7 +522,9 @@ static int row_stats_checked(const void* z_d, const void* z_c, const int32_t* x,
              SV_ERR_ALIGN);
   SV_REQUIRE(ws && is_aligned(ws, kWsAlign) && ws_bytes >= sv_workspace_bytes(B, k, V, dtype),
              SV_ERR_WORKSPACE);
-  StatsArgs a{z_d, z_c, x, B, k, V, lse_d, lse_c, S, A, kl, entropy_d, pd_x, flags, sc_d, sc_c, cut_d, cut_c};
+  const VerifyWs w = carve_verify_ws(ws, B, k, V);
+  StatsArgs a{z_d, z_c, x, B, k, V, lse_d, lse_c, S, A, kl, entropy_d, pd_x, flags, sc_d, sc_c, cut_d, cut_c,
+              w.chain, w.chain_s, w.chain_m, w.chain_zx, dtype};
   const bool extended = kl || entropy_d;   // sums that need P_d of every entry
   const bool rows_aligned = is_aligned(z_d, 16) && is_aligned(z_c, 16) && ((size_t)V * eb) % 16 == 0;
   hipStream_t st = as_stream(stream);

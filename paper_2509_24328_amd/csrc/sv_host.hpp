@@ -32,6 +32,16 @@ inline bool is_aligned(const void* p, size_t a) { return (reinterpret_cast<uintp
 
 inline int n_chunks(int V) { return (V + kChunk - 1) / kChunk; }
 
+// What sv_row_stats leaves in the workspace for sv_verify_sample_chained: which
+// call wrote the draft normalisers that follow it.
+struct alignas(16) ChainHeader {
+  uint64_t z_d, x, cut_d;    // device addresses the statistics pass was given (cut_d: 0 without warps)
+  int32_t B, k, V, dtype;
+  uint32_t scale_bits;       // bit pattern of the draft's exponent scale fl32(log2(e) / T)
+  uint32_t magic;
+};
+constexpr uint32_t kChainMagic = 0x53564348u;
+
 // Workspace carve-up for sv_verify_sample.  All offsets are multiples of 256.
 struct VerifyWs {
   double* s_t;        // [B*(k+1)*kMaxSplit] partial sums relative to c(m) of each target row
@@ -43,6 +53,11 @@ struct VerifyWs {
   double* mass_r;     // [B*C] residual mass of each chunk of the sampling row
   double* mass_t;     // [B*C] target mass of each chunk of the sampling row
   Plan* plan;          // [B] per-sequence sampling plan (verify_sample.hip)
+  // written by sv_row_stats, read by sv_verify_sample_chained
+  ChainHeader* chain;  // [1]
+  double* chain_s;     // [B*k] sum relative to c(m) of each whole draft row
+  float* chain_m;      // [B*k] maximum of each draft row
+  float* chain_zx;     // [B*k] draft logit of the drafted token (NaN: token out of range)
   size_t bytes;
 };
 
@@ -63,6 +78,10 @@ inline VerifyWs carve_verify_ws(void* base, int B, int k, int V) {
   w.mass_r = reinterpret_cast<double*>(take(bc * 8));
   w.mass_t = reinterpret_cast<double*>(take(bc * 8));
   w.plan = reinterpret_cast<Plan*>(take((size_t)B * 32));
+  w.chain = reinterpret_cast<ChainHeader*>(take(sizeof(ChainHeader)));
+  w.chain_s = reinterpret_cast<double*>(take(rd * 8));
+  w.chain_m = reinterpret_cast<float*>(take(rd * 4));
+  w.chain_zx = reinterpret_cast<float*>(take(rd * 4));
   w.bytes = off;
   return w;
 }

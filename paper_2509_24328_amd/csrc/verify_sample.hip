@@ -67,6 +67,9 @@ struct VerifyArgs {
   Scale sc_t, sc_d;           // exponent scales (temperatures) of the two tensors
   const float* cut_t;         // nullable: support cutoff of every row of z_t
   const float* cut_d;         // nullable: support cutoff of every row of z_d
+  int chained;                // 1: draft normalisers come from the statistics pass (workspace), z_d's rows
+                              // are not swept
+  int dtype;
   VerifyWs ws;
 };
 
@@ -112,6 +115,24 @@ __device__ __forceinline__ MS target_ms(const VerifyArgs& a, int b, int i) {
   const int idx = (b * (a.k + 1) + i) * a.split;
   return fold_row_parts(a.ws.m_t + idx, a.ws.s_t + idx, a.split, a.sc_t.L);
 }
+// Chained calls: does the workspace hold the draft normalisers of this very step?  (The
+// header names the tensors, shape and scale the statistics pass was given; what the
+// tensors contain is the caller's business.)
+__device__ __forceinline__ bool chain_matches(const VerifyArgs& a) {
+  // the whole header in three 128-bit loads, compared without short-circuit: field-by-field
+  // loads inside a chain of && become as many dependent trips to memory
+  static_assert(sizeof(ChainHeader) == 48, "three 16-byte words");
+  const u32x4* w = reinterpret_cast<const u32x4*>(a.ws.chain);
+  const u32x4 w0 = w[0], w1 = w[1], w2 = w[2];
+  const uint64_t zd = reinterpret_cast<uint64_t>(a.z_d), x = reinterpret_cast<uint64_t>(a.x),
+                 cd = reinterpret_cast<uint64_t>(a.cut_d);
+  uint32_t diff = (w0.x ^ (uint32_t)zd) | (w0.y ^ (uint32_t)(zd >> 32)) | (w0.z ^ (uint32_t)x) |
+                  (w0.w ^ (uint32_t)(x >> 32));
+  diff |= (w1.x ^ (uint32_t)cd) | (w1.y ^ (uint32_t)(cd >> 32)) | (w1.z ^ (uint32_t)a.B) | (w1.w ^ (uint32_t)a.k);
+  diff |= (w2.x ^ (uint32_t)a.V) | (w2.y ^ (uint32_t)a.dtype) | (w2.z ^ __float_as_uint(a.sc_d.L)) |
+          (w2.w ^ kChainMagic);
+  return diff == 0;
+}
 __device__ __forceinline__ MS draft_ms(const VerifyArgs& a, int b, int i) {
   const int idx = (b * a.k + i) * a.split;
   return fold_row_parts(a.ws.m_d + idx, a.ws.s_d + idx, a.split, a.sc_d.L);
@@ -132,7 +153,7 @@ struct RowPart {
 template <int DT, bool CUT>
 __device__ __forceinline__ RowPart sweep_row_part(const VerifyArgs& a, MergeScratch<1>& sm) {
   RowPart r;
-  const int per_seq = 2 * a.k + 1;
+  const int per_seq = a.chained ? a.k + 1 : 2 * a.k + 1;       // chained: target rows only
   const int slot = blockIdx.x / a.split;
   r.part = blockIdx.x - slot * a.split;
   r.b = slot / per_seq;
@@ -259,7 +280,7 @@ static_assert(sizeof(Plan) == 32, "workspace carve-up reserves 32 bytes per sequ
 // every workgroup of the mass kernel that works on sequence b calls it and gets
 // the same plan, the one with `publish` set also writes the accepted tokens,
 // the ratios, the accept count and the plan itself for the pick kernel.
-template <int DT>
+template <int DT, bool CHAIN>
 __device__ __forceinline__ void accept_plan(const VerifyArgs& a, const int b, const int i, const bool publish,
                                             Plan* plan_out) {
   const int k = a.k, V = a.V;
@@ -270,12 +291,25 @@ __device__ __forceinline__ void accept_plan(const VerifyArgs& a, const int b, co
   double rho = __builtin_nan("");
   double lse_t = __builtin_nan(""), lse_d = __builtin_nan("");
   bool have_target = false;
+  // chained: everything the statistics pass left goes into flight at once, before any branch
+  // (three dependent round trips to memory otherwise: header, normaliser, logit)
+  bool chain_ok = true;
+  MS chain_ms;
+  float chain_zx = 0.f;
+  if (CHAIN) {
+    const int at = b * k + min(i, k - 1);
+    chain_ms.m = a.ws.chain_m[at];
+    chain_ms.s = a.ws.chain_s[at];
+    chain_zx = a.ws.chain_zx[at];
+    chain_ok = chain_matches(a);
+    if (!chain_ok) { chain_ms.m = -INFINITY; chain_ms.s = 0.0; }   // no sum: an unusable row
+  }
   if (i <= g) {                                   // target rows 0..g (row g: bonus position)
     have_target = target_row<DT>(a, b, i) != nullptr;
     lse_t = lse_from_ms(target_ms(a, b, i), a.sc_t);
   }
   if (evaluated) {
-    lse_d = lse_from_ms(draft_ms(a, b, i), a.sc_d);
+    lse_d = lse_from_ms(CHAIN ? chain_ms : draft_ms(a, b, i), a.sc_d);
     const int tok = a.x[b * k + i];
     if (tok < 0 || tok >= V) {
       fl |= SV_FLAG_BAD_TOKEN;
@@ -283,7 +317,7 @@ __device__ __forceinline__ void accept_plan(const VerifyArgs& a, const int b, co
       fl |= SV_FLAG_BAD_ROW;
     } else {
       const double lt = (double)a.ws.zx_t[b * k + i] * a.sc_t.inv_t - lse_t;
-      const double ld = (double)a.ws.zx_d[b * k + i] * a.sc_d.inv_t - lse_d;
+      const double ld = (double)(CHAIN ? chain_zx : a.ws.zx_d[b * k + i]) * a.sc_d.inv_t - lse_d;
       rho = exp(lt - ld);                         // -inf - -inf = NaN: rejected
     }
     const U4 r = philox4x32_10((uint32_t)i, (uint32_t)b, 0u, a.step, a.seed_lo, a.seed_hi);
@@ -323,6 +357,7 @@ __device__ __forceinline__ void accept_plan(const VerifyArgs& a, const int b, co
       flags |= SV_FLAG_BAD_ROW | SV_FLAG_RESIDUAL_FALLBACK;
     }
     if (!target_ok) flags |= SV_FLAG_BAD_ROW;
+    if (CHAIN && !chain_ok) flags |= SV_FLAG_NO_CHAIN;
     Plan pl;
     pl.lse_t = lse_t_n; pl.lse_d = resid ? lse_d_n : 0.0; pl.n = n; pl.flags = flags;
     pl.resid = resid ? 1 : 0; pl.target_ok = target_ok ? 1 : 0;
@@ -379,12 +414,12 @@ struct MassShared {
 // grid (chunks, B): the accept decision of the sequence (every workgroup forms it for
 // itself, chunk 0 publishes it), then the residual and target mass of one chunk of the
 // sampling row.
-template <int DT, bool CUT>
+template <int DT, bool CUT, bool CHAIN>
 __global__ __launch_bounds__(kSampleThreads) void verify_mass_kernel(VerifyArgs a) {
   __shared__ MassShared sh;
   const int b = blockIdx.y, c = blockIdx.x, C = gridDim.x;
   const int tid = threadIdx.x;
-  if (tid < kWave) accept_plan<DT>(a, b, tid, c == 0, &sh.plan);
+  if (tid < kWave) accept_plan<DT, CHAIN>(a, b, tid, c == 0, &sh.plan);
   __syncthreads();
   const Plan pl = sh.plan;
   double mass_r, mass_t;
@@ -583,7 +618,7 @@ static int rows_split(int rows, int V) {
 
 template <int DT, bool CUT>
 static int launch_verify(const VerifyArgs& a, hipStream_t st) {
-  const int rows = a.B * (2 * a.k + 1);
+  const int rows = a.B * (a.chained ? a.k + 1 : 2 * a.k + 1);
   {
     TapScope tap(SV_KERNEL_VERIFY_ROWS, st);
     hipLaunchKernelGGL((verify_rows_kernel<DT, CUT>), dim3(rows * a.split), dim3(kRowsThreads), 0, st, a);
@@ -592,7 +627,8 @@ static int launch_verify(const VerifyArgs& a, hipStream_t st) {
   const int C = n_chunks(a.V);
   {
     TapScope tap(SV_KERNEL_VERIFY_MASS, st);
-    hipLaunchKernelGGL((verify_mass_kernel<DT, CUT>), dim3(C, a.B), dim3(kSampleThreads), 0, st, a);
+    if (a.chained) hipLaunchKernelGGL((verify_mass_kernel<DT, CUT, true>), dim3(C, a.B), dim3(kSampleThreads), 0, st, a);
+    else hipLaunchKernelGGL((verify_mass_kernel<DT, CUT, false>), dim3(C, a.B), dim3(kSampleThreads), 0, st, a);
   }
   if (launch_status() != SV_OK) return SV_ERR_LAUNCH;
   {
@@ -608,7 +644,8 @@ static int verify_sample_checked(const void* z_t, const int32_t* t_offsets, int 
                                  const int32_t* x, const int32_t* gamma, int B, int k, int V, int dtype,
                                  const Scale& sc_t, const float* cut_t, const Scale& sc_d, const float* cut_d,
                                  uint64_t seed, uint32_t step, int32_t* out_tokens, int32_t* n_accept,
-                                 uint32_t* flags, float* ratio, void* ws, size_t ws_bytes, sv_stream_t stream) {
+                                 uint32_t* flags, float* ratio, void* ws, size_t ws_bytes, sv_stream_t stream,
+                                 bool chained = false) {
   SV_REQUIRE(dtype == SV_F32 || dtype == SV_BF16, SV_ERR_DTYPE);
   SV_REQUIRE(B >= 0 && k >= 1 && V >= 1, SV_ERR_INVALID_ARG);
   SV_REQUIRE(k <= SV_MAX_K && n_chunks(V) <= kMaxChunks, SV_ERR_TOO_LARGE);
@@ -628,7 +665,9 @@ static int verify_sample_checked(const void* z_t, const int32_t* t_offsets, int 
   a.z_t = z_t; a.t_offsets = t_offsets; a.n_t_rows = n_t_rows;
   a.z_d = z_d; a.x = x; a.gamma = gamma;
   a.B = B; a.k = k; a.V = V;
-  a.split = rows_split(B * (2 * k + 1), V);
+  a.chained = chained ? 1 : 0;
+  a.dtype = dtype;
+  a.split = rows_split(B * (chained ? k + 1 : 2 * k + 1), V);
   a.t_seq_rows = k + 1;
   a.with_bonus = 1;
   a.seed_lo = (uint32_t)(seed & 0xffffffffu); a.seed_hi = (uint32_t)(seed >> 32); a.step = step;
@@ -713,6 +752,34 @@ extern "C" int sv_verify_sample_warped(const void* z_t, const int32_t* t_offsets
   return verify_sample_checked(z_t, t_offsets_or_null, n_t_rows, z_d, x, gamma_or_null, B, k, V, dtype,
                                sc_t, cutoff_t_or_null, sc_d, cutoff_d_or_null, seed, step, out_tokens, n_accept,
                                flags, ratio_or_null, ws, ws_bytes, stream);
+}
+
+extern "C" int sv_verify_sample_chained(const void* z_t, const int32_t* t_offsets_or_null, int n_t_rows,
+                                        const void* z_d, const int32_t* x, const int32_t* gamma_or_null,
+                                        int B, int k, int V, int dtype, uint64_t seed, uint32_t step,
+                                        int32_t* out_tokens, int32_t* n_accept, uint32_t* flags,
+                                        float* ratio_or_null, void* ws, size_t ws_bytes, sv_stream_t stream) {
+  using namespace sv;
+  return verify_sample_checked(z_t, t_offsets_or_null, n_t_rows, z_d, x, gamma_or_null, B, k, V, dtype,
+                               unit_scale(), nullptr, unit_scale(), nullptr, seed, step, out_tokens, n_accept,
+                               flags, ratio_or_null, ws, ws_bytes, stream, true);
+}
+
+extern "C" int sv_verify_sample_warped_chained(const void* z_t, const int32_t* t_offsets_or_null, int n_t_rows,
+                                               const void* z_d, const int32_t* x, const int32_t* gamma_or_null,
+                                               int B, int k, int V, int dtype,
+                                               float temperature_t, const float* cutoff_t_or_null,
+                                               float temperature_d, const float* cutoff_d_or_null,
+                                               uint64_t seed, uint32_t step,
+                                               int32_t* out_tokens, int32_t* n_accept, uint32_t* flags,
+                                               float* ratio_or_null, void* ws, size_t ws_bytes,
+                                               sv_stream_t stream) {
+  using namespace sv;
+  Scale sc_t, sc_d;
+  SV_REQUIRE(scale_of(temperature_t, &sc_t) && scale_of(temperature_d, &sc_d), SV_ERR_INVALID_ARG);
+  return verify_sample_checked(z_t, t_offsets_or_null, n_t_rows, z_d, x, gamma_or_null, B, k, V, dtype,
+                               sc_t, cutoff_t_or_null, sc_d, cutoff_d_or_null, seed, step, out_tokens, n_accept,
+                               flags, ratio_or_null, ws, ws_bytes, stream, true);
 }
 
 namespace sv {

@@ -84,6 +84,12 @@ int main(void) {
   EXPECT(sv_verify_sample(p, 0, 0, p, p, 0, 0, 2, 8, SV_BF16, 0, 0, 0, 0, 0, 0, 0, 0, 0), SV_OK);
   EXPECT(sv_verify_sample_warped(p, 0, 0, p, p, 0, 2, 2, 8, SV_BF16, 1e4f, 0, 1.0f, 0, 0, 0, p, p, p, 0, p, big, 0),
          SV_ERR_INVALID_ARG);
+  EXPECT(sv_verify_sample_chained(p, 0, 0, p, p, 0, 2, 2, 8, SV_BF16, 0, 0, p, p, p, 0, p, 0, 0), SV_ERR_WORKSPACE);
+  EXPECT(sv_verify_sample_chained(p, 0, 0, p, 0, 0, 2, 2, 8, SV_BF16, 0, 0, p, p, p, 0, p, big, 0), SV_ERR_NULL);
+  EXPECT(sv_verify_sample_chained(p, 0, 0, p, p, 0, 0, 2, 8, SV_BF16, 0, 0, 0, 0, 0, 0, 0, 0, 0), SV_OK);
+  EXPECT(sv_verify_sample_warped_chained(p, 0, 0, p, p, 0, 2, 2, 8, SV_BF16, 1.0f, 0, 0.0f, 0, 0, 0, p, p, p, 0, p, big,
+                                         0),
+         SV_ERR_INVALID_ARG);
   EXPECT(sv_verify_sample_static(p, 0, 0, p, p, 0, 4096, 64, 152064, SV_BF16, 0, 0, p, p, p, 0, 0), SV_ERR_TOO_LARGE);
   EXPECT(sv_verify_sample_static(p, 0, 0, p, p, 0, 0, 2, 8, SV_BF16, 0, 0, 0, 0, 0, 0, 0), SV_OK);
   EXPECT(sv_accept_ratio(p, 5, p, p, 2, 2, 8, SV_BF16, p, 0, p, big, 0), SV_ERR_INVALID_ARG);

@@ -61,6 +61,15 @@ def test_argument_errors_are_reported_before_any_launch():
     assert vs(offs=p, nt=-1) == Bd.SV_ERR_INVALID_ARG
     assert vs(wsb=0) == Bd.SV_ERR_WORKSPACE
 
+    vc = lambda **kw: L.sv_verify_sample_chained(kw.get("zt", p), None, 0, p, p, None, kw.get("B", 2),
+                                                 kw.get("k", 2), 8, kw.get("dt", 1), 0, 0, p, p, p, None,
+                                                 kw.get("ws", p), kw.get("wsb", big), None)
+    assert vc(dt=-1) == Bd.SV_ERR_DTYPE
+    assert vc(k=65) == Bd.SV_ERR_TOO_LARGE
+    assert vc(zt=None) == Bd.SV_ERR_NULL
+    assert vc(ws=None) == Bd.SV_ERR_WORKSPACE
+    assert vc(B=0) == Bd.SV_OK
+
     ae = lambda **kw: L.sv_accept_estimate(kw.get("S", p), p, kw.get("n", 4), p, kw.get("ns", 5), p, 5,
                                            p, p, None, None)
     assert ae(n=-1) == Bd.SV_ERR_INVALID_ARG
