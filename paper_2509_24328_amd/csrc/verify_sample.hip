@@ -415,19 +415,23 @@ struct MassShared {
 // itself, chunk 0 publishes it), then the residual and target mass of one chunk of the
 // sampling row.
 template <int DT, bool CUT, bool CHAIN>
-__global__ __launch_bounds__(kSampleThreads) void verify_mass_kernel(VerifyArgs a) {
+__global__ __launch_bounds__(kSampleThreads, 8) void verify_mass_kernel(VerifyArgs a) {
   __shared__ MassShared sh;
   const int b = blockIdx.y, c = blockIdx.x, C = gridDim.x;
   const int tid = threadIdx.x;
+  SV_PHASE_MARK(6)
   if (tid < kWave) accept_plan<DT, CHAIN>(a, b, tid, c == 0, &sh.plan);
   __syncthreads();
+  SV_PHASE_MARK(7)
   const Plan pl = sh.plan;
   double mass_r, mass_t;
   chunk_masses<DT, CUT>(a, b, pl, c, sh.red, &mass_r, &mass_t);
+  SV_PHASE_MARK(8)
   if (tid == 0) {
     a.ws.mass_r[b * C + c] = mass_r;
     a.ws.mass_t[b * C + c] = mass_t;
   }
+  SV_PHASE_MARK(9)
 }
 
 template <int THREADS>
