@@ -182,3 +182,14 @@ def assert_verify(got, ref, k):
 def oracle_inputs(cfg):
     return dict(z_t=svgen.to_numpy_bits(cfg["z_t"]), z_d=svgen.to_numpy_bits(cfg["z_d"]),
                 z_c=svgen.to_numpy_bits(cfg["z_c"]), x=cfg["x"].cpu().numpy())
+
+
+def uniforms_of(seqs, k, seed=0, step=0):
+    """The Philox uniforms (accept [n, k], sampling [n, k + 1]) of the sequences with batch
+    indices `seqs`, for handing a slice of a batch to the oracle."""
+    from oracle import philox
+    seq = np.asarray(seqs)[:, None]
+    ua, _ = philox.sv_uniforms(seed, step, np.broadcast_to(seq, (len(seqs), k)), np.arange(k)[None, :])
+    _, us = philox.sv_uniforms(seed, step, np.broadcast_to(seq, (len(seqs), k + 1)), np.arange(k + 1)[None, :])
+    return ua, us
+

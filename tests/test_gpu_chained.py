@@ -214,14 +214,6 @@ def test_chained_full_size_headline_configuration():
     pick = [0, 7, 31, 63]
     inp = H.oracle_inputs(cfg)
     ref = H.oracle_verify(inp["z_t"][pick], inp["z_d"][pick], inp["x"][pick], seed=0, step=0,
-                          uniforms=_uniforms_of(pick, k))
+                          uniforms=H.uniforms_of(pick, k))
     sub = {n: got[n][pick] for n in got}
     H.assert_verify(sub, ref, k)
-
-
-def _uniforms_of(seqs, k, seed=0, step=0):
-    from oracle import philox
-    seq = np.asarray(seqs)[:, None]
-    ua, _ = philox.sv_uniforms(seed, step, np.broadcast_to(seq, (len(seqs), k)), np.arange(k)[None, :])
-    _, us = philox.sv_uniforms(seed, step, np.broadcast_to(seq, (len(seqs), k + 1)), np.arange(k + 1)[None, :])
-    return ua, us
