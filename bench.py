@@ -55,6 +55,9 @@ def parse():
                     help="skip the timing of the profile-construction pass")
     ap.add_argument("--no-warped", action="store_true",
                     help="skip the timing of the step on temperature/top-k/top-p warped distributions")
+    ap.add_argument("--verify", choices=("plain", "chained"), default="plain",
+                    help="chained: the whole run uses sv_verify_sample_chained (draft normalisers from "
+                         "sv_row_stats; rows counted = rows swept); default: the four independent calls")
     ap.add_argument("--no-chained", action="store_true",
                     help="skip the timing of the step with sv_verify_sample_chained")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -357,6 +360,8 @@ def main():
     B, k, V = cfgdesc["B"], cfgdesc["k"], cfgdesc["V"]
     ragged = (args.config == 4) and not args.dense
     workload = cfgdesc["name"] if ragged or args.config != 4 else cfgdesc["name"].replace("_ragged", "_dense")
+    if args.verify == "chained":
+        workload += "_chained"
     cpu_cfg = svgen.make_config(args.config)
     edges_s, edges_a, table = svgen.profile_table(10, 10)
     lat = svgen.latency_table(B * k)
@@ -371,6 +376,10 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     run = Runner(P, svgen, torch, args.config, args.copies, cpu_cfg=cpu_cfg, ragged=ragged)
+    chained_run = args.verify == "chained"
+    run.chained = chained_run
+    if chained_run:        # rows of the verification call = the target rows it sweeps, sum_b (gamma_b + 1)
+        run.verify_rows = [(v + B) // 2 for v in run.verify_rows]
     copies, stream, ws = run.copies, run.stream, run.ws
     lse_d, lse_c, S, A, p_hat = run.lse_d, run.lse_c, run.S, run.A, run.p_hat
     gamma, offs, total, tokens, n_acc, flags = run.gamma, run.offs, run.total, run.tokens, run.n_acc, run.flags
@@ -450,7 +459,7 @@ def main():
     # sv_row_stats left in the workspace, so verification sweeps the target rows only.  Reported
     # beside the headline, which keeps the four independent calls and their byte count.
     chained_step = None
-    if not args.no_chained:
+    if not args.no_chained and not chained_run:
         run.chained = True
         ch_ms = run.time_steps(args.warmup, args.steps)
         ch_samples, ch_call = run.time_kernels(hip, Bd, args.steps)
@@ -700,7 +709,7 @@ def main():
         torch.cuda.synchronize()
 
     rows_per_step = run.rows_per_step()
-    calls = "row_stats+accept_estimate+select_length+verify_sample(" + \
+    calls = "row_stats+accept_estimate+select_length+" + ("verify_sample_chained(" if chained_run else "verify_sample(") + \
         ("gamma from select_length, packed target rows)" if ragged else "gamma=k)")
     out = {
         "metric": METRIC,
