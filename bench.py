@@ -202,7 +202,7 @@ class Runner:
         self.eb = 2 if self.desc["dtype"] == "bf16" else 4
         self.tag = P.SV_BF16 if self.eb == 2 else P.SV_F32
         self.ragged = ragged
-        self.chained = False     # True: sv_verify_sample_chained (draft normalisers from sv_row_stats)
+        self.chained = False     # True: the three-call form (sv_estimate_select, sv_verify_sample_chained)
         B, k, V = self.B, self.k, self.V
         self.copies = []
         if cpu_cfg is not None:      # copy 0 = the canonical CPU-seeded batch (the one the oracle gets)
@@ -243,6 +243,10 @@ class Runner:
     def select(self, c, s=None):
         P, s = self.P, (s or self.stream)
         P.sv_row_stats(c["z_d"], c["z_c"], c["x"], self.lse_d, self.lse_c, self.S, self.A, None, None, self.ws, s)
+        if self.chained:     # the serving form of the step: estimate and selection in one launch as well
+            P.sv_estimate_select(self.S, self.A, self.d_es, self.d_ea, self.d_tab, self.d_lat, P.SV_BATCH_GREEDY,
+                                 self.p_hat, self.gamma, self.offs, self.total, None, s)
+            return
         P.sv_accept_estimate(self.S, self.A, self.d_es, self.d_ea, self.d_tab, self.p_hat, None, s)
         P.sv_select_length(self.p_hat, self.d_lat, P.SV_BATCH_GREEDY, self.gamma, self.offs, self.total, s)
 
@@ -455,9 +459,10 @@ def main():
                   "offsets_equal": bool(np.array_equal(got["t_offsets"], ref["t_offsets"]))}
         assert bad == 0 and s_err < 1e-5 and a_err < 1e-5 and parity["gamma_equal"], parity
 
-    # ---- the same step with sv_verify_sample_chained: the draft rows' normalisers come from what
-    # sv_row_stats left in the workspace, so verification sweeps the target rows only.  Reported
-    # beside the headline, which keeps the four independent calls and their byte count.
+    # ---- the same step in its three-call form: sv_estimate_select (lookup and selection in one
+    # launch) and sv_verify_sample_chained (the draft rows' normalisers come from what sv_row_stats
+    # left in the workspace, so verification sweeps the target rows only).  Reported beside the
+    # headline, which keeps the four independent calls and their byte count.
     chained_step = None
     if not args.no_chained and not chained_run:
         run.chained = True
@@ -475,7 +480,7 @@ def main():
         t_rows = (verify_rows + B) / 2                      # sum_b (gamma_b + 1) target rows
         rows_us = float(np.mean(ch_samples["verify_rows_kernel"]))
         call_ch = float(np.mean(ch_call))
-        chained_step = {"calls": "row_stats+accept_estimate+select_length+verify_sample_chained",
+        chained_step = {"calls": "row_stats+estimate_select+verify_sample_chained",
                         "ms_per_step": round(ch_ms, 5),
                         "rows_swept_per_step": round(stats_rows + t_rows, 1),
                         "verify_rows_swept": round(t_rows, 1),
@@ -496,9 +501,13 @@ def main():
             ms = r2.time_steps(5, 40)
             gms = None if args.no_graph else r2.time_graphs(5, 40)
             smp, cus = r2.time_kernels(hip, Bd, 40)
+            r2.chained = True
+            ms3 = r2.time_steps(5, 40)
+            r2.chained = False
             vr = sum(r2.verify_rows) / len(r2.verify_rows)
             other.append({"workload": r2.desc["name"], "ms_per_step": round(ms, 5),
                           "graph_replay_ms_per_step": None if gms is None else round(gms, 5),
+                          "three_call_ms_per_step": round(ms3, 5),
                           "rows_per_step": round(r2.rows_per_step(), 1),
                           "rows_per_s": round(r2.rows_per_step() / (ms * 1e-3), 1),
                           "verify_rows": round(vr, 1), "verify_call_us": round(float(np.mean(cus)), 2),
@@ -709,7 +718,8 @@ def main():
         torch.cuda.synchronize()
 
     rows_per_step = run.rows_per_step()
-    calls = "row_stats+accept_estimate+select_length+" + ("verify_sample_chained(" if chained_run else "verify_sample(") + \
+    calls = ("row_stats+estimate_select+verify_sample_chained(" if chained_run else
+             "row_stats+accept_estimate+select_length+verify_sample(") + \
         ("gamma from select_length, packed target rows)" if ragged else "gamma=k)")
     out = {
         "metric": METRIC,

@@ -176,6 +176,23 @@ int sv_select_length(const float* p_hat, int B, int k,
                      sv_stream_t stream);
 
 /*
+ * sv_accept_estimate and sv_select_length in one launch (same sources): the
+ * estimates of the B*k positions are looked up from (S, A) by the rule of
+ * sv_accept_estimate, written to p_hat, and the lengths are selected from them
+ * by the rule of sv_select_length.  Results are those of the two calls; the
+ * launch in between is saved, which is what a small batch's step is made of.
+ *   S, A [B,k] float in;  edges_s [n_s+1], edges_a [n_a+1], table [n_s,n_a] float in
+ *   p_hat [B,k] float out;  edge_flag_or_null [B,k] uint8 out
+ *   latency, mode, gamma, t_offsets, total_M, limits and errors as for sv_select_length.
+ */
+int sv_estimate_select(const float* S, const float* A, int B, int k,
+                       const float* edges_s, int n_s, const float* edges_a, int n_a,
+                       const float* table, const float* latency, int n_latency, int mode,
+                       float* p_hat, uint8_t* edge_flag_or_null,
+                       int32_t* gamma, int32_t* t_offsets, int32_t* total_M,
+                       sv_stream_t stream);
+
+/*
  * Speculative-sampling verification of the first gamma[b] drafted tokens of
  * each sequence (Sec. 4.2, last paragraph; the rule itself is Leviathan et al.'s):
  * for i < gamma[b] accept x[b,i] iff u_i < p_t(x)/p_d(x); n = leading accepts;

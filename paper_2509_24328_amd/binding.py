@@ -33,7 +33,7 @@ EXPORTS = ("sv_strerror", "sv_workspace_bytes", "sv_row_stats", "sv_accept_estim
            "sv_warp_compact", "sv_row_stats_sparse", "sv_verify_sample_sparse", "sv_uniforms",
            "sv_accept_ratio_sparse", "sv_verify_sample_static", "sv_accept_ratio_warped",
            "sv_warp_cutoffs_multi", "sv_warp_compact_multi", "sv_verify_sample_chained",
-           "sv_verify_sample_warped_chained")
+           "sv_verify_sample_warped_chained", "sv_estimate_select")
 SV_WARP_MAX_TENSORS = 8
 SV_STATIC_SCRATCH_BYTES = 1 << 20
 (SV_KERNEL_ROW_STATS, SV_KERNEL_ACCEPT_ESTIMATE, SV_KERNEL_SELECT_LENGTH, SV_KERNEL_VERIFY_ROWS,
@@ -56,6 +56,8 @@ lib.sv_accept_estimate.restype = _i
 lib.sv_accept_estimate.argtypes = [_vp, _vp, _i, _vp, _i, _vp, _i, _vp, _vp, _vp, _vp]
 lib.sv_select_length.restype = _i
 lib.sv_select_length.argtypes = [_vp, _i, _i, _vp, _i, _i, _vp, _vp, _vp, _vp]
+lib.sv_estimate_select.restype = _i
+lib.sv_estimate_select.argtypes = [_vp, _vp, _i, _i, _vp, _i, _vp, _i, _vp, _vp, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.sv_verify_sample.restype = _i
 lib.sv_verify_sample.argtypes = [_vp, _vp, _i, _vp, _vp, _vp, _i, _i, _i, _i, ctypes.c_uint64,
                                  ctypes.c_uint32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
@@ -174,6 +176,15 @@ def sv_select_length(p_hat, latency, mode, gamma, t_offsets, total_M, stream=Non
     B, k = p_hat.shape
     _check(lib.sv_select_length(_ptr(p_hat), B, k, _ptr(latency), latency.numel(), mode,
                                 _ptr(gamma), _ptr(t_offsets), _ptr(total_M), _stream(stream)))
+
+
+def sv_estimate_select(S, A, edges_s, edges_a, table, latency, mode, p_hat, gamma, t_offsets, total_M,
+                       edge_flag=None, stream=None):
+    B, k = S.shape
+    _check(lib.sv_estimate_select(_ptr(S), _ptr(A), B, k, _ptr(edges_s), edges_s.numel() - 1, _ptr(edges_a),
+                                  edges_a.numel() - 1, _ptr(table), _ptr(latency), latency.numel(), mode,
+                                  _ptr(p_hat), _ptr(edge_flag), _ptr(gamma), _ptr(t_offsets), _ptr(total_M),
+                                  _stream(stream)))
 
 
 def sv_verify_sample(z_t, t_offsets, z_d, x, gamma, seed, step, out_tokens, n_accept, flags,

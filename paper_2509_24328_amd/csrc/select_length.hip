@@ -16,6 +16,7 @@
 // re-sums in order otherwise; goodput and first-peak search in parallel; counts
 // and offsets.  Launch-latency bound at the paper's batch sizes (12 us at 512
 // keys; 55 us at 4096, 120 us at 8192).
+#include "sv_bins.hpp"
 #include "sv_device.hpp"
 #include "sv_host.hpp"
 
@@ -71,9 +72,32 @@ __device__ __forceinline__ void offsets_scan(const int* cnt, int B, int32_t* gam
   if (tid == 0) t_offsets[B] = total;
 }
 
+// sv_estimate_select: the estimates are looked up here (the rule of sv_accept_estimate,
+// sv_bins.hpp) instead of being read, which saves the launch in between.
+struct EstimateArgs {
+  const float* S;
+  const float* A;
+  const float* edges_s;
+  const float* edges_a;
+  const float* table;
+  int n_s, n_a;
+  float* p_hat;          // nullable: the estimates are also written out
+  uint8_t* edge_flag;    // nullable
+};
+
+// The estimate of key j.  es / ea: the edge arrays (in LDS when they fit).
+__device__ __forceinline__ float estimate_of(const EstimateArgs& e, const float* es, const float* ea, int j) {
+  const float s = e.S[j], a = e.A[j];
+  const float p = e.table[bin_of(s, es, e.n_s) * e.n_a + bin_of(a, ea, e.n_a)];
+  if (e.p_hat) e.p_hat[j] = p;
+  if (e.edge_flag) e.edge_flag[j] = (near_edge(s, es, e.n_s) || near_edge(a, ea, e.n_a)) ? 1 : 0;
+  return p;
+}
+
+template <bool FUSED>
 __global__ __launch_bounds__(kSelThreads) void select_batch_kernel(
     const float* p_hat, int B, int k, const float* latency, int32_t* gamma, int32_t* t_offsets,
-    int32_t* total_M) {
+    int32_t* total_M, EstimateArgs est) {
   __shared__ double key_c[kSelMax];     // sort keys, later the running sums E_M
   __shared__ int key_i[kSelMax];        // first the raw estimates (as float bits), then key indices
   __shared__ int part[kSelThreads];
@@ -96,7 +120,15 @@ __global__ __launch_bounds__(kSelThreads) void select_batch_kernel(
   }
   // estimates into LDS with one round of coalesced loads
   float* p_lds = reinterpret_cast<float*>(key_i);
-  for (int j = tid; j < n; j += nt) p_lds[j] = p_hat[j];
+  if (FUSED) {
+    __shared__ float e_lds[kEdgeLds];
+    const bool in_lds = stage_edges(e_lds, est.edges_s, est.n_s, est.edges_a, est.n_a);
+    const float* es = in_lds ? e_lds : est.edges_s;
+    const float* ea = in_lds ? e_lds + est.n_s + 1 : est.edges_a;
+    for (int j = tid; j < n; j += nt) p_lds[j] = estimate_of(est, es, ea, j);
+  } else {
+    for (int j = tid; j < n; j += nt) p_lds[j] = p_hat[j];
+  }
   __syncthreads();
   for (int b = tid; b < B; b += nt) {
     double acc = 1.0;
@@ -290,13 +322,23 @@ __global__ __launch_bounds__(kSelThreads) void select_batch_kernel(
   SV_PHASE_MARK(6)
 }
 
+template <bool FUSED>
 __global__ __launch_bounds__(kSelThreads) void select_per_sequence_kernel(
     const float* p_hat, int B, int k, const float* latency, int32_t* gamma, int32_t* t_offsets,
-    int32_t* total_M) {
+    int32_t* total_M, EstimateArgs est) {
   __shared__ int part[kSelThreads];
   __shared__ int total;
   const int tid = threadIdx.x, nt = blockDim.x;
   if (tid == 0) total = 0;
+  if (FUSED) {
+    // every estimate is looked up (and written out) first: the search below stops early
+    __shared__ float e_lds[kEdgeLds];
+    const bool in_lds = stage_edges(e_lds, est.edges_s, est.n_s, est.edges_a, est.n_a);
+    const float* es = in_lds ? e_lds : est.edges_s;
+    const float* ea = in_lds ? e_lds + est.n_s + 1 : est.edges_a;
+    for (int j = tid; j < B * k; j += nt) est.p_hat[j] = estimate_of(est, es, ea, j);
+    __threadfence_block();
+  }
   __syncthreads();
   int mine = 0;
   for (int b = tid; b < B; b += nt) {
@@ -320,12 +362,14 @@ __global__ __launch_bounds__(kSelThreads) void select_per_sequence_kernel(
 
 }  // namespace sv
 
-extern "C" int sv_select_length(const float* p_hat, int B, int k, const float* latency, int n_latency,
-                                int mode, int32_t* gamma, int32_t* t_offsets, int32_t* total_M,
-                                sv_stream_t stream) {
-  using namespace sv;
+namespace sv {
+// Argument checks and launch shared by sv_select_length and sv_estimate_select.
+static int select_checked(const float* p_hat, int B, int k, const float* latency, int n_latency, int mode,
+                          int32_t* gamma, int32_t* t_offsets, int32_t* total_M, const EstimateArgs* est,
+                          sv_stream_t stream) {
   SV_REQUIRE(mode == SV_BATCH_GREEDY || mode == SV_PER_SEQUENCE, SV_ERR_INVALID_ARG);
   SV_REQUIRE(B >= 0 && k >= 1, SV_ERR_INVALID_ARG);
+  SV_REQUIRE(!est || (est->n_s >= 1 && est->n_a >= 1), SV_ERR_INVALID_ARG);
   SV_REQUIRE((long long)B * k <= SV_SELECT_MAX_KEYS, SV_ERR_TOO_LARGE);
   if (B == 0) return SV_OK;
   SV_REQUIRE(n_latency >= (mode == SV_BATCH_GREEDY ? B * k + 1 : k + 1), SV_ERR_INVALID_ARG);
@@ -333,16 +377,48 @@ extern "C" int sv_select_length(const float* p_hat, int B, int k, const float* l
   SV_REQUIRE(is_aligned(p_hat, 4) && is_aligned(latency, 4) && is_aligned(gamma, 4) &&
                  is_aligned(t_offsets, 4) && is_aligned(total_M, 4),
              SV_ERR_ALIGN);
+  if (est) {
+    SV_REQUIRE(est->S && est->A && est->edges_s && est->edges_a && est->table, SV_ERR_NULL);
+    SV_REQUIRE(is_aligned(est->S, 4) && is_aligned(est->A, 4) && is_aligned(est->edges_s, 4) &&
+                   is_aligned(est->edges_a, 4) && is_aligned(est->table, 4),
+               SV_ERR_ALIGN);
+  }
   hipStream_t st = as_stream(stream);
   TapScope tap(SV_KERNEL_SELECT_LENGTH, st);
   // one lane per (padded) key up to the workgroup limit
   int threads = 64;
   while (threads < kSelThreads && threads < B * k) threads <<= 1;
-  if (mode == SV_BATCH_GREEDY)
-    hipLaunchKernelGGL(select_batch_kernel, dim3(1), dim3(threads), 0, st, p_hat, B, k, latency,
-                       gamma, t_offsets, total_M);
-  else
-    hipLaunchKernelGGL(select_per_sequence_kernel, dim3(1), dim3(kSelThreads), 0, st, p_hat, B, k,
-                       latency, gamma, t_offsets, total_M);
+  const EstimateArgs none = {};
+  if (mode == SV_BATCH_GREEDY) {
+    if (est)
+      hipLaunchKernelGGL(select_batch_kernel<true>, dim3(1), dim3(threads), 0, st, p_hat, B, k, latency, gamma,
+                         t_offsets, total_M, *est);
+    else
+      hipLaunchKernelGGL(select_batch_kernel<false>, dim3(1), dim3(threads), 0, st, p_hat, B, k, latency, gamma,
+                         t_offsets, total_M, none);
+  } else {
+    if (est)
+      hipLaunchKernelGGL(select_per_sequence_kernel<true>, dim3(1), dim3(kSelThreads), 0, st, p_hat, B, k, latency,
+                         gamma, t_offsets, total_M, *est);
+    else
+      hipLaunchKernelGGL(select_per_sequence_kernel<false>, dim3(1), dim3(kSelThreads), 0, st, p_hat, B, k, latency,
+                         gamma, t_offsets, total_M, none);
+  }
   return launch_status();
+}
+}  // namespace sv
+
+extern "C" int sv_select_length(const float* p_hat, int B, int k, const float* latency, int n_latency,
+                                int mode, int32_t* gamma, int32_t* t_offsets, int32_t* total_M,
+                                sv_stream_t stream) {
+  return sv::select_checked(p_hat, B, k, latency, n_latency, mode, gamma, t_offsets, total_M, nullptr, stream);
+}
+
+extern "C" int sv_estimate_select(const float* S, const float* A, int B, int k,
+                                  const float* edges_s, int n_s, const float* edges_a, int n_a,
+                                  const float* table, const float* latency, int n_latency, int mode,
+                                  float* p_hat, uint8_t* edge_flag_or_null,
+                                  int32_t* gamma, int32_t* t_offsets, int32_t* total_M, sv_stream_t stream) {
+  const sv::EstimateArgs est{S, A, edges_s, edges_a, table, n_s, n_a, p_hat, edge_flag_or_null};
+  return sv::select_checked(p_hat, B, k, latency, n_latency, mode, gamma, t_offsets, total_M, &est, stream);
 }

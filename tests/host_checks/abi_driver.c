@@ -74,6 +74,13 @@ int main(void) {
   EXPECT(sv_select_length(0, 4, 4, p, 17, SV_BATCH_GREEDY, p, p, p, 0), SV_ERR_NULL);
   EXPECT(sv_select_length(0, 0, 4, 0, 0, SV_PER_SEQUENCE, 0, 0, 0, 0), SV_OK);
 
+  EXPECT(sv_estimate_select(p, p, 4, 4, p, 5, p, 5, p, p, 17, 2, p, 0, p, p, p, 0), SV_ERR_INVALID_ARG);
+  EXPECT(sv_estimate_select(p, p, 4, 4, p, 0, p, 5, p, p, 17, 0, p, 0, p, p, p, 0), SV_ERR_INVALID_ARG);
+  EXPECT(sv_estimate_select(p, p, 4, 4, p, 5, p, 5, p, p, 16, 0, p, 0, p, p, p, 0), SV_ERR_INVALID_ARG);
+  EXPECT(sv_estimate_select(0, p, 4, 4, p, 5, p, 5, p, p, 17, 0, p, 0, p, p, p, 0), SV_ERR_NULL);
+  EXPECT(sv_estimate_select(p, p, 4, 4, p, 5, p, 5, p, p, 17, 0, 0, 0, p, p, p, 0), SV_ERR_NULL);
+  EXPECT(sv_estimate_select(p, p, SV_SELECT_MAX_KEYS + 1, 1, p, 5, p, 5, p, p, 10000, 0, p, 0, p, p, p, 0), SV_ERR_TOO_LARGE);
+  EXPECT(sv_estimate_select(0, 0, 0, 4, 0, 5, 0, 5, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0), SV_OK);
   /* sv_verify_sample and its variants */
   EXPECT(sv_verify_sample(p, 0, 0, p, p, 0, 2, 2, 8, -1, 0, 0, p, p, p, 0, p, big, 0), SV_ERR_DTYPE);
   EXPECT(sv_verify_sample(p, 0, 0, p, p, 0, 2, SV_MAX_K + 1, 8, SV_BF16, 0, 0, p, p, p, 0, p, big, 0), SV_ERR_TOO_LARGE);
