@@ -300,8 +300,8 @@ __device__ __forceinline__ MS fold_row_parts(const float* m, const double* s, in
 // also takes the scalar tail); rows that do not start on 16 bytes are split by
 // elements and read with scalar loads.
 // ---------------------------------------------------------------------------
-// NT: the row is not read again soon (non-temporal loads).
-template <int DT, bool CUT = false, bool NT = true>
+// NT: the row is not read again soon (non-temporal loads).  U: vectors in flight per lane.
+template <int DT, bool CUT = false, bool NT = true, int U = 4>
 __device__ __forceinline__ void sweep_online(const void* row, int V, int part, int split, Online& acc,
                                              const float L = kL32, const float cut = -INFINITY) {
   constexpr int EPV = Elem<DT>::per_vec;
@@ -326,14 +326,23 @@ __device__ __forceinline__ void sweep_online(const void* row, int V, int part, i
     const int end = min(nvec, (part + 1) * per);
     int i = part * per + tid;
     auto load = [&](int j) { return NT ? __builtin_nontemporal_load(p + j) : p[j]; };
-    for (; i + 3 * nt < end; i += 4 * nt) {
-      const u32x4 q0 = load(i);
-      const u32x4 q1 = load(i + nt);
-      const u32x4 q2 = load(i + 2 * nt);
-      const u32x4 q3 = load(i + 3 * nt);
-      add_vec(q0); add_vec(q1); add_vec(q2); add_vec(q3);
+    for (; i + (U - 1) * nt < end; i += U * nt) {
+      u32x4 q[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) q[u] = load(i + u * nt);
+#pragma unroll
+      for (int u = 0; u < U; ++u) add_vec(q[u]);
     }
-    for (; i < end; i += nt) add_vec(load(i));
+    if (i < end) {
+      // the last, partial round: its loads go out together as well (one trip to memory, not one per vector)
+      u32x4 q[U - 1];
+#pragma unroll
+      for (int u = 0; u < U - 1; ++u)
+        if (i + u * nt < end) q[u] = load(i + u * nt);
+#pragma unroll
+      for (int u = 0; u < U - 1; ++u)
+        if (i + u * nt < end) add_vec(q[u]);
+    }
     if (part == split - 1)
       for (int v = nvec * EPV + tid; v < V; v += nt) add_one(v);
   } else {

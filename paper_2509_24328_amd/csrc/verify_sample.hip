@@ -171,7 +171,9 @@ __device__ __forceinline__ RowPart sweep_row_part(const VerifyArgs& a, MergeScra
   if (CUT) cut = r.is_target ? target_cut(a, r.b, r.i) : draft_cut(a, r.b, r.i);
   Online acc[1];
   acc[0].init();
-  if (row) sweep_online<DT, CUT>(row, a.V, r.part, a.split, acc[0], L, cut);
+  // six vectors in flight per lane: a part is 8-10 vectors per lane at the benchmark shapes, i.e. two
+  // round trips to memory (6 + the rest, whose loads also go out together) instead of three or four
+  if (row) sweep_online<DT, CUT, true, 6>(row, a.V, r.part, a.split, acc[0], L, cut);
   MS merged[1];
   block_merge<1>(acc, sm, merged, L);
   r.ms = merged[0];                                      // s = 0 for a missing row => bad row
