@@ -306,20 +306,29 @@ __device__ __forceinline__ void accept_plan(const VerifyArgs& a, const int b, co
     chain_ok = chain_matches(a);
     if (!chain_ok) { chain_ms.m = -INFINITY; chain_ms.s = 0.0; }   // no sum: an unusable row
   }
+  // Everything the decision may need is asked for here, for every lane and before the length is
+  // known (rows past the length hold whatever an earlier call left: read, never used), so that
+  // the loads travel together instead of in three dependent rounds: length, partials, logits.
+  const int it = min(i, k), id = min(i, k - 1);
+  const MS ms_t = target_ms(a, b, it);
+  const MS ms_d = CHAIN ? chain_ms : draft_ms(a, b, id);
+  const float zx_t = a.ws.zx_t[b * k + id];
+  const float zx_d = CHAIN ? chain_zx : a.ws.zx_d[b * k + id];
+  const int tok = a.x[b * k + id];
+  const bool target_there = target_index(a, b, it) >= 0;
   if (i <= g) {                                   // target rows 0..g (row g: bonus position)
-    have_target = target_row<DT>(a, b, i) != nullptr;
-    lse_t = lse_from_ms(target_ms(a, b, i), a.sc_t);
+    have_target = target_there;
+    lse_t = lse_from_ms(ms_t, a.sc_t);
   }
   if (evaluated) {
-    lse_d = lse_from_ms(CHAIN ? chain_ms : draft_ms(a, b, i), a.sc_d);
-    const int tok = a.x[b * k + i];
+    lse_d = lse_from_ms(ms_d, a.sc_d);
     if (tok < 0 || tok >= V) {
       fl |= SV_FLAG_BAD_TOKEN;
     } else if (isnan(lse_t) || isnan(lse_d)) {
       fl |= SV_FLAG_BAD_ROW;
     } else {
-      const double lt = (double)a.ws.zx_t[b * k + i] * a.sc_t.inv_t - lse_t;
-      const double ld = (double)(CHAIN ? chain_zx : a.ws.zx_d[b * k + i]) * a.sc_d.inv_t - lse_d;
+      const double lt = (double)zx_t * a.sc_t.inv_t - lse_t;
+      const double ld = (double)zx_d * a.sc_d.inv_t - lse_d;
       rho = exp(lt - ld);                         // -inf - -inf = NaN: rejected
     }
     const U4 r = philox4x32_10((uint32_t)i, (uint32_t)b, 0u, a.step, a.seed_lo, a.seed_hi);
