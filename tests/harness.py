@@ -90,6 +90,26 @@ def gpu_verify(z_t, z_d, x, gamma=None, t_offsets=None, seed=0, step=0):
                 flags=flags.cpu().numpy().astype(np.uint32), ratio=ratio.cpu().numpy())
 
 
+def gpu_verify_chained(z_t, z_d, z_c, x, gamma=None, t_offsets=None, seed=0, step=0):
+    """sv_row_stats, then sv_verify_sample_chained on the same workspace."""
+    P = sv()
+    B, k, V = z_d.shape
+    mk = lambda: torch.full((B, k), -7.0, dtype=torch.float32, device="cuda")
+    ws = P.alloc_workspace(B, k, V, P.binding._dtype_tag(z_d))
+    P.sv_row_stats(z_d, z_c, x, mk(), mk(), mk(), mk(), None, None, ws)
+    tokens = torch.full((B, k + 1), -5, dtype=torch.int32, device="cuda")
+    n_acc = torch.full((B,), -5, dtype=torch.int32, device="cuda")
+    flags = torch.full((B,), 0x7FFF, dtype=torch.int32, device="cuda")
+    ratio = torch.full((B, k), -5.0, dtype=torch.float32, device="cuda")
+    g = None if gamma is None else dev(gamma, torch.int32)
+    o = None if t_offsets is None else dev(t_offsets, torch.int32)
+    P.sv_verify_sample_chained(z_t, o, z_d, x, g, seed, step, tokens, n_acc, flags, ratio, ws)
+    torch.cuda.synchronize()
+    fl = flags.cpu().numpy().astype(np.uint32)
+    assert not (fl & P.binding.FLAG_NO_CHAIN).any(), "the chained call did not find the statistics pass"
+    return dict(tokens=tokens.cpu().numpy(), n_accept=n_acc.cpu().numpy(), flags=fl, ratio=ratio.cpu().numpy())
+
+
 # ------------------------------------------------------------------ compare
 def close(got, ref, rel=REL, abs_floor=0.0):
     """|got - ref| <= rel |ref| + abs_floor, NaN = NaN, inf = inf.  A float32

@@ -37,6 +37,8 @@ def test_random_problems(block):
         vgot = H.gpu_verify(d["z_t"], d["z_d"], d["x"], gamma=gamma, seed=pseed, step=step)
         t, e = H.assert_verify(vgot, vref, k)
         n_tie, n_edge, n_seq = n_tie + t, n_edge + e, n_seq + B
+        H.assert_verify(H.gpu_verify_chained(d["z_t"], d["z_d"], d["z_c"], d["x"], gamma=gamma, seed=pseed, step=step),
+                        vref, k)
         p = rng.random((B, k)).astype(np.float32)
         lat = svgen.latency_table(B * k, t0=float(rng.uniform(0.1, 30)), d=float(rng.uniform(0.01, 1)),
                                   m0=int(rng.integers(1, B * k + 1)))
@@ -112,16 +114,20 @@ def _warped_case(rng, zs, dtype, par, with_kl=True):
     sub = lambda dct, m: {n: ([v[i] for i in np.flatnonzero(m)] if isinstance(v, list) else np.asarray(v)[m])
                           for n, v in dct.items()}
     n_seq = n_tie = 0
-    for mode in ("dense", "sparse"):
+    for mode in ("dense", "chained", "sparse"):
         tokens, n_acc, flags, ratio = i32(B, k + 1), i32(B), i32(B), f32(B, k)
         if mode == "dense":
             P.sv_verify_sample_warped(d["t"], None, d["d"], xg, gg, par["t"][0], gcut["t"], par["d"][0],
                                       gcut["d"], pseed, step, tokens, n_acc, flags, ratio, ws)
+        elif mode == "chained":      # draft normalisers from the sv_row_stats_warped call above (same ws)
+            P.sv_verify_sample_warped_chained(d["t"], None, d["d"], xg, gg, par["t"][0], gcut["t"], par["d"][0],
+                                              gcut["d"], pseed, step, tokens, n_acc, flags, ratio, ws)
         else:
             P.sv_verify_sample_sparse(sup["t"], None, sup["d"], xg, gg, V, pseed, step, tokens, n_acc, flags, ratio)
         torch.cuda.synchronize()
         vgot = dict(tokens=tokens.cpu().numpy(), n_accept=n_acc.cpu().numpy(),
                     flags=flags.cpu().numpy().astype(np.uint32), ratio=ratio.cpu().numpy())
+        assert mode != "chained" or not (vgot["flags"] & 64).any()     # the statistics pass was found
         m = ~seq_tie & ((vgot["flags"] & 32) == 0)
         t, _ = H.assert_verify(sub(vgot, m), sub(vref, m), k)
         n_tie += t
@@ -211,6 +217,8 @@ def test_random_adversarial_values(block):
         vgot = H.gpu_verify(H.dev(z_t, dtype), H.dev(z_d, dtype), H.dev(x), seed=case, step=block)
         t, _ = H.assert_verify(vgot, vref, k)
         n_seq, n_tie = n_seq + B, n_tie + t
+        H.assert_verify(H.gpu_verify_chained(H.dev(z_t, dtype), H.dev(z_d, dtype), H.dev(z_c, dtype), H.dev(x),
+                                             seed=case, step=block), vref, k)
     print(f"\n  block {block}: {n_seq} sequences, near-tie {n_tie}", flush=True)
 
 
