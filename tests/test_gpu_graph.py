@@ -1,5 +1,5 @@
-"""The four calls of a decode step captured into a HIP graph (as a serving loop
-would run them) and replayed: every replay must reproduce the eager results.
+"""The calls of a decode step (its four-call and its three-call form) captured into a HIP
+graph (as a serving loop would run them) and replayed: every replay must reproduce the eager results.
 The library enqueues kernels only - no allocation, no memset, no host sync -
 so the whole step is capturable once each kernel has been launched eagerly."""
 import numpy as np
@@ -13,7 +13,8 @@ import harness as H
 pytestmark = pytest.mark.gpu
 
 
-def test_step_replays_from_a_graph():
+@pytest.mark.parametrize("form", ["four calls", "three calls"])
+def test_step_replays_from_a_graph(form):
     P = H.sv()
     B, k, V = 8, 8, 32000
     cfgs = [svgen.make_config(1, B=B, k=k, V=V, dtype="bf16", seed=s) for s in (11, 12, 13)]
@@ -34,6 +35,10 @@ def test_step_replays_from_a_graph():
 
     def step():
         P.sv_row_stats(z_d, z_c, x, lse_d, lse_c, S, A, None, None, ws)
+        if form == "three calls":      # estimate + selection in one launch, draft normalisers handed over in ws
+            P.sv_estimate_select(S, A, d_es, d_ea, d_tab, d_lat, P.SV_BATCH_GREEDY, p_hat, gamma, offs, total)
+            P.sv_verify_sample_chained(z_t, None, z_d, x, gamma, 7, 3, tokens, n_acc, flags, ratio, ws)
+            return
         P.sv_accept_estimate(S, A, d_es, d_ea, d_tab, p_hat, None)
         P.sv_select_length(p_hat, d_lat, P.SV_BATCH_GREEDY, gamma, offs, total)
         P.sv_verify_sample(z_t, None, z_d, x, gamma, 7, 3, tokens, n_acc, flags, ratio, ws)
