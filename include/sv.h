@@ -541,8 +541,10 @@ int sv_uniforms(uint64_t seed, uint32_t step, int B, int n_pos, double* u_accept
  * hipEvent_t handles is set for `kernel`, every launch of that kernel records
  * `start_event` immediately before and `stop_event` immediately after it on the
  * launch stream, so that hipEventElapsedTime(start, stop) brackets that kernel
- * alone.  Pass NULLs to clear.  Host-side global state: not thread-safe, and
- * the events must outlive the launches.  Returns SV_ERR_INVALID_ARG for an
+ * alone.  Pass NULLs to clear.  The setting is process-wide (it applies to the
+ * launches of every thread) and may be changed from any thread at any time: a
+ * launch sees either the old pair or the new one.  The events must outlive the
+ * launches.  Returns SV_ERR_INVALID_ARG for an
  * unknown kernel id or when only one of the two events is given.
  */
 int sv_set_timing_events(int kernel, void* start_event, void* stop_event);

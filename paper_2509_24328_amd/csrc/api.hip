@@ -1,4 +1,7 @@
 // Shape-independent parts of the C ABI: status strings and workspace sizing.
+#include <atomic>
+#include <mutex>
+
 #include "sv_device.hpp"
 #include "sv_host.hpp"
 
@@ -23,14 +26,27 @@ extern "C" size_t sv_workspace_bytes(int B, int k, int V, int dtype) {
 }
 
 namespace sv {
+namespace {
 TimingTap g_taps[SV_KERNEL_COUNT] = {};
+std::mutex g_taps_mutex;
+std::atomic<int> g_taps_set{0};      // number of kernels with a pair set: launches skip the lock while it is 0
+}  // namespace
+
+TimingTap timing_tap(int kernel) {
+  if (g_taps_set.load(std::memory_order_acquire) == 0) return TimingTap{nullptr, nullptr};
+  std::lock_guard<std::mutex> lock(g_taps_mutex);
+  return g_taps[kernel];             // both handles of one setting, never half of each
 }
+}  // namespace sv
 
 extern "C" int sv_set_timing_events(int kernel, void* start_event, void* stop_event) {
   if (kernel < 0 || kernel >= SV_KERNEL_COUNT) return SV_ERR_INVALID_ARG;
   if ((start_event == nullptr) != (stop_event == nullptr)) return SV_ERR_INVALID_ARG;
+  std::lock_guard<std::mutex> lock(sv::g_taps_mutex);
+  const bool was = sv::g_taps[kernel].start != nullptr, is = start_event != nullptr;
   sv::g_taps[kernel].start = reinterpret_cast<hipEvent_t>(start_event);
   sv::g_taps[kernel].stop = reinterpret_cast<hipEvent_t>(stop_event);
+  sv::g_taps_set.fetch_add((is ? 1 : 0) - (was ? 1 : 0), std::memory_order_release);
   return SV_OK;
 }
 

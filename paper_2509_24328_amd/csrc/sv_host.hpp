@@ -92,13 +92,15 @@ inline int launch_status() { return hipGetLastError() == hipSuccess ? SV_OK : SV
 struct TimingTap {
   hipEvent_t start, stop;
 };
-extern TimingTap g_taps[SV_KERNEL_COUNT];
+TimingTap timing_tap(int kernel);      // the pair set for `kernel` (nulls when none); safe from any thread
 
 struct TapScope {           // records start on construction, stop on destruction
   hipStream_t st;
   hipEvent_t stop;
-  TapScope(int kernel, hipStream_t s) : st(s), stop(g_taps[kernel].stop) {
-    if (g_taps[kernel].start) (void)hipEventRecord(g_taps[kernel].start, st);
+  TapScope(int kernel, hipStream_t s) : st(s), stop(nullptr) {
+    const TimingTap tap = timing_tap(kernel);
+    stop = tap.stop;
+    if (tap.start) (void)hipEventRecord(tap.start, st);
   }
   ~TapScope() {
     if (stop) (void)hipEventRecord(stop, st);
