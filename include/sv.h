@@ -83,6 +83,8 @@ enum {
 #define SV_MAX_K 64
 /* Largest number of tensors one sv_warp_*_multi call takes. */
 #define SV_WARP_MAX_TENSORS 8
+/* Largest history (context + drafted prefix) one sv_repetition_penalty call takes per row. */
+#define SV_PENALTY_MAX_TOKENS 4096
 /* Largest per-row capacity of a compacted support (sv_warp_compact). */
 #define SV_SUPPORT_MAX_CAP 1024
 
@@ -368,6 +370,27 @@ int sv_warp_cutoffs(const void* z, int rows, int V, int dtype,
 int sv_warp_cutoffs_multi(int n, const void* const* z, const int* rows, int V, int dtype,
                           const float* temperature, const int* top_k, const float* top_p,
                           float* const* cutoff, uint32_t* const* flags_or_null, sv_stream_t stream);
+
+/*
+ * Repetition penalty (appendix table of sampling hyper-parameters; the usual
+ * logits processor), in place, to be applied before the other warps: for every
+ * row (b, i) and every distinct token t of its history, z[t] becomes z[t] / penalty
+ * if z[t] > 0, else z[t] * penalty.  History of row (b, i): history[b, :], plus
+ * x[b, 0 .. min(i, k) - 1] when x is given (the tokens drafted before position i).
+ * Token ids outside [0, V) (padding: -1) are ignored.  float32 arithmetic (the
+ * division correctly rounded); bfloat16 logits are rounded to nearest-even.
+ *   z        dense [B, rows_per_seq, V], or packed [n_rows, V] with
+ *            row_offsets_or_null [B+1] int32: sequence b owns rows
+ *            row_offsets[b] .. row_offsets[b+1]-1 (at most rows_per_seq of them are
+ *            touched; a range outside [0, n_rows] is skipped)          in/out
+ *   history  [B, n_hist] int32 (may be NULL when n_hist = 0)            in
+ *   x_or_null [B, k] int32                                              in
+ * penalty > 0.  Limits: n_hist (+ k with x) <= SV_PENALTY_MAX_TOKENS; B,
+ * rows_per_seq <= 65535.  Calls on tensors that share rows must not overlap.
+ */
+int sv_repetition_penalty(void* z, const int32_t* row_offsets_or_null, int n_rows, int B, int rows_per_seq,
+                          int V, int dtype, const int32_t* history, int n_hist,
+                          const int32_t* x_or_null, int k, float penalty, sv_stream_t stream);
 
 /*
  * sv_row_stats on warped distributions: P_d = soft-max(z_d / temperature_d) over

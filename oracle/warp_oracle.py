@@ -1,8 +1,8 @@
 """Plain CPU oracle for the sampling warps applied to logits before the SV
 computations: temperature, top-k and top-p (the sampling hyper-parameters the
 SV paper lists per model series in its appendix table "Sampling
-hyperparameters for each model series"; repetition penalty needs the token
-history and is not covered).
+hyperparameters for each model series"), and the repetition penalty of the
+same table, which acts on the logits before them and needs the token history.
 
 TEST INFRASTRUCTURE ONLY (see sv_oracle): float64 NumPy, one row at a time.
 
@@ -22,9 +22,22 @@ arbitrary sort order).  Without ties this is exactly "the K most likely
 tokens" and "the smallest set of most likely tokens whose mass reaches P".
 K <= 0 or K >= V switches top-k off, P >= 1 switches top-p off.
 
+Repetition penalty (the table gives one value per model series, not the
+operation; the usual logits processor is used): every token that occurs in the
+history of a position has its logit divided by theta if it is positive and
+multiplied by theta otherwise, once per distinct token.  The history of drafted
+position i of a sequence is the sequence's context plus the tokens drafted before
+i.  The penalised logit is written back in the storage type, so the arithmetic
+is fixed to keep both sides of the parity check on the same bits: theta and the
+logit are float32, the product / quotient is the correctly rounded float32
+operation, and bfloat16 storage rounds that to nearest-even.
+
 Pins (tests/test_oracle_warp.py): torch.topk, a sort/cumsum rendering of top-p
 on rows without ties, scipy soft-max for the temperature, minimality of the
-kept set, monotonicity in K and P, whole-group treatment of ties.
+kept set, monotonicity in K and P, whole-group treatment of ties; the three
+warps in sequence and the repetition penalty against the logits processors of
+the `transformers` package on rows without ties; the bfloat16 rounding against
+torch's conversion.
 """
 from __future__ import annotations
 
@@ -86,3 +99,49 @@ def warp_rows(z, temperature=1.0, top_k=0, top_p=1.0):
             y = np.where(row >= c, y, -np.inf)
         out[idx] = y
     return out, cut, flags
+
+
+def _store_like(values32, like):
+    """float32 values in the storage type of `like`: float32 as is, uint16 = bfloat16 bit
+    patterns rounded to nearest-even (NaN stays NaN)."""
+    v = np.asarray(values32, dtype=np.float32)
+    if np.asarray(like).dtype != np.uint16:
+        return v
+    u = v.view(np.uint32).astype(np.uint64)
+    rounded = ((u + np.uint64(0x7FFF) + ((u >> np.uint64(16)) & np.uint64(1))) >> np.uint64(16)).astype(np.uint16)
+    nan = np.isnan(v)
+    rounded[nan] = ((u[nan] >> np.uint64(16)) | np.uint64(0x0040)).astype(np.uint16)     # quiet, sign and payload top kept
+    return rounded
+
+
+def repetition_penalty(z, history, penalty, x=None):
+    """Logits after the repetition penalty, in the storage type of `z`.
+
+    z        [B, R, V] stored logits (float32, or uint16 bfloat16 bit patterns); row i of
+             sequence b is position i
+    history  [B, n_hist] context token ids, entries outside [0, V) (padding: -1) are ignored
+    x        optional [B, k] drafted tokens: position i is also penalised for x[b, :min(i, k)]
+    penalty  theta > 0, taken as a float32
+    """
+    z = np.asarray(z)
+    out = z.copy()
+    B, R, V = z.shape
+    theta = np.float32(penalty)
+    history = np.asarray(history)
+    for b in range(B):
+        for i in range(R):
+            toks = list(history[b])
+            if x is not None:
+                toks += list(np.asarray(x)[b, :min(i, np.asarray(x).shape[1])])
+            toks = sorted({int(t) for t in toks if 0 <= int(t) < V})          # once per distinct token
+            if not toks:
+                continue
+            if z.dtype == np.uint16:
+                vals = (z[b, i, toks].astype(np.uint32) << np.uint32(16)).view(np.float32)
+            else:
+                vals = z[b, i, toks].astype(np.float32)
+            with np.errstate(all="ignore"):
+                new = np.where(vals < 0, vals * theta, vals / theta).astype(np.float32)
+            out[b, i, toks] = _store_like(new, z)
+    return out
+

@@ -33,7 +33,7 @@ EXPORTS = ("sv_strerror", "sv_workspace_bytes", "sv_row_stats", "sv_accept_estim
            "sv_warp_compact", "sv_row_stats_sparse", "sv_verify_sample_sparse", "sv_uniforms",
            "sv_accept_ratio_sparse", "sv_verify_sample_static", "sv_accept_ratio_warped",
            "sv_warp_cutoffs_multi", "sv_warp_compact_multi", "sv_verify_sample_chained",
-           "sv_verify_sample_warped_chained", "sv_estimate_select")
+           "sv_verify_sample_warped_chained", "sv_estimate_select", "sv_repetition_penalty")
 SV_WARP_MAX_TENSORS = 8
 SV_STATIC_SCRATCH_BYTES = 1 << 20
 (SV_KERNEL_ROW_STATS, SV_KERNEL_ACCEPT_ESTIMATE, SV_KERNEL_SELECT_LENGTH, SV_KERNEL_VERIFY_ROWS,
@@ -56,6 +56,8 @@ lib.sv_accept_estimate.restype = _i
 lib.sv_accept_estimate.argtypes = [_vp, _vp, _i, _vp, _i, _vp, _i, _vp, _vp, _vp, _vp]
 lib.sv_select_length.restype = _i
 lib.sv_select_length.argtypes = [_vp, _i, _i, _vp, _i, _i, _vp, _vp, _vp, _vp]
+lib.sv_repetition_penalty.restype = _i
+lib.sv_repetition_penalty.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _vp, _i, _vp, _i, ctypes.c_float, _vp]
 lib.sv_estimate_select.restype = _i
 lib.sv_estimate_select.argtypes = [_vp, _vp, _i, _i, _vp, _i, _vp, _i, _vp, _vp, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.sv_verify_sample.restype = _i
@@ -328,6 +330,19 @@ def sv_verify_sample_warped_chained(z_t, t_offsets, z_d, x, gamma, temperature_t
                                                _ptr(cutoff_t), temperature_d, _ptr(cutoff_d), seed, step,
                                                _ptr(out_tokens), _ptr(n_accept), _ptr(flags), _ptr(ratio),
                                                _ptr(ws), 0 if ws is None else ws.numel(), _stream(stream)))
+
+
+def sv_repetition_penalty(z, history, penalty, x=None, row_offsets=None, B=None, rows_per_seq=None, stream=None):
+    """In place.  z: dense [B, R, V]; or packed [n_rows, V] with row_offsets [B+1], B and rows_per_seq given."""
+    if row_offsets is None:
+        B, rows_per_seq, V = z.shape
+        n_rows = 0
+    else:
+        n_rows, V = z.shape
+    n_hist = 0 if history is None else history.shape[1]
+    k = 0 if x is None else x.shape[1]
+    _check(lib.sv_repetition_penalty(_ptr(z), _ptr(row_offsets), n_rows, B, rows_per_seq, V, _dtype_tag(z),
+                                     _ptr(history), n_hist, _ptr(x), k, penalty, _stream(stream)))
 
 
 class Supports:

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsv.so")
 SOURCES = ["api.hip", "row_stats.hip", "accept_estimate.hip", "select_length.hip", "verify_sample.hip",
-           "profile.hip", "warp.hip", "sparse.hip"]
+           "profile.hip", "warp.hip", "sparse.hip", "penalty.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
          # products are fused only where the code says fmaf: the online
          # accumulator relies on c(m) being the same rounded fp32 number

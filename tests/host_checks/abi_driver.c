@@ -81,6 +81,15 @@ int main(void) {
   EXPECT(sv_estimate_select(p, p, 4, 4, p, 5, p, 5, p, p, 17, 0, 0, 0, p, p, p, 0), SV_ERR_NULL);
   EXPECT(sv_estimate_select(p, p, SV_SELECT_MAX_KEYS + 1, 1, p, 5, p, 5, p, p, 10000, 0, p, 0, p, p, p, 0), SV_ERR_TOO_LARGE);
   EXPECT(sv_estimate_select(0, 0, 0, 4, 0, 5, 0, 5, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0), SV_OK);
+  EXPECT(sv_repetition_penalty(p, 0, 0, 2, 3, 8, -1, p, 4, 0, 0, 1.2f, 0), SV_ERR_DTYPE);
+  EXPECT(sv_repetition_penalty(p, 0, 0, 2, 3, 8, SV_BF16, p, 4, 0, 0, 0.0f, 0), SV_ERR_INVALID_ARG);
+  EXPECT(sv_repetition_penalty(p, 0, 0, 2, 0, 8, SV_BF16, p, 4, 0, 0, 1.2f, 0), SV_ERR_INVALID_ARG);
+  EXPECT(sv_repetition_penalty(p, 0, 0, 2, 3, 8, SV_BF16, p, SV_PENALTY_MAX_TOKENS + 1, 0, 0, 1.2f, 0), SV_ERR_TOO_LARGE);
+  EXPECT(sv_repetition_penalty(p, 0, 0, 2, 3, 8, SV_BF16, p, SV_PENALTY_MAX_TOKENS, p, 1, 1.2f, 0), SV_ERR_TOO_LARGE);
+  EXPECT(sv_repetition_penalty(0, 0, 0, 2, 3, 8, SV_BF16, p, 4, 0, 0, 1.2f, 0), SV_ERR_NULL);
+  EXPECT(sv_repetition_penalty(p, 0, 0, 2, 3, 8, SV_BF16, 0, 4, 0, 0, 1.2f, 0), SV_ERR_NULL);
+  EXPECT(sv_repetition_penalty(p, 0, 0, 0, 3, 8, SV_BF16, 0, 4, 0, 0, 1.2f, 0), SV_OK);
+  EXPECT(sv_repetition_penalty(p, 0, 0, 2, 3, 8, SV_BF16, 0, 0, 0, 0, 1.2f, 0), SV_OK);
   /* sv_verify_sample and its variants */
   EXPECT(sv_verify_sample(p, 0, 0, p, p, 0, 2, 2, 8, -1, 0, 0, p, p, p, 0, p, big, 0), SV_ERR_DTYPE);
   EXPECT(sv_verify_sample(p, 0, 0, p, p, 0, 2, SV_MAX_K + 1, 8, SV_BF16, 0, 0, p, p, p, 0, p, big, 0), SV_ERR_TOO_LARGE);

@@ -104,3 +104,85 @@ def test_warp_rows_and_temperature():
     zb[0, 0, 3] = np.nan
     out, cut, fl = W.warp_rows(zb, 1.0, 5, 0.9)
     assert fl[0, 0] & O.FLAG_BAD_ROW and np.isnan(cut[0, 0]) and np.isnan(out[0, 0, 3])
+
+
+def test_warps_in_sequence_match_the_transformers_logits_processors():
+    """Temperature -> top-k -> top-p on rows without ties: the kept set of the oracle is the set
+    the `transformers` warpers leave finite, and the kept values are z / T."""
+    from transformers import TemperatureLogitsWarper, TopKLogitsWarper, TopPLogitsWarper
+    rng = np.random.default_rng(11)
+    ids = torch.zeros((1, 1), dtype=torch.long)
+    for V, T, K, P in ((200, 0.7, 20, 0.8), (1000, 0.95, 20, 0.6), (1000, 0.6, 0, 0.9), (64, 1.3, 5, 1.0),
+                       (5000, 0.7, 50, 0.95), (300, 1.0, 0, 0.5)):
+        for _ in range(5):
+            z = _distinct_row(rng, V)
+            y, cut, fl = W.warp_rows(z[None, None, :], T, K, P)
+            s = torch.from_numpy(z)[None, :].clone()
+            s = TemperatureLogitsWarper(T)(ids, s)
+            if 0 < K < V:
+                s = TopKLogitsWarper(top_k=K)(ids, s)
+            if P < 1.0:
+                s = TopPLogitsWarper(top_p=P)(ids, s)
+            lib_kept = np.isfinite(s[0].numpy())
+            if fl[0, 0] & O.FLAG_NEAR_TIE:
+                continue                                      # a decision within 1e-6 of P may go either way
+            mine = np.isfinite(y[0, 0])
+            assert np.array_equal(mine, lib_kept), (V, T, K, P, mine.sum(), lib_kept.sum())
+            assert np.allclose(y[0, 0][mine], s[0].numpy()[lib_kept], rtol=1e-12)
+
+
+def test_repetition_penalty_matches_the_transformers_processor():
+    from transformers import RepetitionPenaltyLogitsProcessor
+    rng = np.random.default_rng(12)
+    for V, n_hist, theta in ((50, 7, 1.3), (1000, 200, 1.1), (1000, 40, 1.05), (33, 60, 2.0), (200, 0, 1.2)):
+        B, R = 3, 2
+        z = (3 * rng.standard_normal((B, R, V))).astype(np.float32)
+        z[0, 0, 3] = 0.0
+        z[1, 1, 5] = -np.inf
+        hist = rng.integers(0, V, size=(B, max(n_hist, 1))).astype(np.int64)
+        if n_hist == 0:
+            hist[:] = -1                                     # padding only
+        else:
+            hist[:, 0] = hist[:, -1]                         # a duplicate: penalised once
+            hist[0, 1] = 3
+            hist[1, 2] = 5
+        got = W.repetition_penalty(z, hist, theta)
+        proc = RepetitionPenaltyLogitsProcessor(penalty=float(np.float32(theta)))
+        for i in range(R):
+            if n_hist == 0:
+                ref = z[:, i]
+            else:
+                ref = proc(torch.from_numpy(hist), torch.from_numpy(z[:, i].copy())).numpy()
+            assert np.array_equal(got[:, i], ref, equal_nan=True), (V, n_hist, theta, i)
+    # padding and out-of-range ids are ignored, theta = 1 changes nothing
+    z = (3 * rng.standard_normal((1, 1, 20))).astype(np.float32)
+    assert np.array_equal(W.repetition_penalty(z, np.array([[-1, 20, 99, -7]]), 1.5), z)
+    assert np.array_equal(W.repetition_penalty(z, np.array([[1, 2, 3]]), 1.0), z)
+
+
+def test_repetition_penalty_draft_prefix_and_bfloat16_storage():
+    rng = np.random.default_rng(13)
+    B, k, V = 2, 3, 40
+    zf = (3 * rng.standard_normal((B, k + 1, V))).astype(np.float32)
+    zb = torch.from_numpy(zf).to(torch.bfloat16)
+    bits = zb.view(torch.int16).numpy().view(np.uint16)
+    hist = np.array([[1, 2, -1], [7, 7, 9]])
+    x = np.array([[4, 5, 6], [9, 10, 11]])
+    theta = 1.25
+    got = W.repetition_penalty(bits, hist, theta, x=x)
+    stored = zb.float().numpy()
+    for b in range(B):
+        for i in range(k + 1):
+            toks = {int(t) for t in hist[b] if t >= 0} | {int(t) for t in x[b, :min(i, k)]}
+            exp = stored[b, i].copy()
+            for t in toks:                                   # position i sees the tokens drafted before it
+                v = np.float32(exp[t])
+                exp[t] = v * np.float32(theta) if v < 0 else v / np.float32(theta)
+            exp_bits = torch.from_numpy(exp).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+            assert np.array_equal(got[b, i], exp_bits), (b, i)
+    # the rounding helper against torch's conversion on arbitrary float32 values (ties, tiny, huge, inf)
+    v = np.concatenate([rng.standard_normal(5000).astype(np.float32) * np.float32(10.0) ** rng.integers(-30, 30, 5000),
+                        np.array([0.0, -0.0, np.inf, -np.inf, 1.00390625, 1.01171875, 3.3895e38], dtype=np.float32)])
+    mine = W._store_like(v, np.zeros(1, dtype=np.uint16))
+    ref = torch.from_numpy(v).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(mine, ref)
