@@ -652,6 +652,23 @@ def main():
                        "cutoff_pass_GBps": round(B * (3 * k + 1) * row_bytes / cut_us * 1e-3, 1),
                        "cutoff_pass_one_launch_per_tensor_us": round(cut3_us, 1)}
 
+        # the repetition penalty of the same table row (1.05), timed on scratch copies of the three
+        # tensors (it rewrites logits in place): 512 context tokens per sequence plus the drafted prefix
+        rp_hist = torch.randint(0, V, (B, 512), dtype=torch.int32, device="cuda")
+        rp_z = [c0["z_t"].clone(), c0["z_d"].clone(), c0["z_c"].clone()]
+        for z_ in rp_z:
+            P.sv_repetition_penalty(z_, rp_hist, 1.05, x=c0["x"], stream=stream)
+        torch.cuda.synchronize()
+        rp_reps = 20
+        r0 = time.perf_counter()
+        for _ in range(rp_reps):
+            for z_ in rp_z:
+                P.sv_repetition_penalty(z_, rp_hist, 1.05, x=c0["x"], stream=stream)
+        torch.cuda.synchronize()
+        warped_step["repetition_penalty"] = {"penalty": 1.05, "context_tokens": 512, "rows": B * (3 * k + 1),
+                                             "three_calls_us": round((time.perf_counter() - r0) * 1e6 / rp_reps, 1)}
+        del rp_z
+
         # the same warped step on compacted supports: one compaction pass per tensor, then
         # every later stage works on the few kept tokens of each row
         cap = 64
