@@ -9,6 +9,13 @@
  *   sv_select_length    verification length per sequence         (Sec. 5: E(N|gamma), goodput, batch greedy)
  *   sv_verify_sample    speculative-sampling verification        (Sec. 4.2 last paragraph; Leviathan et al.)
  *
+ * The same step in three calls: sv_row_stats, sv_estimate_select (the second and
+ * third call in one launch), sv_verify_sample_chained (takes the draft rows'
+ * normalisers over from sv_row_stats through the workspace and sweeps the
+ * target rows only).  Further down: the profile-construction pass that
+ * produces the table, the sampling warps (temperature, top-k, top-p,
+ * repetition penalty) with dense and compacted forms of the step, and helpers.
+ *
  * Conventions common to all calls
  *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
  *     never allocates, frees or synchronises: each call only enqueues kernels
@@ -31,7 +38,9 @@
  *   - `ws` is caller-provided device scratch of at least
  *     sv_workspace_bytes(B, k, V, dtype) bytes, 256-byte aligned, which may be
  *     reused by the next call on the same stream.  Calls that share a
- *     workspace must not overlap in time.
+ *     workspace must not overlap in time.  Its contents mean nothing to the
+ *     caller and need no initialisation; the one thing that survives a call is
+ *     what sv_row_stats leaves for sv_verify_sample_chained.
  */
 #ifndef SV_H_
 #define SV_H_
