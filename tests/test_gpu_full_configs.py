@@ -64,6 +64,7 @@ def test_full_config_dense(index):
     n_tie, n_edge = H.assert_verify(got, ref, k)
     print(f"  verify (selected gamma, mean {rg.mean():.2f}) ok: near-tie {n_tie}, near-cdf-edge {n_edge}",
           flush=True)
+    H.assert_verify(H.gpu_verify_chained(d["z_t"], d["z_d"], d["z_c"], d["x"], gamma=rg, seed=1, step=3), ref, k)
 
 
 def test_full_config5_ragged_chain():
@@ -87,6 +88,9 @@ def test_full_config5_ragged_chain():
     got_dense = H.gpu_verify(d["z_t"], d["z_d"], d["x"], gamma=rg, seed=5, step=2)
     assert np.array_equal(got_dense["tokens"], got["tokens"])
     assert np.array_equal(got_dense["n_accept"], got["n_accept"])
+    # the chained call (draft normalisers from sv_row_stats, only the packed target rows swept)
+    got_chained = H.gpu_verify_chained(packed, d["z_d"], d["z_c"], d["x"], gamma=rg, t_offsets=ro, seed=5, step=2)
+    H.assert_verify(got_chained, ref, k)
 
 
 def test_full_config_warped_compacted_ragged():
