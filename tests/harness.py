@@ -129,7 +129,8 @@ def close(got, ref, rel=REL, abs_floor=0.0):
 
 
 def assert_row_stats(got, ref, with_kl=True):
-    """fp32 stats within 1e-5 relative.  TV = 1 - S and KL are sums of
+    """fp32 stats within 1e-5 relative (S additionally to 2e-31 absolute: below that its terms
+    underflow float32).  TV = 1 - S and KL are sums of
     probability differences whose entries carry ~1e-7 relative error each, so
     near zero they get an absolute floor: 2e-6 for KL and the entropy, 5e-6 for
     TV (on a flat row every term has the same exponent, near -17 at 1e5 entries,
@@ -138,7 +139,9 @@ def assert_row_stats(got, ref, with_kl=True):
     for name in ("lse_d", "lse_c"):
         ok = close(got[name], ref[name], REL, 1e-6)
         assert ok.all(), (name, got[name][~ok], ref[name][~ok])
-    ok = close(got["S"], ref["S"], REL)
+    # (terms of S below 2^-126 underflow float32 on the HIP side: an S of that order of
+    #  magnitude - disjoint distributions - is resolved to V * 2^-126 only; V <= 2^24)
+    ok = close(got["S"], ref["S"], REL, float(2 ** 24 * np.finfo(np.float32).tiny))
     assert ok.all(), ("S", got["S"][~ok], ref["S"][~ok])
     ok = close(got["A"], ref["A"], REL, 1e-30)
     assert ok.all(), ("A", got["A"][~ok], ref["A"][~ok])
