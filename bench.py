@@ -679,8 +679,8 @@ def main():
         def sparse_once(i):
             P.sv_warp_compact_multi(w_zs, wT, wK, wP, [sup_t, sup_d, sup_c], None, None, stream)
             P.sv_row_stats_sparse(sup_d, sup_c, c0["x"], V, lse_d, lse_c, s_S, s_A, None, None, stream)
-            P.sv_accept_estimate(s_S, s_A, d_es, d_ea, d_tab, p_hat, None, stream)
-            P.sv_select_length(p_hat, d_lat, P.SV_BATCH_GREEDY, gamma, offs, total, stream)
+            P.sv_estimate_select(s_S, s_A, d_es, d_ea, d_tab, d_lat, P.SV_BATCH_GREEDY, p_hat, gamma, offs, total,
+                                 None, stream)
             P.sv_verify_sample_sparse(sup_t, None, sup_d, c0["x"], None, V, 0, i, s_tokens, s_nacc, s_flags,
                                       None, stream)
 
