@@ -618,15 +618,36 @@ def main():
             P.sv_verify_sample_warped(c0["z_t"], None, c0["z_d"], c0["x"], None, wT, cut_t, wT, cut_d, 0, i,
                                       tokens, n_acc, flags, None, ws, stream)
 
+        def warped_once3(i):        # three-call form: estimate + selection in one launch, chained verification
+            P.sv_warp_cutoffs_multi(w_zs, wT, wK, wP, w_cuts, None, stream)
+            P.sv_row_stats_warped(c0["z_d"], c0["z_c"], c0["x"], wT, cut_d, wT, cut_c, lse_d, lse_c, S, A,
+                                  None, None, ws, stream)
+            P.sv_estimate_select(S, A, d_es, d_ea, d_tab, d_lat, P.SV_BATCH_GREEDY, p_hat, gamma, offs, total, None, stream)
+            P.sv_verify_sample_warped_chained(c0["z_t"], None, c0["z_d"], c0["x"], None, wT, cut_t, wT, cut_d, 0, i,
+                                              tokens, n_acc, flags, None, ws, stream)
+
+        reps = 20
+        for i in range(3):
+            warped_once3(i)
+        torch.cuda.synchronize()
+        w0 = time.perf_counter()
+        for i in range(reps):
+            warped_once3(i)
+        torch.cuda.synchronize()
+        warped3_ms = (time.perf_counter() - w0) * 1e3 / reps
+        assert not (flags.cpu().numpy() & 64).any(), "chained warped verification did not find the statistics pass"
+        tokens3, n_acc3 = tokens.clone(), n_acc.clone()
         for i in range(3):
             warped_once(i)
         torch.cuda.synchronize()
-        reps = 20
         w0 = time.perf_counter()
         for i in range(reps):
             warped_once(i)
         torch.cuda.synchronize()
         w1 = time.perf_counter()
+        # (both forms ended on step reps - 1: same uniforms, so the same accept counts off the near flags)
+        same3 = bool(np.array_equal(n_acc3.cpu().numpy()[(flags.cpu().numpy() & (2 | 8)) == 0],
+                                    n_acc.cpu().numpy()[(flags.cpu().numpy() & (2 | 8)) == 0]))
         ce0, ce1 = hip.event(), hip.event()
         torch.cuda.synchronize()
         # the cutoff pass alone (all three tensors in one launch), bracketed by events on the launch
@@ -647,6 +668,8 @@ def main():
         cut_us, cut3_us = float(np.mean(cut_t_)), float(np.mean(cut3_t_))
         warped_step = {"temperature": 0.7, "top_k": wK, "top_p": wP,
                        "ms_per_step": round((w1 - w0) * 1e3 / reps, 4),
+                       "three_call_ms_per_step": round(warped3_ms, 4),
+                       "three_call_n_accept_equal_off_near_flags": same3,
                        "cutoff_pass_us": round(cut_us, 1),
                        "cutoff_rows": B * (3 * k + 1),
                        "cutoff_pass_GBps": round(B * (3 * k + 1) * row_bytes / cut_us * 1e-3, 1),
