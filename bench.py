@@ -679,8 +679,7 @@ def main():
         # tensors (it rewrites logits in place): 512 context tokens per sequence plus the drafted prefix
         rp_hist = torch.randint(0, V, (B, 512), dtype=torch.int32, device="cuda")
         rp_z = [c0["z_t"].clone(), c0["z_d"].clone(), c0["z_c"].clone()]
-        for z_ in rp_z:
-            P.sv_repetition_penalty(z_, rp_hist, 1.05, x=c0["x"], stream=stream)
+        P.sv_repetition_penalty_multi(rp_z, rp_hist, 1.05, x=c0["x"], stream=stream)
         torch.cuda.synchronize()
         rp_reps = 20
         r0 = time.perf_counter()
@@ -688,8 +687,13 @@ def main():
             for z_ in rp_z:
                 P.sv_repetition_penalty(z_, rp_hist, 1.05, x=c0["x"], stream=stream)
         torch.cuda.synchronize()
+        r1 = time.perf_counter()
+        for _ in range(rp_reps):
+            P.sv_repetition_penalty_multi(rp_z, rp_hist, 1.05, x=c0["x"], stream=stream)
+        torch.cuda.synchronize()
         warped_step["repetition_penalty"] = {"penalty": 1.05, "context_tokens": 512, "rows": B * (3 * k + 1),
-                                             "three_calls_us": round((time.perf_counter() - r0) * 1e6 / rp_reps, 1)}
+                                             "three_calls_us": round((r1 - r0) * 1e6 / rp_reps, 1),
+                                             "one_launch_us": round((time.perf_counter() - r1) * 1e6 / rp_reps, 1)}
         del rp_z
 
         # the same warped step on compacted supports: one compaction pass per tensor, then

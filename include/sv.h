@@ -402,6 +402,21 @@ int sv_repetition_penalty(void* z, const int32_t* row_offsets_or_null, int n_row
                           const int32_t* x_or_null, int k, float penalty, sv_stream_t stream);
 
 /*
+ * sv_repetition_penalty on up to SV_WARP_MAX_TENSORS logit tensors of one batch in
+ * one launch (the draft, companion and target logits of a step share B, V, dtype,
+ * the history and the drafted tokens; they differ in their rows per sequence and
+ * in whether they are packed).
+ *   z, row_offsets_or_null, n_rows_or_null, rows_per_seq   HOST arrays of length n with the
+ *        per-tensor arguments of sv_repetition_penalty (row_offsets_or_null itself, or
+ *        single entries of it, may be NULL = dense; n_rows_or_null may be NULL when
+ *        row_offsets_or_null is)
+ */
+int sv_repetition_penalty_multi(int n, void* const* z, const int32_t* const* row_offsets_or_null,
+                                const int* n_rows_or_null, int B, const int* rows_per_seq, int V, int dtype,
+                                const int32_t* history, int n_hist, const int32_t* x_or_null, int k,
+                                float penalty, sv_stream_t stream);
+
+/*
  * sv_row_stats on warped distributions: P_d = soft-max(z_d / temperature_d) over
  * {v : z_d[v] >= cutoff_d[row]}, P_c likewise with its own temperature and
  * cutoffs (the draft and the companion are run with the sampling

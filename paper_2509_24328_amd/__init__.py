@@ -8,5 +8,5 @@ from .binding import (sv_warp_cutoffs_multi, sv_warp_compact_multi, sv_accept_ra
                       SV_BATCH_GREEDY, SV_BF16, SV_F32, SV_PER_SEQUENCE, SvError,  # noqa: F401
                       alloc_workspace, sv_accept_estimate, sv_row_stats, sv_select_length,
                       sv_set_timing_events, sv_strerror, sv_verify_sample, sv_verify_sample_static,
-                      sv_verify_sample_chained, sv_verify_sample_warped_chained, sv_estimate_select, sv_repetition_penalty,
+                      sv_verify_sample_chained, sv_verify_sample_warped_chained, sv_estimate_select, sv_repetition_penalty, sv_repetition_penalty_multi,
                       sv_workspace_bytes)

@@ -33,7 +33,8 @@ EXPORTS = ("sv_strerror", "sv_workspace_bytes", "sv_row_stats", "sv_accept_estim
            "sv_warp_compact", "sv_row_stats_sparse", "sv_verify_sample_sparse", "sv_uniforms",
            "sv_accept_ratio_sparse", "sv_verify_sample_static", "sv_accept_ratio_warped",
            "sv_warp_cutoffs_multi", "sv_warp_compact_multi", "sv_verify_sample_chained",
-           "sv_verify_sample_warped_chained", "sv_estimate_select", "sv_repetition_penalty")
+           "sv_verify_sample_warped_chained", "sv_estimate_select", "sv_repetition_penalty",
+           "sv_repetition_penalty_multi")
 SV_WARP_MAX_TENSORS = 8
 SV_STATIC_SCRATCH_BYTES = 1 << 20
 (SV_KERNEL_ROW_STATS, SV_KERNEL_ACCEPT_ESTIMATE, SV_KERNEL_SELECT_LENGTH, SV_KERNEL_VERIFY_ROWS,
@@ -58,6 +59,8 @@ lib.sv_select_length.restype = _i
 lib.sv_select_length.argtypes = [_vp, _i, _i, _vp, _i, _i, _vp, _vp, _vp, _vp]
 lib.sv_repetition_penalty.restype = _i
 lib.sv_repetition_penalty.argtypes = [_vp, _vp, _i, _i, _i, _i, _i, _vp, _i, _vp, _i, ctypes.c_float, _vp]
+lib.sv_repetition_penalty_multi.restype = _i
+lib.sv_repetition_penalty_multi.argtypes = [_i, _vp, _vp, _vp, _i, _vp, _i, _i, _vp, _i, _vp, _i, ctypes.c_float, _vp]
 lib.sv_estimate_select.restype = _i
 lib.sv_estimate_select.argtypes = [_vp, _vp, _i, _i, _vp, _i, _vp, _i, _vp, _vp, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.sv_verify_sample.restype = _i
@@ -343,6 +346,31 @@ def sv_repetition_penalty(z, history, penalty, x=None, row_offsets=None, B=None,
     k = 0 if x is None else x.shape[1]
     _check(lib.sv_repetition_penalty(_ptr(z), _ptr(row_offsets), n_rows, B, rows_per_seq, V, _dtype_tag(z),
                                      _ptr(history), n_hist, _ptr(x), k, penalty, _stream(stream)))
+
+
+def sv_repetition_penalty_multi(zs, history, penalty, x=None, row_offsets=None, B=None, rows_per_seq=None,
+                                stream=None):
+    """In place, several tensors of one batch in one launch.  zs: dense [B, R_t, V] tensors; a packed one
+    ([n_rows, V]) needs its entry of row_offsets ([B+1]) and of rows_per_seq set, and B given."""
+    n = len(zs)
+    offs = [None] * n if row_offsets is None else list(row_offsets)
+    rps = [None] * n if rows_per_seq is None else list(rows_per_seq)
+    n_rows = []
+    for t, z in enumerate(zs):
+        if offs[t] is None:
+            B, rps[t] = z.shape[0], z.shape[1]
+            n_rows.append(0)
+        else:
+            n_rows.append(z.shape[0])
+    V = zs[0].shape[-1]
+    tag = _dtype_tag(zs[0])
+    if any(z.shape[-1] != V or _dtype_tag(z) != tag for z in zs):
+        raise SvError(SV_ERR_INVALID_ARG)
+    n_hist = 0 if history is None else history.shape[1]
+    k = 0 if x is None else x.shape[1]
+    _check(lib.sv_repetition_penalty_multi(n, _host_ptrs(zs), _host_ptrs(offs), (ctypes.c_int * n)(*n_rows), B,
+                                           (ctypes.c_int * n)(*rps), V, tag, _ptr(history), n_hist, _ptr(x), k,
+                                           penalty, _stream(stream)))
 
 
 class Supports:

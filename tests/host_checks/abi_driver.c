@@ -90,6 +90,14 @@ int main(void) {
   EXPECT(sv_repetition_penalty(p, 0, 0, 2, 3, 8, SV_BF16, 0, 4, 0, 0, 1.2f, 0), SV_ERR_NULL);
   EXPECT(sv_repetition_penalty(p, 0, 0, 0, 3, 8, SV_BF16, 0, 4, 0, 0, 1.2f, 0), SV_OK);
   EXPECT(sv_repetition_penalty(p, 0, 0, 2, 3, 8, SV_BF16, 0, 0, 0, 0, 1.2f, 0), SV_OK);
+  {
+    void* zs[2] = {p, p};
+    int rps[2] = {3, 4};
+    EXPECT(sv_repetition_penalty_multi(0, zs, 0, 0, 2, rps, 8, SV_BF16, p, 4, 0, 0, 1.2f, 0), SV_ERR_INVALID_ARG);
+    EXPECT(sv_repetition_penalty_multi(2, 0, 0, 0, 2, rps, 8, SV_BF16, p, 4, 0, 0, 1.2f, 0), SV_ERR_NULL);
+    EXPECT(sv_repetition_penalty_multi(2, zs, 0, 0, 2, rps, 8, SV_BF16, p, 4, 0, 0, -1.0f, 0), SV_ERR_INVALID_ARG);
+    EXPECT(sv_repetition_penalty_multi(2, zs, 0, 0, 0, rps, 8, SV_BF16, p, 4, 0, 0, 1.2f, 0), SV_OK);
+  }
   /* sv_verify_sample and its variants */
   EXPECT(sv_verify_sample(p, 0, 0, p, p, 0, 2, 2, 8, -1, 0, 0, p, p, p, 0, p, big, 0), SV_ERR_DTYPE);
   EXPECT(sv_verify_sample(p, 0, 0, p, p, 0, 2, SV_MAX_K + 1, 8, SV_BF16, 0, 0, p, p, p, 0, p, big, 0), SV_ERR_TOO_LARGE);

@@ -82,6 +82,28 @@ def test_packed_target_rows_and_the_rest_of_the_step():
     H.assert_verify(got, H.oracle_verify(ref_t, ref_d, x, gamma=gamma, seed=2, step=9), k)
 
 
+def test_three_tensors_in_one_launch_equal_three_launches():
+    P = H.sv()
+    B, k, V = 5, 4, 32000
+    rng = np.random.default_rng(6)
+    cfg = svgen.make_config(1, seed=4322, B=B, k=k, V=V, dtype="bf16", device="cuda")
+    hist = H.dev(_history(rng, B, 200, V), torch.int32)
+    gamma = np.array([4, 0, 2, 1, 3], dtype=np.int32)
+    offs = H.dev(np.concatenate([[0], np.cumsum(gamma + 1)]).astype(np.int32), torch.int32)
+    packed = torch.cat([cfg["z_t"][b, :gamma[b] + 1] for b in range(B)]).contiguous()
+    one = [packed.clone(), cfg["z_d"].clone(), cfg["z_c"].clone()]
+    P.sv_repetition_penalty(one[0], hist, 1.05, x=cfg["x"], row_offsets=offs, B=B, rows_per_seq=k + 1)
+    P.sv_repetition_penalty(one[1], hist, 1.05, x=cfg["x"])
+    P.sv_repetition_penalty(one[2], hist, 1.05, x=cfg["x"])
+    many = [packed.clone(), cfg["z_d"].clone(), cfg["z_c"].clone()]
+    P.sv_repetition_penalty_multi(many, hist, 1.05, x=cfg["x"], row_offsets=[offs, None, None], B=B,
+                                  rows_per_seq=[k + 1, None, None])
+    torch.cuda.synchronize()
+    for a_, b_ in zip(one, many):
+        assert torch.equal(a_.view(torch.int16), b_.view(torch.int16))
+    assert not torch.equal(many[1].view(torch.int16), cfg["z_d"].view(torch.int16))
+
+
 def test_limits_and_no_ops():
     P = H.sv()
     Bd = P.binding
