@@ -747,9 +747,9 @@ __device__ __forceinline__ void warp_row(const void* z, const int r, int V, cons
 }
 
 // Up to kWarpMaxTensors logit tensors of one vocabulary size in one launch (one workgroup
-// per row of any of them): with about two rows per compute unit all workgroups of a
-// launch sweep, then all decide, and the memory system idles meanwhile; more rows per
-// launch overlap the decisions of some rows with the sweeps of others.
+// per row of any of them): a launch with about two rows per compute unit has nothing to
+// put behind the decisions of its last rows and thins out over its final third; more
+// rows per launch overlap the decisions of some rows with the sweeps of others.
 constexpr int kWarpMaxTensors = SV_WARP_MAX_TENSORS;
 struct WarpBatch {
   int n;

@@ -332,3 +332,45 @@ def test_accept_ratio_sparse_matches_oracle():
             ok = ~tie & (fl == 0)
             assert ok.sum() >= B * k // 2
             assert H.close(got[ok], np.asarray(ref)[ok], H.REL, 1e-30).all(), (got[ok], np.asarray(ref)[ok])
+
+
+def _mixed_rows(rows, V, seed):
+    """Rows of every kind in turn, so that all paths of the kernel run side by side in one
+    launch: peaked, nearly flat, masked, bad, tied, empty."""
+    rng = np.random.default_rng(seed)
+    z = (3.0 * rng.standard_normal((rows, V))).astype(np.float32)
+    kind = np.arange(rows) % 7
+    z[kind == 1] *= 0.003                                         # nearly flat
+    for r in np.flatnonzero(kind == 2):
+        z[r, rng.random(V) < 0.995] = -np.inf                     # a handful of finite entries
+    for r in np.flatnonzero(kind == 3):
+        z[r, rng.integers(V)] = np.nan if r % 2 else np.inf       # bad rows
+    z[kind == 4] = np.round(z[kind == 4] * 2) / 2                 # ties
+    z[kind == 5] = -np.inf                                        # nothing finite: bad as well
+    return torch.from_numpy(z)
+
+
+@pytest.mark.parametrize("V,dtype", [(4104, torch.bfloat16), (4100, torch.float32), (4101, torch.bfloat16)])
+def test_launches_with_more_rows_than_resident_workgroups(V, dtype):
+    """A launch of more rows than the chip holds workgroups at once (1024), with rows of every
+    kind mixed: every row against the oracle, and bit for bit what launches of at most 1000
+    rows give (a row's result must not depend on what else the launch holds)."""
+    P = H.sv()
+    rows = 2 * 1024 + 517
+    z = _mixed_rows(rows, V, seed=V).to(dtype)
+    zc = z.cuda()
+    for T, K, Pp, cap in ((0.7, 20, 0.8, 64), (0.6, 0, 0.9, 256), (1.0, 0, 1.0, 64)):
+        T = _t32(T)
+        n_compact, _ = _check_supports(z, T, K, Pp, cap)
+        if K:
+            assert n_compact > rows // 2
+        whole, cut_w, flags_w = _compact(zc, T, K, Pp, cap)
+        for r0 in range(0, rows, 1000):
+            part, cut_p, flags_p = _compact(zc[r0:r0 + 1000], T, K, Pp, cap)
+            n = part.count.shape[0]
+            assert torch.equal(part.count, whole.count[r0:r0 + n])
+            assert torch.equal(part.token, whole.token[r0:r0 + n])
+            assert torch.equal(part.prob.view(torch.int64), whole.prob[r0:r0 + n].view(torch.int64))
+            assert torch.equal(part.lse.view(torch.int32), whole.lse[r0:r0 + n].view(torch.int32))
+            assert np.array_equal(cut_p.view(np.uint32), cut_w[r0:r0 + n].view(np.uint32))
+            assert np.array_equal(flags_p, flags_w[r0:r0 + n])
