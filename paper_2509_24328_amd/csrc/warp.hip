@@ -428,7 +428,7 @@ __device__ __forceinline__ void warp_row(const void* z, const int r, int V, cons
 
   // The same decisions for a list of at most 64 entries, taken by wavefront 0 alone
   // with shuffles (no barriers, no serial walk); it also writes the row's support.
-  auto settle_wave = [&](int n, float tau) {
+  auto settle_wave = [&](int n) {
     const int lane = tid;                                // wavefront 0: tid = lane
     uint64_t key = lane < n ? sh.key[lane] : 0;
     int n2 = 2;
@@ -511,7 +511,7 @@ __device__ __forceinline__ void warp_row(const void* z, const int r, int V, cons
   auto settle = [&](float tau) {
     const int n = sh.n_cand;
     if (n <= kWave && (!use_k || n >= top_k || tau == -INFINITY)) {
-      if (tid < kWave) settle_wave(n, tau);
+      if (tid < kWave) settle_wave(n);
       __syncthreads();
       return sh.settled != 0;
     }
