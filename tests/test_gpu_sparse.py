@@ -64,11 +64,19 @@ def _check_supports(z_torch, T, K, Pp, cap):
             assert keep.size > cap or not (0 < K < V) or K > 512 or few_finite, (r, T, K, Pp, keep.size, cap)
             continue
         n_compact += 1
-        assert count[r] == keep.size, (r, T, K, Pp, count[r], keep.size)
-        assert np.array_equal(token[r, :count[r]], keep), (r, T, K, Pp)
-        e = np.exp(y[keep] - y[keep].max())
+        # a kept entry whose mass exp((z - max) / T) underflows float64 has probability zero and is
+        # not listed (the stated format of the support); right at the underflow either is accepted
+        with np.errstate(under="ignore"):
+            e_all = np.exp(y[keep] - y[keep].max())
+        must = keep[e_all > 1e-300]
+        listed = token[r, :count[r]]
+        assert must.size <= count[r] <= keep.size, (r, T, K, Pp, count[r], must.size, keep.size)
+        assert np.isin(must, listed).all() and np.isin(listed, keep).all(), (r, T, K, Pp)
+        assert np.all(np.diff(listed) > 0), (r, T, K, Pp)
+        on = np.isin(keep, listed)
+        keep, e = keep[on], e_all[on]
         p_ref = e / e.sum()
-        assert np.allclose(prob[r, :count[r]], p_ref, rtol=1e-12, atol=0), (r, T, K, Pp)
+        assert np.allclose(prob[r, :count[r]], p_ref, rtol=1e-12, atol=1e-300), (r, T, K, Pp)
         lse_ref = y[keep].max() + np.log(e.sum())
         assert abs(lse[r] - lse_ref) <= 1e-6 * max(1.0, abs(lse_ref)), (r, lse[r], lse_ref)
         # untouched beyond the count
@@ -102,6 +110,26 @@ def test_compact_bad_rows_and_masked_entries():
     z[4, ::2] = float("-inf")
     _check_supports(z, 1.0, 200, 0.95, 1024)
     _check_supports(z.to(torch.bfloat16), _t32(0.7), 20, 0.8, 64)
+
+
+def test_compact_entries_whose_mass_underflows_are_not_listed():
+    """A row whose largest entry stands hundreds of units above the rest at a low temperature:
+    top-k keeps K entries, but all except the first have a mass below what float64 holds; the
+    support lists the entries of positive probability only."""
+    rng = np.random.default_rng(3)
+    z = rng.standard_normal((4, 5000)).astype(np.float32)
+    z[0, 17] = 300.0                       # (z - 300) / 0.3 < -745 for every other entry
+    z[1, 4000] = 250.0
+    z[1, 123] = 249.0                      # two entries with mass, eighteen without
+    z[2] *= 300.0                          # a wide row: some of its top 20 underflow, some do not
+    T = _t32(0.3)
+    for dtype in (torch.float32, torch.bfloat16):
+        t = torch.from_numpy(z).to(dtype)
+        n_compact, _ = _check_supports(t, T, 20, 1.0, 64)
+        assert n_compact == 4
+        sup, _, _ = _compact(t.cuda(), T, 20, 1.0, 64)
+        count = sup.count.cpu().numpy()
+        assert count[0] == 1 and count[1] == 2 and 1 <= count[2] < 20 and count[3] == 20
 
 
 def _supports_for(cfg_t, T, K, Pp, cap):
